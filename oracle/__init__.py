@@ -1,0 +1,128 @@
+"""fp64 CPU oracle for the Llama decoder-layer linear operators.
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by ``__graft_entry__.smoke``
+and by the ``cpu_baseline`` leg of ``bench.py``.  Nothing in the product
+package imports it, and it imports nothing from the product package.
+
+The arithmetic lives in ``thi_oracle.c`` (plain C, fp64, index-order loops);
+this module only builds that file with gcc and marshals numpy arrays.
+Operators follow Sec. III-B.1 (Y = X*W), Sec. III-B.4 (fp16 storage, wider
+accumulation and statistics) and Sec. III-C.1 (low-density operators wrapped
+around the linear one) of the paper.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "thi_oracle.c")
+_LIB = os.path.join(_HERE, "libthi_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile thi_oracle.c into libthi_oracle.so (gcc, OpenMP)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-o", _LIB, _SRC, "-lm"]
+        )
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        u16p = ctypes.POINTER(ctypes.c_uint16)
+        f64p = ctypes.POINTER(ctypes.c_double)
+        L = ctypes.c_long
+        lib.thi_oracle_threads.restype = ctypes.c_int
+        lib.thi_oracle_half_to_double.restype = ctypes.c_double
+        lib.thi_oracle_half_to_double.argtypes = [ctypes.c_uint16]
+        lib.thi_oracle_silu.restype = ctypes.c_double
+        lib.thi_oracle_silu.argtypes = [ctypes.c_double]
+        lib.thi_oracle_linear.argtypes = [u16p, u16p, f64p, f64p, L, L, L]
+        lib.thi_oracle_rmsnorm_qkv.argtypes = [u16p, u16p, ctypes.c_float, u16p, f64p, f64p, L, L, L]
+        lib.thi_oracle_swiglu_mlp.argtypes = [u16p, u16p, u16p, u16p, f64p, f64p, f64p, L, L, L]
+        _lib = lib
+    return _lib
+
+
+def _bits(a: np.ndarray, shape) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.float16:
+        raise TypeError("oracle inputs are float16 arrays (their bit patterns are read)")
+    if tuple(a.shape) != tuple(shape):
+        raise ValueError(f"expected shape {tuple(shape)}, got {tuple(a.shape)}")
+    return a.view(np.uint16)
+
+
+def _p16(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16))
+
+
+def _p64(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def threads() -> int:
+    """Number of OpenMP threads the C oracle will use."""
+    return int(_load().thi_oracle_threads())
+
+
+def half_to_double(bits: int) -> float:
+    return float(_load().thi_oracle_half_to_double(ctypes.c_uint16(bits)))
+
+
+def silu(t: float) -> float:
+    return float(_load().thi_oracle_silu(ctypes.c_double(t)))
+
+
+def linear(x: np.ndarray, w: np.ndarray):
+    """y[m,n] = sum_k x[m,k] w[n,k] and S[m,n] = sum_k |x[m,k] w[n,k]| in fp64."""
+    M, K = x.shape
+    N = w.shape[0]
+    xb, wb = _bits(x, (M, K)), _bits(w, (N, K))
+    y = np.empty((M, N), np.float64)
+    s = np.empty((M, N), np.float64)
+    rc = _load().thi_oracle_linear(_p16(xb), _p16(wb), _p64(y), _p64(s), M, N, K)
+    if rc:
+        raise MemoryError("thi_oracle_linear failed")
+    return y, s
+
+
+def rmsnorm_qkv(x: np.ndarray, gamma: np.ndarray, eps: float, w: np.ndarray):
+    """y = rmsnorm(x; gamma, eps) w^T and its magnitude sum, in fp64."""
+    M, K = x.shape
+    N = w.shape[0]
+    xb, gb, wb = _bits(x, (M, K)), _bits(gamma, (K,)), _bits(w, (N, K))
+    y = np.empty((M, N), np.float64)
+    s = np.empty((M, N), np.float64)
+    rc = _load().thi_oracle_rmsnorm_qkv(
+        _p16(xb), _p16(gb), ctypes.c_float(eps), _p16(wb), _p64(y), _p64(s), M, N, K
+    )
+    if rc:
+        raise MemoryError("thi_oracle_rmsnorm_qkv failed")
+    return y, s
+
+
+def swiglu_mlp(x: np.ndarray, wg: np.ndarray, wu: np.ndarray, wd: np.ndarray, return_h: bool = False):
+    """y = (silu(x wg^T) * (x wu^T)) wd^T, S = sum_j |h wd|, optionally h, in fp64."""
+    M, H = x.shape
+    I = wg.shape[0]
+    xb, gb, ub, db = _bits(x, (M, H)), _bits(wg, (I, H)), _bits(wu, (I, H)), _bits(wd, (H, I))
+    y = np.empty((M, H), np.float64)
+    s = np.empty((M, H), np.float64)
+    h = np.empty((M, I), np.float64) if return_h else None
+    rc = _load().thi_oracle_swiglu_mlp(
+        _p16(xb), _p16(gb), _p16(ub), _p16(db), _p64(y), _p64(s),
+        _p64(h) if return_h else None, M, H, I,
+    )
+    if rc:
+        raise MemoryError("thi_oracle_swiglu_mlp failed")
+    return (y, s, h) if return_h else (y, s)

@@ -1,0 +1,194 @@
+/*
+ * thi_oracle -- TEST INFRASTRUCTURE, NOT A PRODUCT PATH.
+ *
+ * A plain, slow, fp64 CPU statement of what the Llama decoder-layer linear
+ * operators compute.  Only the test-suite, the smoke check and the benchmark's
+ * "cpu_baseline" leg may call it.  It shares no code, header, table or helper
+ * with the HIP library and is never a fallback for it.
+ *
+ * What is computed, and where the paper fixes it:
+ *   - the linear operator Y = X * W                (Sec. III-B.1, the GEMM
+ *     statement before Eq. 1); weights are held [N,K] row-major here, i.e. the
+ *     paper's W transposed (the layout this library's boundary uses);
+ *   - "FP16 storage, FP32 accumulation", with normalisation statistics kept in
+ *     higher precision (Sec. III-B.4).  The oracle reads the same fp16 bit
+ *     patterns as the GPU, widens them exactly to fp64 and rounds nothing
+ *     afterwards, so it is the mathematical result up to ~K*2^-53 relative;
+ *   - low-density operators wrapped around the high-density one
+ *     (Sec. III-C.1, the "[low]-high-[low]" fusion unit): RMSNorm before the QKV
+ *     projection, SiLU(gate)*up after the gate/up projections.  The paper does
+ *     not print the RMSNorm and SwiGLU formulas; the standard Llama definitions
+ *     are used: rmsnorm(x)[k] = x[k] * gamma[k] / sqrt(mean_k x[k]^2 + eps),
+ *     silu(t) = t / (1 + exp(-t)), h = silu(gate) * up.
+ *
+ * Every function also returns S[m,n] = sum_k |a[m,k] * w[n,k]|, the magnitude
+ * against which the acceptance tolerance is scaled.
+ *
+ * Loop order is the index order of the definitions.  The only parallelism is
+ * an OpenMP "for" over output rows n (each output element is still one serial
+ * sum in index order, so results do not depend on the thread count).
+ *
+ * Parity pins (tests/test_oracle_*.py): identity / one-hot / all-ones / +-1
+ * weights, RMSNorm of constant vectors, RMSNorm scale invariance and
+ * factorisation, SiLU reference values and identities, SwiGLU with selector
+ * matrices, exact rational brute force on tiny shapes, a numpy fp64 witness on
+ * mid-size shapes, linearity, and the paper's Eq. 1-3 / Eq. 7 arithmetic for
+ * the roofline helpers used by the benchmark.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* IEEE binary16 bit pattern -> double, exact (subnormals, inf, nan kept). */
+static double half_bits_to_double(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int expo = (h >> 10) & 0x1f;
+    int frac = h & 0x3ff;
+    double v;
+    if (expo == 0) {
+        v = ldexp((double)frac, -24);            /* subnormal or zero: frac * 2^-24 */
+    } else if (expo == 31) {
+        v = frac ? NAN : INFINITY;
+    } else {
+        v = ldexp((double)(1024 + frac), expo - 25); /* (1 + frac/1024) * 2^(expo-15) */
+    }
+    return sign ? -v : v;
+}
+
+static void widen_row(const uint16_t *src, double *dst, long count)
+{
+    for (long i = 0; i < count; ++i) dst[i] = half_bits_to_double(src[i]);
+}
+
+int thi_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+double thi_oracle_half_to_double(uint16_t h) { return half_bits_to_double(h); }
+
+double thi_oracle_silu(double t) { return t / (1.0 + exp(-t)); }
+
+/*
+ * Core of every operator: a[M,K] (fp64, already widened or already an fp64
+ * intermediate) against fp16 weights w[N,K]:
+ *     y[m,n] = sum_k a[m,k] * w[n,k],   s[m,n] = sum_k |a[m,k] * w[n,k]|.
+ * s may be NULL.
+ */
+static int dense_rows(const double *a, const uint16_t *w, double *y, double *s,
+                      long M, long N, long K)
+{
+    int failed = 0;
+#pragma omp parallel
+    {
+        double *wrow = (double *)malloc((size_t)K * sizeof(double));
+        if (!wrow) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp barrier
+        if (!failed) {
+#pragma omp for schedule(static)
+            for (long n = 0; n < N; ++n) {
+                widen_row(w + n * K, wrow, K);
+                for (long m = 0; m < M; ++m) {
+                    const double *arow = a + m * K;
+                    double acc = 0.0, mag = 0.0;
+                    for (long k = 0; k < K; ++k) {
+                        double p = arow[k] * wrow[k];
+                        acc += p;
+                        mag += fabs(p);
+                    }
+                    y[m * N + n] = acc;
+                    if (s) s[m * N + n] = mag;
+                }
+            }
+        }
+        free(wrow);
+    }
+    return failed ? -1 : 0;
+}
+
+/* Sec. III-B.1: y = x * w^T with x[M,K], w[N,K] fp16 bit patterns. */
+int thi_oracle_linear(const uint16_t *x, const uint16_t *w, double *y, double *s,
+                      long M, long N, long K)
+{
+    double *a = (double *)malloc((size_t)M * K * sizeof(double));
+    if (!a) return -1;
+    widen_row(x, a, M * K);
+    int rc = dense_rows(a, w, y, s, M, N, K);
+    free(a);
+    return rc;
+}
+
+/*
+ * Sec. III-B.4 (RMSNorm statistics in higher precision) + Sec. III-C.1 (low-
+ * density operator placed in front of the linear operator):
+ *   ms_m = (1/K) sum_k x[m,k]^2,  r_m = 1/sqrt(ms_m + eps),
+ *   xhat[m,k] = x[m,k] * r_m * gamma[k]   (never rounded),
+ *   y = xhat * w^T.
+ * eps is the fp32 value the GPU entry point receives, widened exactly.
+ */
+int thi_oracle_rmsnorm_qkv(const uint16_t *x, const uint16_t *gamma, float eps,
+                           const uint16_t *w, double *y, double *s,
+                           long M, long N, long K)
+{
+    double *a = (double *)malloc((size_t)M * K * sizeof(double));
+    double *g = (double *)malloc((size_t)K * sizeof(double));
+    if (!a || !g) { free(a); free(g); return -1; }
+    widen_row(x, a, M * K);
+    widen_row(gamma, g, K);
+    for (long m = 0; m < M; ++m) {
+        double *row = a + m * K;
+        double sumsq = 0.0;
+        for (long k = 0; k < K; ++k) sumsq += row[k] * row[k];
+        double r = 1.0 / sqrt(sumsq / (double)K + (double)eps);
+        for (long k = 0; k < K; ++k) row[k] = row[k] * r * g[k];
+    }
+    int rc = dense_rows(a, w, y, s, M, N, K);
+    free(a);
+    free(g);
+    return rc;
+}
+
+/*
+ * Sec. III-C.1 (low-density operator placed behind the linear operators):
+ *   gate = x * wg^T, up = x * wu^T          x[M,H], wg/wu[I,H]
+ *   h    = silu(gate) * up                  (fp64, never rounded)
+ *   y    = h * wd^T                         wd[H,I]
+ *   s[m,n] = sum_j |h[m,j] * wd[n,j]|
+ * h_out (may be NULL) receives h[M,I] so tests can check the composition.
+ */
+int thi_oracle_swiglu_mlp(const uint16_t *x, const uint16_t *wg, const uint16_t *wu,
+                          const uint16_t *wd, double *y, double *s, double *h_out,
+                          long M, long H, long I)
+{
+    double *a = (double *)malloc((size_t)M * H * sizeof(double));
+    double *gate = (double *)malloc((size_t)M * I * sizeof(double));
+    double *up = (double *)malloc((size_t)M * I * sizeof(double));
+    int rc = -1;
+    if (a && gate && up) {
+        widen_row(x, a, M * H);
+        rc = dense_rows(a, wg, gate, NULL, M, I, H);
+        if (rc == 0) rc = dense_rows(a, wu, up, NULL, M, I, H);
+        if (rc == 0) {
+            for (long i = 0; i < M * I; ++i) gate[i] = thi_oracle_silu(gate[i]) * up[i];
+            if (h_out) memcpy(h_out, gate, (size_t)M * I * sizeof(double));
+            rc = dense_rows(gate, wd, y, s, M, H, I);
+        }
+    }
+    free(a);
+    free(gate);
+    free(up);
+    return rc;
+}

@@ -1,0 +1,26 @@
+"""thi: fp16 linear operators of a Llama decoder layer on MI355X (gfx950).
+
+Thin Python binding over the C-ABI library ``libthi.so`` (hand-written HIP
+kernels).  The binding only marshals arguments; importing this package does
+not import torch or load the library until an operator is called.
+"""
+from .binding import (  # noqa: F401
+    THI_OK,
+    ThiError,
+    Workspace,
+    library_path,
+    load_library,
+    thi_linear,
+    thi_rmsnorm_qkv,
+    thi_swiglu_mlp,
+    thi_status_string,
+    thi_version,
+    thi_workspace_bytes,
+    thi_workspace_init,
+)
+
+__all__ = [
+    "THI_OK", "ThiError", "Workspace", "library_path", "load_library", "thi_linear",
+    "thi_rmsnorm_qkv", "thi_swiglu_mlp", "thi_status_string", "thi_version",
+    "thi_workspace_bytes", "thi_workspace_init",
+]
