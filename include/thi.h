@@ -1,0 +1,137 @@
+/*
+ * thi.h -- C ABI of libthi: the fp16 linear-operator hot path of a Llama
+ * decoder layer on AMD MI355X (gfx950).
+ *
+ * Numerical contract (paper Sec. III-B.4, "FP16 operator support"): operands
+ * are stored as IEEE binary16, products are accumulated in fp32, RMSNorm
+ * statistics are kept in fp32, results are rounded to binary16
+ * (round-to-nearest-even) once, at the store.
+ *
+ * Common conventions for every entry point
+ *   - Every data pointer is a DEVICE pointer (HIP global memory) to dense,
+ *     row-major fp16 data whose innermost extent is contiguous; it must be
+ *     16-byte aligned (THI_ERR_ALIGN otherwise).  K (and H, I) must be a
+ *     multiple of 8 so that every row starts 16-byte aligned (THI_ERR_SHAPE).
+ *     M, N, K >= 1.  Weights are [N,K]: one row per output feature, i.e. the
+ *     transpose of the W in the paper's Y = X*W (Sec. III-B.1).
+ *   - Ownership: the caller owns every buffer, including `workspace`; the
+ *     library allocates nothing, frees nothing and keeps no pointer after the
+ *     call returns.  `out` must not overlap any input or the workspace.
+ *   - Workspace: at least thi_workspace_bytes(op, ...) bytes, 256-byte
+ *     aligned, and prepared ONCE after allocation with thi_workspace_init().
+ *     Every call leaves the workspace ready for the next call.  One workspace
+ *     must not be used by two calls that may run concurrently.
+ *   - Execution: work is enqueued on `hip_stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream); the call returns without
+ *     synchronising.  Results are bitwise reproducible from run to run.
+ *   - Errors: arguments are validated on the host before anything is
+ *     launched; a thi_status code is returned (never an exception, abort or
+ *     message on stderr).  THI_ERR_HIP reports a failed launch.
+ */
+#ifndef THI_H
+#define THI_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    THI_OK = 0,
+    THI_ERR_NULL = 1,      /* a required pointer is NULL */
+    THI_ERR_SHAPE = 2,     /* non-positive extent, or K/H/I not a multiple of 8 */
+    THI_ERR_ALIGN = 3,     /* a pointer is not 16-byte (workspace: 256-byte) aligned */
+    THI_ERR_WORKSPACE = 4, /* workspace smaller than thi_workspace_bytes() */
+    THI_ERR_HIP = 5        /* the HIP runtime refused a launch */
+} thi_status;
+
+typedef enum {
+    THI_OP_RMSNORM_QKV = 0,
+    THI_OP_LINEAR = 1,
+    THI_OP_SWIGLU_MLP = 2
+} thi_op;
+
+/*
+ * RMSNorm fused in front of the QKV projection: the "[low-density] -
+ * high-density" half of the paper's fusion unit (Sec. III-C.1), with the
+ * statistics in fp32 (Sec. III-B.4).
+ *
+ *   r[m]     = 1 / sqrt( (1/K) * sum_k x[m,k]^2 + eps )
+ *   out[m,n] = sum_k ( x[m,k] * r[m] * gamma[k] ) * w_qkv[n,k]
+ *
+ * x [M,K], gamma [K], w_qkv [N,K] (rows of Wq, Wk, Wv stacked; grouped-query
+ * attention only changes N), out [M,N]; all fp16 device memory.  The
+ * normalised activations are never written to HBM.
+ */
+int thi_rmsnorm_qkv(const void* x, const void* gamma, float eps, const void* w_qkv,
+                    void* out, int M, int N, int K,
+                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * The linear operator (Sec. III-B.1; decode shapes follow the small-M rule of
+ * Sec. III-B.2: broadcast X, split N):  out[m,n] = sum_k x[m,k] * w[n,k].
+ * x [M,K], w [N,K], out [M,N]; all fp16 device memory.
+ */
+int thi_linear(const void* x, const void* w, void* out, int M, int N, int K,
+               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * SwiGLU MLP with SiLU(gate)*up fused behind the gate/up projections (the
+ * "high-density - [low-density]" half of the fusion unit, Sec. III-C.1):
+ *
+ *   g[m,j]   = sum_k x[m,k] * w_gate[j,k],   u[m,j] = sum_k x[m,k] * w_up[j,k]
+ *   h[m,j]   = g / (1 + exp(-g)) * u          (fp32; stored once as fp16 in the workspace)
+ *   out[m,n] = sum_j h[m,j] * w_down[n,j]
+ *
+ * x [M,H], w_gate and w_up [I,H], w_down [H,I], out [M,H]; all fp16 device
+ * memory.  g and u are never written to HBM.
+ */
+int thi_swiglu_mlp(const void* x, const void* w_gate, const void* w_up, const void* w_down,
+                   void* out, int M, int H, int I,
+                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * First half of thi_swiglu_mlp on its own: h[m,j] = silu(x w_gate^T) * (x w_up^T),
+ * h [M,I] fp16 device memory owned by the caller (Sec. III-C.1, linear operator
+ * followed by a low-density one).  Useful when the down projection is sharded
+ * differently, and to time the layer's largest kernel in isolation.  Workspace:
+ * as for thi_swiglu_mlp with the same (M, H, I).
+ */
+int thi_swiglu_gate_up(const void* x, const void* w_gate, const void* w_up, void* h,
+                       int M, int H, int I,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Bytes of workspace the given operator needs for the given shape
+ * (op = thi_op; (M, N, K) for the first two operators, (M, H, I) for the MLP).
+ * Pure host arithmetic: touches no device.  Returns 0 for invalid arguments.
+ */
+size_t thi_workspace_bytes(int op, int M, int N_or_H, int K_or_I);
+
+/*
+ * Prepare a freshly allocated workspace (device pointer, 256-byte aligned):
+ * enqueues a small fill kernel on `hip_stream` that zeroes the arrival
+ * counters the split-K reductions use.  Needed once per allocation (and again
+ * only if a call on that workspace was aborted half-way).
+ */
+int thi_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Human-readable name of a thi_status value (static storage). */
+const char* thi_status_string(int status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int thi_version(void);
+
+/*
+ * Tuning/diagnostic hook used by the benchmark and tests: force a kernel
+ * family for subsequent calls from this process.  family: 0 = automatic
+ * (default), 1 = weight-streaming skinny kernels, 2 = MFMA GEMM kernels.
+ * Returns the previous setting.  Not needed for normal use.
+ */
+int thi_set_kernel_family(int family);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* THI_H */

@@ -1,12 +1,173 @@
-THI_OK=0
-class ThiError(RuntimeError): pass
-class Workspace: pass
-def library_path(): pass
-def load_library(): pass
-def thi_linear(*a): pass
-def thi_rmsnorm_qkv(*a): pass
-def thi_swiglu_mlp(*a): pass
-def thi_status_string(*a): pass
-def thi_version(): pass
-def thi_workspace_bytes(*a): pass
-def thi_workspace_init(*a): pass
+"""ctypes binding over libthi.so: same names as the C ABI, argument marshalling only.
+
+Tensors are torch CUDA (ROCm) tensors used purely as device memory; every
+arithmetic step runs in the HIP kernels behind the C ABI (include/thi.h).
+There is no CPU fallback: if the library is missing or was not built, calls
+raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+THI_OK = 0
+THI_OP_RMSNORM_QKV, THI_OP_LINEAR, THI_OP_SWIGLU_MLP = 0, 1, 2
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libthi.so")
+_lib = None
+
+EXPORTED_SYMBOLS = (
+    "thi_rmsnorm_qkv", "thi_linear", "thi_swiglu_mlp", "thi_swiglu_gate_up", "thi_workspace_bytes",
+    "thi_workspace_init", "thi_status_string", "thi_version", "thi_set_kernel_family",
+)
+
+
+class ThiError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {thi_status_string(status)} (status {status})")
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libthi.so (built in-tree by ``python -m paper_2605_25655_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2605_25655_amd.build` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, sz, ci, cf = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_float
+    lib.thi_rmsnorm_qkv.argtypes = [vp, vp, cf, vp, vp, ci, ci, ci, vp, sz, vp]
+    lib.thi_rmsnorm_qkv.restype = ci
+    lib.thi_linear.argtypes = [vp, vp, vp, ci, ci, ci, vp, sz, vp]
+    lib.thi_linear.restype = ci
+    lib.thi_swiglu_mlp.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, vp, sz, vp]
+    lib.thi_swiglu_mlp.restype = ci
+    lib.thi_swiglu_gate_up.argtypes = [vp, vp, vp, vp, ci, ci, ci, vp, sz, vp]
+    lib.thi_swiglu_gate_up.restype = ci
+    lib.thi_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    lib.thi_workspace_bytes.restype = sz
+    lib.thi_workspace_init.argtypes = [vp, sz, vp]
+    lib.thi_workspace_init.restype = ci
+    lib.thi_status_string.argtypes = [ci]
+    lib.thi_status_string.restype = ctypes.c_char_p
+    lib.thi_version.argtypes = []
+    lib.thi_version.restype = ci
+    lib.thi_set_kernel_family.argtypes = [ci]
+    lib.thi_set_kernel_family.restype = ci
+    _lib = lib
+    return lib
+
+
+def thi_status_string(status: int) -> str:
+    return load_library().thi_status_string(int(status)).decode()
+
+
+def thi_version() -> int:
+    return int(load_library().thi_version())
+
+
+def thi_workspace_bytes(op: int, M: int, N_or_H: int, K_or_I: int) -> int:
+    return int(load_library().thi_workspace_bytes(int(op), int(M), int(N_or_H), int(K_or_I)))
+
+
+def thi_set_kernel_family(family: int) -> int:
+    return int(load_library().thi_set_kernel_family(int(family)))
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+class Workspace:
+    """A caller-owned workspace: a torch byte tensor plus the one-time init call."""
+
+    def __init__(self, nbytes: int, device="cuda", stream=None):
+        import torch
+        self.nbytes = int(nbytes)
+        self.buffer = torch.empty(self.nbytes + 256, dtype=torch.uint8, device=device)
+        off = (-self.buffer.data_ptr()) % 256
+        self.ptr = self.buffer.data_ptr() + off
+        thi_workspace_init(self.ptr, self.nbytes, stream)
+
+    @classmethod
+    def for_ops(cls, shapes, device="cuda", stream=None):
+        """shapes: iterable of (op, M, N_or_H, K_or_I); sized for the largest."""
+        need = max(thi_workspace_bytes(*s) for s in shapes)
+        return cls(need, device=device, stream=stream)
+
+
+def _ws(workspace):
+    if isinstance(workspace, Workspace):
+        return ctypes.c_void_p(workspace.ptr), workspace.nbytes
+    ptr, nbytes = workspace
+    return ctypes.c_void_p(int(ptr)), int(nbytes)
+
+
+def thi_workspace_init(ptr: int, nbytes: int, stream=None) -> None:
+    rc = load_library().thi_workspace_init(ctypes.c_void_p(int(ptr)), int(nbytes), _stream(stream))
+    if rc != THI_OK:
+        raise ThiError(rc, "thi_workspace_init")
+
+
+def thi_rmsnorm_qkv(x, gamma, eps: float, w_qkv, out, workspace, stream=None, check: bool = True) -> int:
+    """out[M,N] = rmsnorm(x[M,K]; gamma[K], eps) @ w_qkv[N,K]^T  (fp16 device tensors)."""
+    M, K = x.shape
+    N = w_qkv.shape[0]
+    wp, wb = _ws(workspace)
+    rc = load_library().thi_rmsnorm_qkv(_ptr(x), _ptr(gamma), float(eps), _ptr(w_qkv), _ptr(out),
+                                        M, N, K, wp, wb, _stream(stream))
+    if check and rc != THI_OK:
+        raise ThiError(rc, "thi_rmsnorm_qkv")
+    return rc
+
+
+def thi_linear(x, w, out, workspace, stream=None, check: bool = True) -> int:
+    """out[M,N] = x[M,K] @ w[N,K]^T  (fp16 device tensors)."""
+    M, K = x.shape
+    N = w.shape[0]
+    wp, wb = _ws(workspace)
+    rc = load_library().thi_linear(_ptr(x), _ptr(w), _ptr(out), M, N, K, wp, wb, _stream(stream))
+    if check and rc != THI_OK:
+        raise ThiError(rc, "thi_linear")
+    return rc
+
+
+def thi_swiglu_mlp(x, w_gate, w_up, w_down, out, workspace, stream=None, check: bool = True) -> int:
+    """out[M,H] = (silu(x @ w_gate^T) * (x @ w_up^T)) @ w_down^T  (fp16 device tensors)."""
+    M, H = x.shape
+    I = w_gate.shape[0]
+    wp, wb = _ws(workspace)
+    rc = load_library().thi_swiglu_mlp(_ptr(x), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(out),
+                                       M, H, I, wp, wb, _stream(stream))
+    if check and rc != THI_OK:
+        raise ThiError(rc, "thi_swiglu_mlp")
+    return rc
+
+
+def thi_swiglu_gate_up(x, w_gate, w_up, h, workspace, stream=None, check: bool = True) -> int:
+    """h[M,I] = silu(x @ w_gate^T) * (x @ w_up^T)  (fp16 device tensors)."""
+    M, H = x.shape
+    I = w_gate.shape[0]
+    wp, wb = _ws(workspace)
+    rc = load_library().thi_swiglu_gate_up(_ptr(x), _ptr(w_gate), _ptr(w_up), _ptr(h), M, H, I, wp, wb,
+                                           _stream(stream))
+    if check and rc != THI_OK:
+        raise ThiError(rc, "thi_swiglu_gate_up")
+    return rc

@@ -1,0 +1,222 @@
+// C-ABI entry points of libthi: argument validation, workspace carving and
+// dispatch on M between the weight-streaming decode kernels and the MFMA GEMM.
+// The declarations and their contract are in include/thi.h.
+#include "../../include/thi.h"
+#include "thi_internal.h"
+
+#include <atomic>
+
+namespace {
+
+using namespace thi;
+
+constexpr int THI_VERSION = 100;          // 0.1.0
+constexpr int SKINNY_GROUP = 32;          // tokens per skinny launch
+constexpr int SKINNY_MAX_M = 64;          // automatic dispatch: M <= this -> skinny kernels
+
+std::atomic<int> g_family{0};
+
+int device_cu_count()
+{
+    // once-initialised, per-device cache of the CU count (the only state the library keeps)
+    static std::atomic<int> cache[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    int v = cache[dev].load(std::memory_order_relaxed);
+    if (v > 0) return v;
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    cache[dev].store(cus, std::memory_order_relaxed);
+    return cus;
+}
+
+inline bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Workspace {
+    unsigned* counters;
+    float* ssq;
+    float* partials;
+    uint16_t* h;
+};
+
+size_t partial_region_bytes(int M) { return skinny_partial_bytes(M < SKINNY_GROUP ? M : SKINNY_GROUP); }
+
+size_t workspace_need(int op, int M, int a, int b)
+{
+    size_t need = WS_COUNTER_BYTES + WS_SSQ_BYTES + partial_region_bytes(M);
+    if (op == THI_OP_SWIGLU_MLP) need += round_up((size_t)M * (size_t)b * 2, 256);
+    (void)a;
+    return need;
+}
+
+Workspace carve(void* base, int M)
+{
+    char* p = static_cast<char*>(base);
+    Workspace w;
+    w.counters = reinterpret_cast<unsigned*>(p);
+    w.ssq = reinterpret_cast<float*>(p + WS_COUNTER_BYTES);
+    w.partials = reinterpret_cast<float*>(p + WS_COUNTER_BYTES + WS_SSQ_BYTES);
+    w.h = reinterpret_cast<uint16_t*>(p + WS_COUNTER_BYTES + WS_SSQ_BYTES + partial_region_bytes(M));
+    return w;
+}
+
+bool use_skinny(int M)
+{
+    const int fam = g_family.load(std::memory_order_relaxed);
+    if (fam == 1) return true;
+    if (fam == 2) return false;
+    return M <= SKINNY_MAX_M;
+}
+
+// One fused projection: out[M, ldo] = epilogue( prologue(x)[M,K] * w^T ), any M.
+int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const uint16_t* w0, const uint16_t* w1,
+                   uint16_t* out, int M, int N, int K, int ldo, int epilogue, const Workspace& ws,
+                   hipStream_t stream)
+{
+    const int cus = device_cu_count();
+    if (use_skinny(M)) {
+        const int rows_per_tile = (epilogue == EPI_SWIGLU) ? SK_ROWS / 2 : SK_ROWS;
+        const int tiles = (N + rows_per_tile - 1) / rows_per_tile;
+        if (tiles > WS_MAX_COUNTERS) return THI_ERR_SHAPE;
+        for (int m0 = 0; m0 < M; m0 += SKINNY_GROUP) {
+            SkinnyArgs a;
+            a.x = x + (size_t)m0 * K;
+            a.gamma = gamma;
+            a.w0 = w0;
+            a.w1 = w1;
+            a.out = out + (size_t)m0 * ldo;
+            a.partials = ws.partials;
+            a.ssq = ws.ssq;
+            a.counters = ws.counters;
+            a.M = (M - m0 < SKINNY_GROUP) ? M - m0 : SKINNY_GROUP;
+            a.N = N;
+            a.K = K;
+            a.ldo = ldo;
+            a.tiles = tiles;
+            a.kchunks = (K + SK_KC - 1) / SK_KC;
+            a.eps = eps;
+            if (launch_skinny(a, epilogue, cus, stream) != hipSuccess) return THI_ERR_HIP;
+        }
+        return THI_OK;
+    }
+    GemmArgs g;
+    g.x = x;
+    g.gamma = gamma;
+    g.w0 = w0;
+    g.w1 = w1;
+    g.out = out;
+    g.M = M;
+    g.N = N;
+    g.K = K;
+    g.ldo = ldo;
+    g.eps = eps;
+    return launch_gemm(g, epilogue, cus, stream) == hipSuccess ? THI_OK : THI_ERR_HIP;
+}
+
+int check_common(int M, int N, int K, const void* workspace, size_t workspace_bytes, size_t need)
+{
+    if (M < 1 || N < 1 || K < 1 || (K & 7)) return THI_ERR_SHAPE;
+    if (!workspace) return THI_ERR_NULL;
+    if (misaligned(workspace, 256)) return THI_ERR_ALIGN;
+    if (workspace_bytes < need) return THI_ERR_WORKSPACE;
+    return THI_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int thi_rmsnorm_qkv(const void* x, const void* gamma, float eps, const void* w_qkv, void* out,
+                    int M, int N, int K, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!x || !gamma || !w_qkv || !out) return THI_ERR_NULL;
+    int rc = check_common(M, N, K, workspace, workspace_bytes, workspace_need(THI_OP_RMSNORM_QKV, M, N, K));
+    if (rc != THI_OK) return rc;
+    if (misaligned(x, 16) || misaligned(gamma, 16) || misaligned(w_qkv, 16) || misaligned(out, 16)) return THI_ERR_ALIGN;
+    Workspace ws = carve(workspace, M);
+    return run_projection((const uint16_t*)x, (const uint16_t*)gamma, eps, (const uint16_t*)w_qkv, nullptr,
+                          (uint16_t*)out, M, N, K, N, EPI_RMSNORM, ws, (hipStream_t)hip_stream);
+}
+
+int thi_linear(const void* x, const void* w, void* out, int M, int N, int K,
+               void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!x || !w || !out) return THI_ERR_NULL;
+    int rc = check_common(M, N, K, workspace, workspace_bytes, workspace_need(THI_OP_LINEAR, M, N, K));
+    if (rc != THI_OK) return rc;
+    if (misaligned(x, 16) || misaligned(w, 16) || misaligned(out, 16)) return THI_ERR_ALIGN;
+    Workspace ws = carve(workspace, M);
+    return run_projection((const uint16_t*)x, nullptr, 0.f, (const uint16_t*)w, nullptr, (uint16_t*)out,
+                          M, N, K, N, EPI_PLAIN, ws, (hipStream_t)hip_stream);
+}
+
+int thi_swiglu_mlp(const void* x, const void* w_gate, const void* w_up, const void* w_down, void* out,
+                   int M, int H, int I, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!x || !w_gate || !w_up || !w_down || !out) return THI_ERR_NULL;
+    if (I < 1 || (I & 7)) return THI_ERR_SHAPE;
+    int rc = check_common(M, H, H, workspace, workspace_bytes, workspace_need(THI_OP_SWIGLU_MLP, M, H, I));
+    if (rc != THI_OK) return rc;
+    if (misaligned(x, 16) || misaligned(w_gate, 16) || misaligned(w_up, 16) || misaligned(w_down, 16) ||
+        misaligned(out, 16))
+        return THI_ERR_ALIGN;
+    Workspace ws = carve(workspace, M);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    rc = run_projection((const uint16_t*)x, nullptr, 0.f, (const uint16_t*)w_gate, (const uint16_t*)w_up, ws.h,
+                        M, I, H, I, EPI_SWIGLU, ws, stream);
+    if (rc != THI_OK) return rc;
+    return run_projection(ws.h, nullptr, 0.f, (const uint16_t*)w_down, nullptr, (uint16_t*)out, M, H, I, H,
+                          EPI_PLAIN, ws, stream);
+}
+
+int thi_swiglu_gate_up(const void* x, const void* w_gate, const void* w_up, void* h, int M, int H, int I,
+                       void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!x || !w_gate || !w_up || !h) return THI_ERR_NULL;
+    if (I < 1 || (I & 7)) return THI_ERR_SHAPE;
+    int rc = check_common(M, H, H, workspace, workspace_bytes, workspace_need(THI_OP_SWIGLU_MLP, M, H, I));
+    if (rc != THI_OK) return rc;
+    if (misaligned(x, 16) || misaligned(w_gate, 16) || misaligned(w_up, 16) || misaligned(h, 16)) return THI_ERR_ALIGN;
+    Workspace ws = carve(workspace, M);
+    return run_projection((const uint16_t*)x, nullptr, 0.f, (const uint16_t*)w_gate, (const uint16_t*)w_up,
+                          (uint16_t*)h, M, I, H, I, EPI_SWIGLU, ws, (hipStream_t)hip_stream);
+}
+
+size_t thi_workspace_bytes(int op, int M, int N_or_H, int K_or_I)
+{
+    if (op < THI_OP_RMSNORM_QKV || op > THI_OP_SWIGLU_MLP) return 0;
+    if (M < 1 || N_or_H < 1 || K_or_I < 1) return 0;
+    return workspace_need(op, M, N_or_H, K_or_I);
+}
+
+int thi_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!workspace) return THI_ERR_NULL;
+    if (misaligned(workspace, 256)) return THI_ERR_ALIGN;
+    if (workspace_bytes < WS_COUNTER_BYTES) return THI_ERR_WORKSPACE;
+    return launch_fill_zero(workspace, WS_COUNTER_BYTES, (hipStream_t)hip_stream) == hipSuccess ? THI_OK : THI_ERR_HIP;
+}
+
+const char* thi_status_string(int status)
+{
+    switch (status) {
+    case THI_OK: return "THI_OK";
+    case THI_ERR_NULL: return "THI_ERR_NULL: a required pointer is NULL";
+    case THI_ERR_SHAPE: return "THI_ERR_SHAPE: extents must be >= 1 and K, H, I multiples of 8";
+    case THI_ERR_ALIGN: return "THI_ERR_ALIGN: pointers must be 16-byte aligned (workspace 256-byte)";
+    case THI_ERR_WORKSPACE: return "THI_ERR_WORKSPACE: workspace smaller than thi_workspace_bytes()";
+    case THI_ERR_HIP: return "THI_ERR_HIP: kernel launch failed";
+    default: return "THI_ERR_UNKNOWN";
+    }
+}
+
+int thi_version(void) { return THI_VERSION; }
+
+int thi_set_kernel_family(int family)
+{
+    if (family < 0 || family > 2) family = 0;
+    return g_family.exchange(family);
+}
+
+}  // extern "C"

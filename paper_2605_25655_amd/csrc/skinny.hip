@@ -1,0 +1,340 @@
+// Weight-streaming skinny GEMM for decode (M <= 32 tokens per launch) on gfx950.
+//
+// The paper's small-M rule (Sec. III-B.2: broadcast X, split the work along N)
+// is kept in spirit -- every workgroup sees the whole activation slice it needs
+// and owns a slice of the weights -- but the partition is made for an HBM-bound
+// GPU: the weight matrix is cut into work units of 128 rows x 256 k, the units
+// are numbered tile-major and dealt out in equal contiguous shares to a fixed
+// number of workgroups ("stream-K"), so every CU streams the same number of
+// bytes whatever N and K are.  A tile whose k range is shared by several
+// workgroups is finished by whichever of them arrives last; it adds the partial
+// tiles in workgroup order, so the result does not depend on arrival order.
+//
+// Per unit and wave: 16 weight rows x 256 k are fetched with fully coalesced
+// 16-byte loads (16 lanes cover 256 contiguous bytes of one row), passed through
+// a wave-private LDS buffer to reach the MFMA operand layout, and multiplied
+// against the activation slice that the workgroup staged in LDS already in
+// operand order.  Products are fp16 x fp16 accumulated in fp32 by
+// v_mfma_f32_16x16x32_f16 (Sec. III-B.4: fp16 storage, fp32 accumulation).
+//
+// Fused low-density operators (Sec. III-C.1):
+//   RMSNorm  : x*gamma is formed while the slice is staged, sum x^2 is
+//              accumulated on the side, the accumulator is scaled by
+//              1/sqrt(mean + eps) before the store  (rmsnorm(x) W^T =
+//              r * ((x*gamma) W^T));
+//   SwiGLU   : a tile holds gate rows and the matching up rows so that one lane
+//              ends up with g and u of the same (token, j); silu(g)*u is applied
+//              to the fp32 accumulators before the fp16 store.
+#include "thi_internal.h"
+
+namespace thi {
+
+namespace {
+
+constexpr int WT_STRIDE = 17;                  // 16-byte units per transposition row (256 B + 16 B pad)
+constexpr int WT_UNITS = 16 * WT_STRIDE;       // per wave
+
+__device__ __forceinline__ uintx4 ld_stream(const uint16_t* p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const uintx4*>(p));
+}
+__device__ __forceinline__ uintx4 ld_cached(const uint16_t* p) {
+    return *reinterpret_cast<const uintx4*>(p);
+}
+
+__device__ __forceinline__ float silu_mul(float g, float u) {
+    return g / (1.0f + __expf(-g)) * u;
+}
+
+__device__ __forceinline__ uint16_t to_half_bits(float v) {
+    _Float16 h = (_Float16)v;   // round-to-nearest-even
+    return __builtin_bit_cast(uint16_t, h);
+}
+
+// Owner (workgroup index) of work unit u when U units are dealt to G workgroups
+// as [w*U/G, (w+1)*U/G).
+__device__ __forceinline__ long unit_owner(long u, long U, long G) { return ((u + 1) * G - 1) / U; }
+
+template <int MT>
+struct UnitRegs {
+    uintx4 w[8];      // 16 rows x 256 k of weights: [phase*4 + jj]
+    uintx4 x[MT];     // activation pieces this thread stages
+    uintx4 g;         // gamma piece (RMSNorm only)
+};
+
+template <int MT, int EPI>
+__global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
+{
+    __shared__ uintx4 xs[2][8 * MT * 64];          // staged activations, MFMA B-operand order
+    __shared__ uintx4 wt[SK_WAVES][WT_UNITS];      // wave-private transposition buffers
+    __shared__ float s_red[SK_WAVES][32];
+    __shared__ float s_ssq[32];
+    __shared__ unsigned s_flag;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wv = tid >> 6;
+    const long G = gridDim.x;
+    const long wg = blockIdx.x;
+    const long kch = a.kchunks;
+    const long U = (long)a.tiles * kch;
+    const long u_begin = wg * U / G;
+    const long u_end = (wg + 1) * U / G;
+    if (u_begin >= u_end) return;
+    const int first_tile = (int)(u_begin / kch);
+
+    const int K = a.K;
+    // staging role: this wave stages k-step `wv` (32 k) of each unit; lane -> (token c, k-group g)
+    const int st_c = lane >> 2, st_g = lane & 3;
+    // weight-load role: load jj of a phase covers MFMA rows 4*jj + lane/16, piece lane%16
+    const int ld_i = lane >> 4, ld_p = lane & 15;
+
+    // ---- issue the global loads of one unit --------------------------------
+    auto issue = [&](long u, UnitRegs<MT>& r) {
+        const int t = (int)(u / kch);
+        const int k0 = (int)(u - (long)t * kch) * SK_KC;
+        const bool full = (k0 + SK_KC <= K);
+        // weights
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const uint16_t* base;
+            if (EPI == EPI_SWIGLU) {
+                int j = t * 64 + wv * 8 + 2 * jj + (ld_i & 1);
+                j = j < a.N ? j : a.N - 1;
+                base = ((ld_i >> 1) ? a.w1 : a.w0) + (size_t)j * K;
+            } else {
+                int n = t * SK_ROWS + wv * 16 + 4 * jj + ld_i;
+                n = n < a.N ? n : a.N - 1;
+                base = a.w0 + (size_t)n * K;
+            }
+#pragma unroll
+            for (int ph = 0; ph < 2; ++ph) {
+                const int k = k0 + ph * 128 + ld_p * 8;
+                if (full || k < K) r.w[ph * 4 + jj] = ld_stream(base + k);
+                else r.w[ph * 4 + jj] = uintx4{0u, 0u, 0u, 0u};
+            }
+        }
+        // activations (+ gamma)
+        const int kx = k0 + wv * 32 + st_g * 8;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const int m = mt * 16 + st_c;
+            if (m < a.M && kx < K) r.x[mt] = ld_cached(a.x + (size_t)m * K + kx);
+            else r.x[mt] = uintx4{0u, 0u, 0u, 0u};
+        }
+        if (EPI == EPI_RMSNORM) {
+            if (kx < K) r.g = ld_cached(a.gamma + kx);
+            else r.g = uintx4{0u, 0u, 0u, 0u};
+        }
+    };
+
+    floatx4 acc[MT];
+    float ssq[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) { acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f}; ssq[mt] = 0.f; }
+
+    UnitRegs<MT> nxt;
+    issue(u_begin, nxt);
+    long run_start = u_begin;        // first unit of the current tile run
+    int buf = 0;
+
+    for (long u = u_begin; u < u_end; ++u) {
+        UnitRegs<MT> cur = nxt;
+        if (u + 1 < u_end) issue(u + 1, nxt);
+
+        const int t = (int)(u / kch);
+        // ---- stage activations (apply gamma, accumulate sum of squares) -----
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            uintx4 xv = cur.x[mt];
+            if (EPI == EPI_RMSNORM) {
+                half8 xh = __builtin_bit_cast(half8, xv);
+                half8 gh = __builtin_bit_cast(half8, cur.g);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { float f = (float)xh[e]; ssq[mt] = __builtin_fmaf(f, f, ssq[mt]); }
+                half8 p = xh * gh;       // one rounding: the fp16 product of two fp16 values
+                xv = __builtin_bit_cast(uintx4, p);
+            }
+            xs[buf][(wv * MT + mt) * 64 + st_g * 16 + st_c] = xv;
+        }
+        __syncthreads();
+
+        // ---- weights: two phases of 16 rows x 128 k through the wave buffer --
+#pragma unroll
+        for (int ph = 0; ph < 2; ++ph) {
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+                wt[wv][(4 * jj + ld_i) * WT_STRIDE + ld_p] = cur.w[ph * 4 + jj];
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                half8 wa = __builtin_bit_cast(half8, wt[wv][(lane & 15) * WT_STRIDE + 4 * s + (lane >> 4)]);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    half8 xb = __builtin_bit_cast(half8, xs[buf][((ph * 4 + s) * MT + mt) * 64 + lane]);
+                    acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wa, xb, acc[mt], 0, 0, 0);
+                }
+            }
+        }
+        buf ^= 1;
+
+        // ---- end of this workgroup's run over tile t? ------------------------
+        const bool run_ends = (u + 1 == u_end) || ((u + 1) % kch == 0);
+        if (!run_ends) continue;
+
+        const long tile_begin = (long)t * kch;
+        const bool whole = (run_start == tile_begin) && (u + 1 == tile_begin + kch);
+
+        // sum of squares of this run, per token (fixed order: lanes, then waves)
+        if (EPI == EPI_RMSNORM) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                float v = ssq[mt];
+                v += __shfl_xor(v, 1);
+                v += __shfl_xor(v, 2);
+                if (st_g == 0) s_red[wv][mt * 16 + st_c] = v;
+            }
+            if (MT == 1 && st_g == 0) s_red[wv][16 + st_c] = 0.f;
+            __syncthreads();
+            if (tid < 32) {
+                float v = 0.f;
+#pragma unroll
+                for (int i = 0; i < SK_WAVES; ++i) v += s_red[i][tid];
+                s_ssq[tid] = v;
+            }
+            __syncthreads();
+        }
+
+        bool finish = whole;
+        long w_first = wg, w_last = wg;
+        if (!whole) {
+            const int slot = (t == first_tile) ? 0 : 1;
+            float* ps = a.partials + ((size_t)wg * 2 + slot) * (SK_WAVES * MT * 4 * 64);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    __hip_atomic_store(ps + ((wv * MT + mt) * 4 + i) * 64 + lane, acc[mt][i],
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (EPI == EPI_RMSNORM && tid < 32)
+                __hip_atomic_store(a.ssq + ((size_t)wg * 2 + slot) * 32 + tid, s_ssq[tid],
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __threadfence();
+            __syncthreads();
+            w_first = unit_owner(tile_begin, U, G);
+            w_last = unit_owner(tile_begin + kch - 1, U, G);
+            if (tid == 0) {
+                unsigned old = __hip_atomic_fetch_add(a.counters + t, 1u, __ATOMIC_ACQ_REL,
+                                                      __HIP_MEMORY_SCOPE_AGENT);
+                s_flag = old;
+            }
+            __syncthreads();
+            finish = (s_flag == (unsigned)(w_last - w_first));
+            if (finish) {
+                __threadfence();
+                if (tid == 0)
+                    __hip_atomic_store(a.counters + t, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+                float sq = 0.f;
+                for (long wc = w_first; wc <= w_last; ++wc) {
+                    const int cslot = ((int)((wc * U / G) / kch) == t) ? 0 : 1;
+                    const float* cs = a.partials + ((size_t)wc * 2 + cslot) * (SK_WAVES * MT * 4 * 64);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            acc[mt][i] += __hip_atomic_load(cs + ((wv * MT + mt) * 4 + i) * 64 + lane,
+                                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (EPI == EPI_RMSNORM && tid < 32)
+                        sq += __hip_atomic_load(a.ssq + ((size_t)wc * 2 + cslot) * 32 + tid,
+                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                if (EPI == EPI_RMSNORM) {
+                    __syncthreads();
+                    if (tid < 32) s_ssq[tid] = sq;
+                    __syncthreads();
+                }
+            }
+        }
+
+        if (finish) {
+            const int q = lane >> 4, c = lane & 15;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const int m = mt * 16 + c;
+                if (m >= a.M) continue;
+                if (EPI == EPI_SWIGLU) {
+                    const int j = t * 64 + wv * 8 + 2 * q;
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+                        if (j + i < a.N)
+                            a.out[(size_t)m * a.ldo + j + i] = to_half_bits(silu_mul(acc[mt][i], acc[mt][i + 2]));
+                } else {
+                    float scale = 1.0f;
+                    if (EPI == EPI_RMSNORM) scale = 1.0f / __builtin_sqrtf(s_ssq[m] / (float)K + a.eps);
+                    const int n = t * SK_ROWS + wv * 16 + 4 * q;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (n + i < a.N)
+                            a.out[(size_t)m * a.ldo + n + i] = to_half_bits(acc[mt][i] * scale);
+                }
+            }
+        }
+
+        // start the next run
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) { acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f}; ssq[mt] = 0.f; }
+        run_start = u + 1;
+        // s_red / s_ssq / s_flag are rewritten only after the next __syncthreads of the unit loop
+    }
+}
+
+template <int MT>
+hipError_t launch_mt(const SkinnyArgs& a, int epilogue, int grid, hipStream_t stream)
+{
+    dim3 g(grid), b(SK_THREADS);
+    switch (epilogue) {
+    case EPI_PLAIN: hipLaunchKernelGGL((skinny_streamk<MT, EPI_PLAIN>), g, b, 0, stream, a); break;
+    case EPI_RMSNORM: hipLaunchKernelGGL((skinny_streamk<MT, EPI_RMSNORM>), g, b, 0, stream, a); break;
+    default: hipLaunchKernelGGL((skinny_streamk<MT, EPI_SWIGLU>), g, b, 0, stream, a); break;
+    }
+    return hipGetLastError();
+}
+
+__global__ void fill_zero_kernel(uint32_t* p, size_t words)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < words; i += stride) p[i] = 0u;
+}
+
+}  // namespace
+
+size_t skinny_partial_bytes(int M)
+{
+    const int mt = (M <= 16) ? 1 : 2;
+    return (size_t)SK_MAX_GRID * 2 * (SK_WAVES * mt * 4 * 64) * sizeof(float);
+}
+
+hipError_t launch_skinny(const SkinnyArgs& a, int epilogue, int num_cus, hipStream_t stream)
+{
+    const long U = (long)a.tiles * a.kchunks;
+    long grid = 2L * num_cus;
+    if (grid > SK_MAX_GRID) grid = SK_MAX_GRID;
+    if (grid > U) grid = U;
+    if (a.M <= 16) return launch_mt<1>(a, epilogue, (int)grid, stream);
+    return launch_mt<2>(a, epilogue, (int)grid, stream);
+}
+
+hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream)
+{
+    const size_t words = bytes / 4;
+    int blocks = (int)((words + 255) / 256);
+    if (blocks > 1024) blocks = 1024;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, stream, (uint32_t*)ptr, words);
+    return hipGetLastError();
+}
+
+}  // namespace thi

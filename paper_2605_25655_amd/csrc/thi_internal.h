@@ -1,0 +1,65 @@
+// Internal declarations shared by the translation units of libthi (never installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace thi {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+
+enum Epilogue { EPI_PLAIN = 0, EPI_RMSNORM = 1, EPI_SWIGLU = 2 };
+
+// ---- workspace layout (bytes from the workspace base) ----------------------
+// [0, 64 KiB)            : arrival counters (uint32), zero between calls
+// [64 KiB, 64 KiB + 1 MiB): per-workgroup partial sums of squares for RMSNorm
+// [.., + partial bytes)  : per-workgroup partial accumulator tiles (fp32)
+// [.., + M*I*2)          : h = silu(gate)*up of the MLP (fp16)
+constexpr size_t WS_COUNTER_BYTES = 64 * 1024;
+constexpr size_t WS_SSQ_BYTES = 1024 * 1024;
+constexpr int WS_MAX_COUNTERS = (int)(WS_COUNTER_BYTES / 4);
+
+// ---- skinny (decode) kernel geometry ---------------------------------------
+constexpr int SK_THREADS = 512;     // 8 waves
+constexpr int SK_WAVES = 8;
+constexpr int SK_ROWS = 128;        // virtual weight rows per tile (16 per wave)
+constexpr int SK_KC = 256;          // k extent of one work unit
+constexpr int SK_MAX_GRID = 2048;   // upper bound on workgroups (sizes the partial buffers)
+
+struct SkinnyArgs {
+    const uint16_t* x;       // [M,K] activations
+    const uint16_t* gamma;   // [K] (RMSNorm) or nullptr
+    const uint16_t* w0;      // weights [N,K]  (gate weights for SwiGLU)
+    const uint16_t* w1;      // up weights [I,K] for SwiGLU, else nullptr
+    uint16_t* out;           // [M,ldo]
+    float* partials;         // [grid][2][slot]
+    float* ssq;              // [grid][2][32]
+    unsigned* counters;      // [tiles]
+    int M, N, K, ldo;        // N = physical rows of w0 (I for SwiGLU); ldo = out row length
+    int tiles, kchunks;      // tiles of SK_ROWS virtual rows; chunks of SK_KC along K
+    float eps;
+};
+
+size_t skinny_partial_bytes(int M);
+hipError_t launch_skinny(const SkinnyArgs& a, int epilogue, int num_cus, hipStream_t stream);
+
+// ---- GEMM (prefill) kernel ---------------------------------------------------
+struct GemmArgs {
+    const uint16_t* x;       // [M,K]
+    const uint16_t* gamma;   // [K] or nullptr
+    const uint16_t* w0;      // [N,K]
+    const uint16_t* w1;      // up weights for SwiGLU
+    uint16_t* out;           // [M,ldo]
+    int M, N, K, ldo;        // N = physical rows of w0
+    float eps;
+};
+hipError_t launch_gemm(const GemmArgs& a, int epilogue, int num_cus, hipStream_t stream);
+
+hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream);
+
+}  // namespace thi

@@ -1,0 +1,81 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports what
+include/thi.h declares, and rejects bad arguments on the host before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2605_25655_amd import binding
+    if not os.path.exists(binding.library_path()):
+        from paper_2605_25655_amd import build
+        build.build(verbose=False)
+    return binding.load_library()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "thi.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(thi_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    from paper_2605_25655_amd import binding
+    names = declared_symbols()
+    assert set(names) == set(binding.EXPORTED_SYMBOLS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_version_and_status_strings(lib):
+    assert lib.thi_version() >= 100
+    assert lib.thi_status_string(0) == b"THI_OK"
+    for s in range(1, 6):
+        assert lib.thi_status_string(s).startswith(b"THI_ERR_")
+    assert lib.thi_status_string(77) == b"THI_ERR_UNKNOWN"
+
+
+def test_workspace_bytes_is_pure_and_monotone(lib):
+    f = lib.thi_workspace_bytes
+    assert f(9, 1, 8, 8) == 0 and f(0, 0, 8, 8) == 0 and f(1, 1, -1, 8) == 0
+    a = f(1, 1, 4096, 4096)
+    assert a > 0 and a == f(1, 1, 4096, 4096)
+    assert f(1, 32, 4096, 4096) >= a
+    mlp1, mlp2 = f(2, 32, 4096, 11008), f(2, 2048, 4096, 11008)
+    assert mlp2 - mlp1 >= (2048 - 32) * 11008 * 2      # h buffer grows with M*I
+
+
+def test_argument_errors_return_codes_without_launching(lib):
+    buf = ctypes.create_string_buffer(1 << 12)
+    base = ctypes.addressof(buf)
+    p = ctypes.c_void_p((base + 255) // 256 * 256)
+    odd = ctypes.c_void_p(p.value + 2)
+    big = 1 << 40
+    null = ctypes.c_void_p(0)
+    # NULL pointers
+    assert lib.thi_linear(null, p, p, 1, 8, 8, p, big, null) == 1
+    assert lib.thi_rmsnorm_qkv(p, null, 1e-6, p, p, 1, 8, 8, p, big, null) == 1
+    assert lib.thi_swiglu_mlp(p, p, null, p, p, 1, 8, 8, p, big, null) == 1
+    assert lib.thi_linear(p, p, p, 1, 8, 8, null, big, null) == 1
+    # shapes
+    assert lib.thi_linear(p, p, p, 0, 8, 8, p, big, null) == 2
+    assert lib.thi_linear(p, p, p, 1, 8, 12, p, big, null) == 2
+    assert lib.thi_swiglu_mlp(p, p, p, p, p, 1, 8, 20, p, big, null) == 2
+    assert lib.thi_swiglu_mlp(p, p, p, p, p, 1, 4, 8, p, big, null) == 2
+    # alignment
+    assert lib.thi_linear(odd, p, p, 1, 8, 8, p, big, null) == 3
+    assert lib.thi_linear(p, p, p, 1, 8, 8, odd, big, null) == 3
+    # workspace too small
+    assert lib.thi_linear(p, p, p, 1, 8, 8, p, 1024, null) == 4
+    assert lib.thi_workspace_init(null, 1 << 20, null) == 1
+    assert lib.thi_workspace_init(p, 16, null) == 4
+
+
+def test_kernel_family_switch_roundtrip(lib):
+    prev = lib.thi_set_kernel_family(1)
+    assert lib.thi_set_kernel_family(prev) == 1

@@ -1,0 +1,192 @@
+"""GPU parity: the HIP library (through the C ABI) against the fp64 oracle,
+element by element, on the same seeded inputs.
+
+Bar: |gpu - y| <= 4e-3 * S per output element and identical per-row argmax
+(tests/parity.py).  Closed-form cases are compared bit-exactly."""
+import numpy as np
+import pytest
+
+from paper_2605_25655_amd import synth
+from tests.gpu_common import Runner, say, to_dev, to_host
+from tests.parity import check
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def thi():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2605_25655_amd as thi
+    thi.load_library()                       # fails loudly if libthi.so is missing
+    thi.thi_set_kernel_family(0)
+    return thi
+
+
+def f16(a):
+    return np.asarray(a, dtype=np.float16)
+
+
+# ------------------------------------------------------------ closed forms
+@pytest.mark.parametrize("M", [1, 5, 16, 32, 40, 128, 200])
+def test_identity_weights_bit_exact(thi, oracle_mod, M):
+    K = 256
+    say(f"[case] identity M={M} K={K}")
+    rng = np.random.default_rng(M)
+    x = f16(rng.standard_normal((M, K)))
+    x[0, 0] = np.float16(6.0e-8)       # subnormal
+    x[0, 1] = np.float16(-5.9e-6)      # subnormal
+    x[M - 1, 5] = np.float16(65504.0)  # max finite
+    r = Runner(M, K, K, K)
+    got = to_host(r.linear(to_dev(x), to_dev(np.eye(K, dtype=np.float16))))
+    assert np.array_equal(got.view(np.uint16), x.view(np.uint16))
+
+
+@pytest.mark.parametrize("M", [1, 32, 130])
+def test_one_hot_gather_bit_exact(thi, M):
+    N, K = 300, 512
+    say(f"[case] one-hot M={M} N={N} K={K}")
+    rng = np.random.default_rng(7)
+    perm = rng.integers(0, K, size=N)
+    w = np.zeros((N, K), np.float16)
+    w[np.arange(N), perm] = 1
+    x = f16(rng.standard_normal((M, K)))
+    r = Runner(M, K, K, N)
+    got = to_host(r.linear(to_dev(x), to_dev(w)))
+    assert np.array_equal(got.view(np.uint16), x[:, perm].view(np.uint16))
+
+
+def test_subnormal_weights_are_not_flushed(thi):
+    K, N, M = 256, 128, 3
+    w = np.full((N, K), 2.0 ** -20, np.float16)       # subnormal fp16
+    x = np.full((M, K), 16.0, np.float16)
+    r = Runner(M, K, K, N)
+    got = to_host(r.linear(to_dev(x), to_dev(w)))
+    assert np.all(got.astype(np.float64) == K * 16.0 * 2.0 ** -20)
+
+
+def test_rmsnorm_constant_rows(thi):
+    K, M = 512, 4
+    x = np.ones((M, K), np.float16)
+    x[1] = -1
+    x[2] = 0.5
+    x[3, ::2] = -1
+    r = Runner(M, K, K, K)
+    got = to_host(r.rmsnorm_qkv(to_dev(x), to_dev(np.ones(K, np.float16)), 1e-6, to_dev(np.eye(K, dtype=np.float16))))
+    exp = (x.astype(np.float64) / np.sqrt((x.astype(np.float64) ** 2).mean(1, keepdims=True) + 1e-6)).astype(np.float16)
+    assert np.array_equal(got, exp)
+
+
+# ----------------------------------------------------------- odd shape grid
+ODD = [
+    (1, 1, 8), (1, 7, 8), (2, 130, 24), (3, 129, 264), (1, 1000, 1376), (4, 255, 520), (8, 257, 4096),
+    (16, 384, 776), (17, 100, 512), (31, 513, 1032), (32, 640, 2056), (33, 200, 264), (64, 128, 512),
+    (65, 130, 136), (100, 300, 520), (127, 129, 72), (256, 256, 256), (300, 200, 1096),
+]
+
+
+@pytest.mark.parametrize("M,N,K", ODD)
+def test_linear_and_rmsnorm_odd_shapes(thi, oracle_mod, M, N, K):
+    say(f"[case] odd linear/rmsnorm M={M} N={N} K={K}")
+    x, w, g = synth.random_problem(1000 + M * 7 + N * 3 + K, M, N, K)
+    r = Runner(M, K, K, N)
+    xd, wd, gd = to_dev(x), to_dev(w), to_dev(g)
+    y, s = oracle_mod.linear(x, w)
+    check(to_host(r.linear(xd, wd)), y, s, f"linear {M}x{N}x{K}", argmax=False)
+    y, s = oracle_mod.rmsnorm_qkv(x, g, 1e-6, w)
+    check(to_host(r.rmsnorm_qkv(xd, gd, 1e-6, wd)), y, s, f"rmsnorm_qkv {M}x{N}x{K}", argmax=False)
+
+
+@pytest.mark.parametrize("M,H,I", [(1, 64, 8), (2, 72, 136), (5, 512, 1376), (16, 256, 200), (32, 136, 1032),
+                                   (33, 128, 264), (70, 264, 520), (129, 512, 328), (256, 128, 128)])
+def test_swiglu_odd_shapes(thi, oracle_mod, M, H, I):
+    say(f"[case] odd swiglu M={M} H={H} I={I}")
+    rng = np.random.Generator(np.random.Philox(key=5000 + M + H + I))
+    x = f16(rng.standard_normal((M, H)))
+    wg, wu = f16(rng.standard_normal((I, H)) * 0.05), f16(rng.standard_normal((I, H)) * 0.05)
+    wd = f16(rng.standard_normal((H, I)) * 0.05)
+    r = Runner(M, H, I, H)
+    got = to_host(r.swiglu_mlp(to_dev(x), to_dev(wg), to_dev(wu), to_dev(wd)))
+    y, s = oracle_mod.swiglu_mlp(x, wg, wu, wd)
+    check(got, y, s, f"swiglu {M}x{H}x{I}", argmax=False)
+
+
+@pytest.mark.parametrize("family", [1, 2])
+@pytest.mark.parametrize("M", [1, 20, 48, 160])
+def test_both_kernel_families_cover_every_m(thi, oracle_mod, family, M):
+    say(f"[case] family={family} M={M}")
+    N, K, I = 272, 520, 328
+    x, w, g = synth.random_problem(77 + M, M, N, K)
+    rng = np.random.Generator(np.random.Philox(key=78 + M))
+    wg, wu = f16(rng.standard_normal((I, K)) * 0.05), f16(rng.standard_normal((I, K)) * 0.05)
+    wd = f16(rng.standard_normal((K, I)) * 0.05)
+    r = Runner(M, K, I, N)
+    prev = thi.thi_set_kernel_family(family)
+    try:
+        a = to_host(r.linear(to_dev(x), to_dev(w)))
+        b = to_host(r.rmsnorm_qkv(to_dev(x), to_dev(g), 1e-6, to_dev(w)))
+        c = to_host(r.swiglu_mlp(to_dev(x), to_dev(wg), to_dev(wu), to_dev(wd)))
+    finally:
+        thi.thi_set_kernel_family(prev)
+    y, s = oracle_mod.linear(x, w)
+    check(a, y, s, "linear", argmax=False)
+    y, s = oracle_mod.rmsnorm_qkv(x, g, 1e-6, w)
+    check(b, y, s, "rmsnorm", argmax=False)
+    y, s = oracle_mod.swiglu_mlp(x, wg, wu, wd)
+    check(c, y, s, "swiglu", argmax=False)
+
+
+# ------------------------------------------------- the five layer configs
+def _layer_case(thi, oracle_mod, cfg_id, rows_limit=32):
+    cfg = synth.CONFIGS[cfg_id]
+    say(f"[case] config {cfg_id} {cfg.name}: generating")
+    L = synth.make_layer(cfg)
+    dev = {k: to_dev(L[k]) for k in ("w_qkv", "w_o", "w_gate", "w_up", "w_down", "gamma")}
+    for M in cfg.all_m:
+        say(f"[case] config {cfg_id} {cfg.name} M={M}")
+        acts = L["acts"][M]
+        r = Runner(M, cfg.hidden, cfg.inter, cfg.n_qkv)
+        q = r.rmsnorm_qkv(to_dev(acts["x_qkv"]), dev["gamma"], L["eps"], dev["w_qkv"])
+        o = r.linear(to_dev(acts["a_o"]), dev["w_o"])
+        y = r.swiglu_mlp(to_dev(acts["x_mlp"]), dev["w_gate"], dev["w_up"], dev["w_down"])
+        # bitwise reproducibility: run everything again and compare bits
+        q2 = r.rmsnorm_qkv(to_dev(acts["x_qkv"]), dev["gamma"], L["eps"], dev["w_qkv"])
+        o2 = r.linear(to_dev(acts["a_o"]), dev["w_o"])
+        y2 = r.swiglu_mlp(to_dev(acts["x_mlp"]), dev["w_gate"], dev["w_up"], dev["w_down"])
+        q, o, y, q2, o2, y2 = (to_host(t) for t in (q, o, y, q2, o2, y2))
+        assert np.array_equal(q.view(np.uint16), q2.view(np.uint16))
+        assert np.array_equal(o.view(np.uint16), o2.view(np.uint16))
+        assert np.array_equal(y.view(np.uint16), y2.view(np.uint16))
+        rows = synth.sample_rows(20260525 + cfg_id, M, rows_limit)   # all rows when M <= 32
+        ref, s = oracle_mod.rmsnorm_qkv(acts["x_qkv"][rows], L["gamma"], L["eps"], L["w_qkv"])
+        info = check(q[rows], ref, s, f"cfg{cfg_id} M={M} rmsnorm_qkv")
+        say(f"    rmsnorm_qkv worst |err|/S = {info['worst_rel']:.2e}")
+        ref, s = oracle_mod.linear(acts["a_o"][rows], L["w_o"])
+        info = check(o[rows], ref, s, f"cfg{cfg_id} M={M} o_proj")
+        say(f"    o_proj      worst |err|/S = {info['worst_rel']:.2e}")
+        ref, s = oracle_mod.swiglu_mlp(acts["x_mlp"][rows], L["w_gate"], L["w_up"], L["w_down"])
+        info = check(y[rows], ref, s, f"cfg{cfg_id} M={M} swiglu_mlp")
+        say(f"    swiglu_mlp  worst |err|/S = {info['worst_rel']:.2e}")
+        # every output row must have been written (no NaN sentinel left)
+        assert np.isfinite(q.astype(np.float32)).all() and np.isfinite(o.astype(np.float32)).all()
+        assert np.isfinite(y.astype(np.float32)).all()
+
+
+def test_config1_tiny(thi, oracle_mod):
+    _layer_case(thi, oracle_mod, 1)
+
+
+def test_config2_llama7b_decode(thi, oracle_mod):
+    _layer_case(thi, oracle_mod, 2)
+
+
+def test_config3_llama13b(thi, oracle_mod):
+    _layer_case(thi, oracle_mod, 3)
+
+
+def test_config4_llama30b(thi, oracle_mod):
+    _layer_case(thi, oracle_mod, 4)
+
+
+def test_config5_llama70b_gqa(thi, oracle_mod):
+    _layer_case(thi, oracle_mod, 5)
