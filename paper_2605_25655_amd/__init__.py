@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     load_library,
     thi_linear,
     thi_rmsnorm_qkv,
+    thi_set_kernel_family,
     thi_swiglu_gate_up,
     thi_swiglu_mlp,
     thi_status_string,
@@ -22,6 +23,6 @@ from .binding import (  # noqa: F401
 
 __all__ = [
     "THI_OK", "ThiError", "Workspace", "library_path", "load_library", "thi_linear",
-    "thi_rmsnorm_qkv", "thi_swiglu_gate_up", "thi_swiglu_mlp", "thi_status_string", "thi_version",
+    "thi_rmsnorm_qkv", "thi_set_kernel_family", "thi_swiglu_gate_up", "thi_swiglu_mlp", "thi_status_string", "thi_version",
     "thi_workspace_bytes", "thi_workspace_init",
 ]

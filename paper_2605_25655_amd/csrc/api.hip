@@ -78,7 +78,7 @@ int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const ui
     if (use_skinny(M)) {
         const int rows_per_tile = (epilogue == EPI_SWIGLU) ? SK_ROWS / 2 : SK_ROWS;
         const int tiles = (N + rows_per_tile - 1) / rows_per_tile;
-        if (tiles > WS_MAX_COUNTERS) return THI_ERR_SHAPE;
+        if (tiles > WS_MAX_COUNTERS || (long)tiles * ((K + SK_KC - 1) / SK_KC) > (1L << 30)) return THI_ERR_SHAPE;
         for (int m0 = 0; m0 < M; m0 += SKINNY_GROUP) {
             SkinnyArgs a;
             a.x = x + (size_t)m0 * K;

@@ -50,9 +50,16 @@ __device__ __forceinline__ uint16_t to_half_bits(float v) {
     return __builtin_bit_cast(uint16_t, h);
 }
 
-// Owner (workgroup index) of work unit u when U units are dealt to G workgroups
-// as [w*U/G, (w+1)*U/G).
-__device__ __forceinline__ long unit_owner(long u, long U, long G) { return ((u + 1) * G - 1) / U; }
+// U work units are dealt to G workgroups in contiguous shares: the first `rem`
+// workgroups take q+1 units, the others q (q = U / G, rem = U % G).
+struct Deal {
+    int q, rem;
+    __device__ __forceinline__ int begin(int w) const { return w * q + (w < rem ? w : rem); }
+    __device__ __forceinline__ int owner(int u) const {
+        const int edge = rem * (q + 1);
+        return u < edge ? u / (q + 1) : rem + (u - edge) / q;
+    }
+};
 
 template <int MT>
 struct UnitRegs {
@@ -73,14 +80,15 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wv = tid >> 6;
-    const long G = gridDim.x;
-    const long wg = blockIdx.x;
-    const long kch = a.kchunks;
-    const long U = (long)a.tiles * kch;
-    const long u_begin = wg * U / G;
-    const long u_end = (wg + 1) * U / G;
+    const int G = gridDim.x;
+    const int wg = blockIdx.x;
+    const int kch = a.kchunks;
+    const int U = a.tiles * kch;
+    const Deal deal{U / G, U % G};
+    const int u_begin = deal.begin(wg);
+    const int u_end = deal.begin(wg + 1);
     if (u_begin >= u_end) return;
-    const int first_tile = (int)(u_begin / kch);
+    const int first_tile = u_begin / kch;
 
     const int K = a.K;
     // staging role: this wave stages k-step `wv` (32 k) of each unit; lane -> (token c, k-group g)
@@ -89,9 +97,9 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
     const int ld_i = lane >> 4, ld_p = lane & 15;
 
     // ---- issue the global loads of one unit --------------------------------
-    auto issue = [&](long u, UnitRegs<MT>& r) {
-        const int t = (int)(u / kch);
-        const int k0 = (int)(u - (long)t * kch) * SK_KC;
+    auto issue = [&](int u, UnitRegs<MT>& r) {
+        const int t = u / kch;
+        const int k0 = (u - t * kch) * SK_KC;
         const bool full = (k0 + SK_KC <= K);
         // weights
 #pragma unroll
@@ -134,14 +142,14 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
 
     UnitRegs<MT> nxt;
     issue(u_begin, nxt);
-    long run_start = u_begin;        // first unit of the current tile run
+    int run_start = u_begin;         // first unit of the current tile run
     int buf = 0;
 
-    for (long u = u_begin; u < u_end; ++u) {
+    for (int u = u_begin; u < u_end; ++u) {
         UnitRegs<MT> cur = nxt;
         if (u + 1 < u_end) issue(u + 1, nxt);
 
-        const int t = (int)(u / kch);
+        const int t = u / kch;
         // ---- stage activations (apply gamma, accumulate sum of squares) -----
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
@@ -182,7 +190,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
         const bool run_ends = (u + 1 == u_end) || ((u + 1) % kch == 0);
         if (!run_ends) continue;
 
-        const long tile_begin = (long)t * kch;
+        const int tile_begin = t * kch;
         const bool whole = (run_start == tile_begin) && (u + 1 == tile_begin + kch);
 
         // sum of squares of this run, per token (fixed order: lanes, then waves)
@@ -206,7 +214,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
         }
 
         bool finish = whole;
-        long w_first = wg, w_last = wg;
+        int w_first = wg, w_last = wg;
         if (!whole) {
             const int slot = (t == first_tile) ? 0 : 1;
             float* ps = a.partials + ((size_t)wg * 2 + slot) * (SK_WAVES * MT * 4 * 64);
@@ -219,26 +227,27 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
             if (EPI == EPI_RMSNORM && tid < 32)
                 __hip_atomic_store(a.ssq + ((size_t)wg * 2 + slot) * 32 + tid, s_ssq[tid],
                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __threadfence();
+            // The partial tile went out with device-coherent (write-through) stores; once every
+            // wave has seen its stores acknowledged, one thread announces the arrival.
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             __syncthreads();
-            w_first = unit_owner(tile_begin, U, G);
-            w_last = unit_owner(tile_begin + kch - 1, U, G);
+            w_first = deal.owner(tile_begin);
+            w_last = deal.owner(tile_begin + kch - 1);
             if (tid == 0) {
-                unsigned old = __hip_atomic_fetch_add(a.counters + t, 1u, __ATOMIC_ACQ_REL,
+                unsigned old = __hip_atomic_fetch_add(a.counters + t, 1u, __ATOMIC_RELAXED,
                                                       __HIP_MEMORY_SCOPE_AGENT);
                 s_flag = old;
             }
             __syncthreads();
             finish = (s_flag == (unsigned)(w_last - w_first));
             if (finish) {
-                __threadfence();
                 if (tid == 0)
                     __hip_atomic_store(a.counters + t, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
                 float sq = 0.f;
-                for (long wc = w_first; wc <= w_last; ++wc) {
-                    const int cslot = ((int)((wc * U / G) / kch) == t) ? 0 : 1;
+                for (int wc = w_first; wc <= w_last; ++wc) {
+                    const int cslot = (deal.begin(wc) / kch == t) ? 0 : 1;
                     const float* cs = a.partials + ((size_t)wc * 2 + cslot) * (SK_WAVES * MT * 4 * 64);
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
