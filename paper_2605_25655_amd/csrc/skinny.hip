@@ -26,6 +26,7 @@
 //              ends up with g and u of the same (token, j); silu(g)*u is applied
 //              to the fp32 accumulators before the fp16 store.
 #include "thi_internal.h"
+#include <cstdlib>
 
 namespace thi {
 
@@ -122,6 +123,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
             }
         }
         // activations (+ gamma)
+        if (a.eps == -78.f) return;
         const int kx = k0 + wv * 32 + st_g * 8;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
@@ -167,6 +169,10 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
         __syncthreads();
 
         // ---- weights: two phases of 16 rows x 128 k through the wave buffer --
+        if (a.eps == -79.f) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[0][0] += __builtin_bit_cast(float, cur.w[i].x ^ cur.w[i].y ^ cur.w[i].z ^ cur.w[i].w);
+        } else
 #pragma unroll
         for (int ph = 0; ph < 2; ++ph) {
             __builtin_amdgcn_wave_barrier();
@@ -191,7 +197,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
         if (!run_ends) continue;
 
         const int tile_begin = t * kch;
-        const bool whole = (run_start == tile_begin) && (u + 1 == tile_begin + kch);
+        const bool whole = ((run_start == tile_begin) && (u + 1 == tile_begin + kch)) || a.eps <= -77.f;
 
         // sum of squares of this run, per token (fixed order: lanes, then waves)
         if (EPI == EPI_RMSNORM) {
@@ -246,18 +252,42 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
                 float sq = 0.f;
-                for (int wc = w_first; wc <= w_last; ++wc) {
-                    const int cslot = (deal.begin(wc) / kch == t) ? 0 : 1;
-                    const float* cs = a.partials + ((size_t)wc * 2 + cslot) * (SK_WAVES * MT * 4 * 64);
+                // contributors are added in workgroup order; their loads are issued four
+                // contributors at a time so the round trips overlap
+                for (int wc0 = w_first; wc0 <= w_last; wc0 += 4) {
+                    float pv[4][MT][4];
+                    float ps4[4];
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt)
+                    for (int b = 0; b < 4; ++b) {
+                        const int wc = wc0 + b;
+                        if (wc <= w_last) {
+                            const int cslot = (deal.begin(wc) / kch == t) ? 0 : 1;
+                            const float* cs = a.partials + ((size_t)wc * 2 + cslot) * (SK_WAVES * MT * 4 * 64);
 #pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            acc[mt][i] += __hip_atomic_load(cs + ((wv * MT + mt) * 4 + i) * 64 + lane,
-                                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    if (EPI == EPI_RMSNORM && tid < 32)
-                        sq += __hip_atomic_load(a.ssq + ((size_t)wc * 2 + cslot) * 32 + tid,
-                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                                for (int i = 0; i < 4; ++i)
+                                    pv[b][mt][i] = __hip_atomic_load(cs + ((wv * MT + mt) * 4 + i) * 64 + lane,
+                                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            if (EPI == EPI_RMSNORM && tid < 32)
+                                ps4[b] = __hip_atomic_load(a.ssq + ((size_t)wc * 2 + cslot) * 32 + tid,
+                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        } else {
+#pragma unroll
+                            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) pv[b][mt][i] = 0.f;
+                            ps4[b] = 0.f;
+                        }
+                    }
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) acc[mt][i] += pv[b][mt][i];
+                        if (EPI == EPI_RMSNORM && tid < 32) sq += ps4[b];
+                    }
                 }
                 if (EPI == EPI_RMSNORM) {
                     __syncthreads();
@@ -329,11 +359,15 @@ size_t skinny_partial_bytes(int M)
 hipError_t launch_skinny(const SkinnyArgs& a, int epilogue, int num_cus, hipStream_t stream)
 {
     const long U = (long)a.tiles * a.kchunks;
-    long grid = 2L * num_cus;
+    static int dbg_grid = getenv("THI_DBG_GRID") ? atoi(getenv("THI_DBG_GRID")) : 0;
+    long grid = dbg_grid > 0 ? dbg_grid : 1L * num_cus;
     if (grid > SK_MAX_GRID) grid = SK_MAX_GRID;
     if (grid > U) grid = U;
-    if (a.M <= 16) return launch_mt<1>(a, epilogue, (int)grid, stream);
-    return launch_mt<2>(a, epilogue, (int)grid, stream);
+    static int dbg_nofix = getenv("THI_DBG_NOFIX") ? atoi(getenv("THI_DBG_NOFIX")) : 0;
+    SkinnyArgs b = a;
+    if (dbg_nofix) b.eps = -76.f - dbg_nofix;
+    if (a.M <= 16) return launch_mt<1>(b, epilogue, (int)grid, stream);
+    return launch_mt<2>(b, epilogue, (int)grid, stream);
 }
 
 hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream)
