@@ -40,7 +40,12 @@ struct Workspace {
     uint16_t* h;
 };
 
-size_t partial_region_bytes(int M) { return skinny_partial_bytes(M < SKINNY_GROUP ? M : SKINNY_GROUP); }
+// one region serves both kernel families (either may be forced for any M)
+size_t partial_region_bytes(int M)
+{
+    const size_t sk = skinny_partial_bytes(M < SKINNY_GROUP ? M : SKINNY_GROUP), ge = gemm_partial_bytes();
+    return sk > ge ? sk : ge;
+}
 
 size_t workspace_need(int op, int M, int a, int b)
 {
@@ -100,12 +105,20 @@ int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const ui
         }
         return THI_OK;
     }
+    {
+        const long tn = (N + 63) / 64, tm = (M + 127) / 128;     // upper bound on tiles of any configuration
+        if (tn * tm > WS_MAX_COUNTERS) return THI_ERR_SHAPE;
+    }
     GemmArgs g;
     g.x = x;
     g.gamma = gamma;
     g.w0 = w0;
     g.w1 = w1;
     g.out = out;
+    g.partials = ws.partials;
+    g.ssq = ws.ssq;
+    g.counters = ws.counters;
+    g.tiles = 0;
     g.M = M;
     g.N = N;
     g.K = K;

@@ -17,6 +17,14 @@
 // store -- and, for SwiGLU, with g and u of the same (token, j) in registers of
 // the same lane (a tile interleaves 8 gate rows with the 8 matching up rows).
 //
+// Scheduling is stream-K: the (tile, k-step) units are dealt in equal contiguous
+// shares to a fixed number of workgroups (one or two per CU), so no CU idles on
+// a ragged last round of tiles and small problems still fill the chip.  Tiles
+// whose k range is shared leave fp32 partial tiles in the workspace; a second,
+// chip-wide kernel adds them in workgroup order (bitwise reproducible) and
+// applies the epilogue.  Only the ragged remainder is cut this way; tiles that
+// fill whole rounds of the grid are computed and finished in one piece.
+//
 // Workgroups are numbered so that the eight XCDs (one L2 each; hardware deals
 // consecutive workgroup ids round-robin to them) each walk a contiguous range
 // of tiles, token-tile fastest, so the weight panel an XCD streams is shared by
@@ -52,10 +60,102 @@ __device__ __forceinline__ void dma16(const uint16_t* src, uintx4* lds_base)
                                      (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
 }
 
+// U work units dealt to G workers in contiguous shares: the first `rem` take q+1, the others q.
+struct Deal {
+    int q, rem;
+    __device__ __forceinline__ int begin(int w) const { return w * q + (w < rem ? w : rem); }
+    __device__ __forceinline__ int owner(int u) const {
+        const int edge = rem * (q + 1);
+        return u < edge ? u / (q + 1) : rem + (u - edge) / q;
+    }
+};
+
+// Epilogue for one 32x32 accumulator fragment: lane (lr = token within the fragment, lg = which
+// half of the rows) holds, per register quad aa, four consecutive n of one token.
+template <int BN, int BM, int WN, int WM, int EPI>
+__device__ __forceinline__ void store_fragment(const GemmArgs& a, int tile_n, int tile_m, int wn, int wm, int tn,
+                                               int tm, int lr, int lg, const floatx16& f, float scale)
+{
+    constexpr int JPT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
+    const int m = tile_m * BM + wm * (BM / WM) + tm * 32 + lr;
+    if (m >= a.M) return;
+    if (EPI == EPI_SWIGLU) {
+#pragma unroll
+        for (int aa = 0; aa < 4; aa += 2) {
+            const int v = wn * (BN / WN) + tn * 32 + 8 * aa;
+            const int j = tile_n * JPT + (v >> 4) * 8 + 4 * lg;
+            half4 hv;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const float g = f[4 * aa + c], uu = f[4 * (aa + 1) + c];
+                hv[c] = (_Float16)(g / (1.0f + __expf(-g)) * uu);
+            }
+            if (j + 3 < a.N && (a.ldo & 3) == 0) {
+                *reinterpret_cast<half4*>(a.out + (size_t)m * a.ldo + j) = hv;
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (j + c < a.N) a.out[(size_t)m * a.ldo + j + c] = __builtin_bit_cast(uint16_t, hv[c]);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int aa = 0; aa < 4; ++aa) {
+            const int n = tile_n * BN + wn * (BN / WN) + tn * 32 + 8 * aa + 4 * lg;
+            if (n + 3 < a.N && (a.ldo & 3) == 0) {
+                half4 hv;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) hv[c] = (_Float16)(f[4 * aa + c] * scale);
+                *reinterpret_cast<half4*>(a.out + (size_t)m * a.ldo + n) = hv;
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (n + c < a.N) a.out[(size_t)m * a.ldo + n + c] = to_half_bits(f[4 * aa + c] * scale);
+            }
+        }
+    }
+}
+
+// Second pass of the stream-K schedule: one workgroup per (shared tile, accumulator fragment) adds the
+// partial fragments of the tile's contributors in workgroup order and applies the epilogue.  The
+// thread <-> element mapping is the main kernel's, so the partials are read back as they were written.
+template <int BN, int BM, int WN, int WM, int EPI>
+__global__ __launch_bounds__(64 * WN * WM) void gemm_fixup(GemmArgs a, int tiles_m, int ktiles, int sk_tiles, int G)
+{
+    constexpr int THREADS = 64 * WN * WM;
+    constexpr int TN = BN / WN / 32, TM = BM / WM / 32;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid / 64;
+    const int wn = wv % WN, wm = wv / WN, lr = lane & 31, lg = lane >> 5;
+    const int t = blockIdx.x / (TN * TM), frag = blockIdx.x % (TN * TM);
+    const int tn = frag / TM, tm = frag % TM;
+    const int U = sk_tiles * ktiles;
+    const Deal deal{U / G, U % G};
+    const int w_first = deal.owner(t * ktiles), w_last = deal.owner(t * ktiles + ktiles - 1);
+    floatx16 f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) f[e] = 0.f;
+    float sq = 0.f;
+    const int ml = wm * (BM / WM) + tm * 32 + lr;
+    for (int wc = w_first; wc <= w_last; ++wc) {
+        const int cslot = (deal.begin(wc) / ktiles == t) ? 0 : 1;
+        const floatx4* cs = reinterpret_cast<const floatx4*>(a.partials + ((size_t)wc * 2 + cslot) * (BN * BM));
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const floatx4 v = cs[(frag * 4 + q) * THREADS + tid];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) f[4 * q + c] += v[c];
+        }
+        if (EPI == EPI_RMSNORM) sq += a.ssq[((size_t)wc * 2 + cslot) * BM + ml];
+    }
+    float scale = 1.0f;
+    if (EPI == EPI_RMSNORM) scale = 1.0f / __builtin_sqrtf(sq / (float)a.K + a.eps);
+    store_fragment<BN, BM, WN, WM, EPI>(a, t / tiles_m, t % tiles_m, wn, wm, tn, tm, lr, lg, f, scale);
+}
+
 // BN x BM output tile, WN x WM waves; wave tile (BN/WN) x (BM/WM) built from 32x32 MFMA tiles.
 // KTAIL: K is not a multiple of 64 (pieces past K are zero-filled; operands then go through VGPRs).
 template <int BN, int BM, int WN, int WM, int EPI, bool KTAIL>
-__global__ __launch_bounds__(64 * WN * WM) void gemm_tile(GemmArgs a, int tiles_n, int tiles_m)
+__global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int tiles_m, int ktiles, int sk_tiles)
 {
     constexpr int NWAVES = WN * WM;
     constexpr int THREADS = 64 * NWAVES;
@@ -75,276 +175,307 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_tile(GemmArgs a, int tiles_
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid / 64;
     const int wn = wv % WN, wm = wv / WN;
-
-    // XCD-aware numbering of the tiles
-    int tile_id;
-    {
-        const int nwg = gridDim.x, bid = blockIdx.x;
-        const int per = nwg / 8, rem = nwg % 8, xcd = bid % 8, local = bid / 8;
-        tile_id = xcd * per + (xcd < rem ? xcd : rem) + local;
-    }
-    const int tile_m = tile_id % tiles_m, tile_n = tile_id / tiles_m;
-    (void)tiles_n;
+    const int lr = lane & 31, lg = lane >> 5;
     const int K = a.K;
-    const int ktiles = (K + GK - 1) / GK;
 
-    // Staging role.  A wave instruction covers 8 tile rows x 8 pieces = 64 consecutive LDS units; lane L
-    // owns unit L of it, i.e. row (8*block + L/8) and physical slot L%8, which holds logical piece
-    // slot ^ f(row).  Pass i of this thread handles 8-row block (wv*PASS + i).
-    const uint16_t* wsrc[WPASS];
-    const uint16_t* xsrc[XPASS];
-    int wunit[WPASS], xunit[XPASS];
+    // XCD-aware worker numbering: consecutive workers (neighbouring tiles) share an XCD
+    const int G = gridDim.x;
+    int worker;
+    {
+        const int bid = blockIdx.x, per = G / 8, rem = G % 8, xcd = bid % 8, local = bid / 8;
+        worker = xcd * per + (xcd < rem ? xcd : rem) + local;
+    }
+    // The first sk_tiles tiles are cut into k-steps and dealt stream-K; the others are taken whole,
+    // round-robin.  The shared tiles come first so that their hand-over overlaps the whole tiles.
+    const int U = sk_tiles * ktiles;
+    const Deal deal{U / G, U % G};
+    const int u_begin = deal.begin(worker), u_end = deal.begin(worker + 1);
+    const int first_tile = u_begin / ktiles;
+    int t_whole = sk_tiles + worker;
+
+    // DMA staging role.  A wave instruction covers 8 tile rows x 8 pieces = 64 consecutive LDS units;
+    // lane L owns unit L of it: row (8*block + L/8), physical slot L%8, logical piece slot ^ f(row).
+    // VGPR staging role (operands that are transformed or zero-padded): logical piece tid%8 of rows
+    // tid/8 + ROWS_PER_PASS*i, so that one gamma piece serves all rows of a thread.
     const int slot = lane & 7;
-#pragma unroll
-    for (int i = 0; i < WPASS; ++i) {
-        const int v = (wv * WPASS + i) * 8 + (lane >> 3);
-        const int piece = slot ^ (((v >> 1) & 7) ^ ((v & 1) << 2));
-        wunit[i] = v * GPIECES + slot;
-        if (EPI == EPI_SWIGLU) {
-            int j = tile_n * JPT + (v >> 4) * 8 + (v & 7);
-            j = j < a.N ? j : a.N - 1;
-            wsrc[i] = (((v >> 3) & 1) ? a.w1 : a.w0) + (size_t)j * K + piece * 8;
-        } else {
-            int n = tile_n * BN + v;
-            n = n < a.N ? n : a.N - 1;
-            wsrc[i] = a.w0 + (size_t)n * K + piece * 8;
-        }
-    }
-    int xpiece[XPASS];
-#pragma unroll
-    for (int i = 0; i < XPASS; ++i) {
-        const int v = (wv * XPASS + i) * 8 + (lane >> 3);
-        xpiece[i] = slot ^ (((v >> 1) & 7) ^ ((v & 1) << 2));
-        xunit[i] = v * GPIECES + slot;
-        int m = tile_m * BM + v;
-        m = m < a.M ? m : a.M - 1;           // rows past M are loaded from a valid row and never stored
-        xsrc[i] = a.x + (size_t)m * K + xpiece[i] * 8;
-    }
-
-    uintx4 wreg[W_DMA ? 1 : WPASS], xreg[X_DMA ? 1 : XPASS], greg[X_DMA ? 1 : XPASS];
-    float ssq[XPASS];
-#pragma unroll
-    for (int i = 0; i < XPASS; ++i) ssq[i] = 0.f;
+    const int vp = tid & 7, vr0 = tid >> 3;
     const uintx4 zero4 = {0u, 0u, 0u, 0u};
 
-    // K is a multiple of 8, so a 16-byte piece is entirely inside or outside [0,K); with KTAIL the
-    // pieces past K are read from k = 0 (valid memory) and replaced by zeros.
-    auto load_w = [&](int kt, int buf) {          // DMA: lands in stage buf; else: into wreg
+    for (int u = u_begin;;) {
+        int t, kb, ke;
+        if (u < u_end) {
+            t = u / ktiles;
+            kb = u - t * ktiles;
+            ke = (ktiles - kb < u_end - u) ? ktiles : kb + (u_end - u);
+            u += ke - kb;
+        } else if (t_whole < a.tiles) {
+            t = t_whole;
+            kb = 0;
+            ke = ktiles;
+            t_whole += G;
+        } else {
+            break;
+        }
+        const int tile_m = t % tiles_m, tile_n = t / tiles_m;
+
+        const uint16_t* wsrc[WPASS];
+        const uint16_t* xsrc[XPASS];
 #pragma unroll
         for (int i = 0; i < WPASS; ++i) {
-            if (W_DMA) {
-                dma16(wsrc[i] + kt * GK, smem + buf * STAGE + (wv * WPASS + i) * 64);
+            const int v = W_DMA ? (wv * WPASS + i) * 8 + (lane >> 3) : vr0 + ROWS_PER_PASS * i;
+            const int piece = W_DMA ? slot ^ (((v >> 1) & 7) ^ ((v & 1) << 2)) : vp;
+            if (EPI == EPI_SWIGLU) {
+                int j = tile_n * JPT + (v >> 4) * 8 + (v & 7);
+                j = j < a.N ? j : a.N - 1;
+                wsrc[i] = (((v >> 3) & 1) ? a.w1 : a.w0) + (size_t)j * K + piece * 8;
             } else {
-                const int piece = (wunit[i] & 7) ^ ((((wunit[i] >> 3) >> 1) & 7) ^ (((wunit[i] >> 3) & 1) << 2));
-                const bool kok = kt * GK + piece * 8 < K;
-                uintx4 v = *reinterpret_cast<const uintx4*>(wsrc[i] + (kok ? kt * GK : -piece * 8));
-                wreg[i] = kok ? v : zero4;
+                int n = tile_n * BN + v;
+                n = n < a.N ? n : a.N - 1;
+                wsrc[i] = a.w0 + (size_t)n * K + piece * 8;
             }
         }
-    };
-    auto load_x = [&](int kt, int buf) {
 #pragma unroll
         for (int i = 0; i < XPASS; ++i) {
-            if (X_DMA) {
-                dma16(xsrc[i] + kt * GK, smem + buf * STAGE + BN * GPIECES + (wv * XPASS + i) * 64);
-            } else {
-                const bool kok = !KTAIL || kt * GK + xpiece[i] * 8 < K;
-                uintx4 v = *reinterpret_cast<const uintx4*>(xsrc[i] + (kok ? kt * GK : -xpiece[i] * 8));
-                xreg[i] = kok ? v : zero4;
-                if (EPI == EPI_RMSNORM) {
-                    uintx4 g = *reinterpret_cast<const uintx4*>(a.gamma + (kok ? kt * GK + xpiece[i] * 8 : 0));
-                    greg[i] = g;
+            const int v = X_DMA ? (wv * XPASS + i) * 8 + (lane >> 3) : vr0 + ROWS_PER_PASS * i;
+            const int piece = X_DMA ? slot ^ (((v >> 1) & 7) ^ ((v & 1) << 2)) : vp;
+            int m = tile_m * BM + v;
+            m = m < a.M ? m : a.M - 1;       // rows past M are loaded from a valid row and never stored
+            xsrc[i] = a.x + (size_t)m * K + piece * 8;
+        }
+
+        uintx4 wreg[W_DMA ? 1 : WPASS], xreg[X_DMA ? 1 : XPASS], greg;
+        float ssq[XPASS];
+#pragma unroll
+        for (int i = 0; i < XPASS; ++i) ssq[i] = 0.f;
+
+        // K is a multiple of 8, so a 16-byte piece is entirely inside or outside [0,K); with KTAIL the
+        // pieces past K are read from the row start (valid memory) and replaced by zeros.
+        auto load_w = [&](int kt, int buf) {      // DMA: lands in stage buf; else: into wreg
+#pragma unroll
+            for (int i = 0; i < WPASS; ++i) {
+                if (W_DMA) {
+                    dma16(wsrc[i] + kt * GK, smem + buf * STAGE + (wv * WPASS + i) * 64);
+                } else {
+                    const bool kok = kt * GK + vp * 8 < K;
+                    uintx4 v = *reinterpret_cast<const uintx4*>(wsrc[i] + (kok ? kt * GK : -vp * 8));
+                    wreg[i] = kok ? v : zero4;
                 }
             }
-        }
-    };
-    auto store_w = [&](int buf) {                 // VGPR path only
-        if (!W_DMA) {
-#pragma unroll
-            for (int i = 0; i < WPASS; ++i) smem[buf * STAGE + wunit[i]] = wreg[i];
-        }
-    };
-    auto store_x = [&](int buf) {
-        if (!X_DMA) {
+        };
+        auto load_x = [&](int kt, int buf) {
 #pragma unroll
             for (int i = 0; i < XPASS; ++i) {
-                uintx4 xv = xreg[i];
-                if (EPI == EPI_RMSNORM) {
-                    half8 xh = __builtin_bit_cast(half8, xv);
-                    half8 gh = __builtin_bit_cast(half8, greg[i]);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) { float f = (float)xh[e]; ssq[i] = __builtin_fmaf(f, f, ssq[i]); }
-                    half8 pr = xh * gh;
-                    xv = __builtin_bit_cast(uintx4, pr);
+                if (X_DMA) {
+                    dma16(xsrc[i] + kt * GK, smem + buf * STAGE + BN * GPIECES + (wv * XPASS + i) * 64);
+                } else {
+                    const bool kok = !KTAIL || kt * GK + vp * 8 < K;
+                    uintx4 v = *reinterpret_cast<const uintx4*>(xsrc[i] + (kok ? kt * GK : -vp * 8));
+                    xreg[i] = kok ? v : zero4;
                 }
-                smem[buf * STAGE + BN * GPIECES + xunit[i]] = xv;
             }
-        }
-    };
+            if (!X_DMA && EPI == EPI_RMSNORM) {
+                const bool kok = !KTAIL || kt * GK + vp * 8 < K;
+                greg = *reinterpret_cast<const uintx4*>(a.gamma + (kok ? kt * GK + vp * 8 : 0));
+            }
+        };
+        auto store_w = [&](int buf) {             // VGPR path only
+            if (!W_DMA) {
+#pragma unroll
+                for (int i = 0; i < WPASS; ++i) smem[buf * STAGE + swz(vr0 + ROWS_PER_PASS * i, vp)] = wreg[i];
+            }
+        };
+        auto store_x = [&](int buf) {
+            if (!X_DMA) {
+#pragma unroll
+                for (int i = 0; i < XPASS; ++i) {
+                    uintx4 xv = xreg[i];
+                    if (EPI == EPI_RMSNORM) {
+                        half8 xh = __builtin_bit_cast(half8, xv);
+                        half8 gh = __builtin_bit_cast(half8, greg);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) { float f = (float)xh[e]; ssq[i] = __builtin_fmaf(f, f, ssq[i]); }
+                        half8 pr = xh * gh;      // one rounding: the fp16 product of two fp16 values
+                        xv = __builtin_bit_cast(uintx4, pr);
+                    }
+                    smem[buf * STAGE + BN * GPIECES + swz(vr0 + ROWS_PER_PASS * i, vp)] = xv;
+                }
+            }
+        };
 
-    floatx16 acc[TN][TM];
+        floatx16 acc[TN][TM];
 #pragma unroll
-    for (int i = 0; i < TN; ++i)
+        for (int i = 0; i < TN; ++i)
 #pragma unroll
-        for (int j = 0; j < TM; ++j)
+            for (int j = 0; j < TM; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    const int lr = lane & 31, lg = lane >> 5;
-    half8 wa[2][TN], xb[2][TM];
-    auto frags = [&](int buf, int kk, int fs) {
+        half8 wa[2][TN], xb[2][TM];
+        auto frags = [&](int buf, int kk, int fs) {
 #pragma unroll
-        for (int tn = 0; tn < TN; ++tn)
-            wa[fs][tn] = __builtin_bit_cast(half8, smem[buf * STAGE + swz(wn * (BN / WN) + tn * 32 + lr, 2 * kk + lg)]);
-#pragma unroll
-        for (int tm = 0; tm < TM; ++tm)
-            xb[fs][tm] = __builtin_bit_cast(half8, smem[buf * STAGE + BN * GPIECES + swz(wm * (BM / WM) + tm * 32 + lr, 2 * kk + lg)]);
-    };
-    auto mfmas = [&](int fs) {
-#pragma unroll
-        for (int tn = 0; tn < TN; ++tn)
+            for (int tn = 0; tn < TN; ++tn)
+                wa[fs][tn] = __builtin_bit_cast(half8, smem[buf * STAGE + swz(wn * (BN / WN) + tn * 32 + lr, 2 * kk + lg)]);
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
-                acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wa[fs][tn], xb[fs][tm], acc[tn][tm], 0, 0, 0);
-    };
-    // pair each LDS read of the next k-step with one MFMA of the current one
-    auto interleave = [&]() {
+                xb[fs][tm] = __builtin_bit_cast(half8, smem[buf * STAGE + BN * GPIECES + swz(wm * (BM / WM) + tm * 32 + lr, 2 * kk + lg)]);
+        };
+        auto mfmas = [&](int fs) {
 #pragma unroll
-        for (int i = 0; i < TN + TM; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, TN * TM - (TN + TM), 0);
-    };
-
-    // ---- prologue: tiles 0 and 1 into stages 0 and 1; VGPR-path operands run one tile further ahead
-    load_w(0, 0); load_x(0, 0);
-    store_w(0); store_x(0);
-    if (ktiles > 1) {
-        load_w(1, 1); load_x(1, 1);
-        store_w(1); store_x(1);
-    }
-    if (ktiles > 2) {
-        if (!W_DMA) load_w(2, 0);
-        if (!X_DMA) load_x(2, 0);
-    }
-    __syncthreads();
-    frags(0, 0, 0);
-
-    for (int kt = 0; kt < ktiles; ++kt) {
-        const int buf = kt & 1;
+            for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-        for (int kk = 0; kk < GK / 16 - 1; ++kk) {
-            frags(buf, kk + 1, (kk + 1) & 1);
-            mfmas(kk & 1);
-            interleave();
-        }
-        // every read of stage buf has been issued; after the barrier the stage is free and tile kt+1
-        // (other stage) is complete.  The direct-to-LDS loads of tile kt+1 were issued one iteration
-        // ago; the compiler does not carry them across the loop edge, so wait for them here.
-        if (W_DMA || X_DMA) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (kt + 2 < ktiles) {
-            if (W_DMA) load_w(kt + 2, buf); else store_w(buf);
-            if (X_DMA) load_x(kt + 2, buf); else store_x(buf);
-            if (kt + 3 < ktiles) {
-                if (!W_DMA) load_w(kt + 3, buf);
-                if (!X_DMA) load_x(kt + 3, buf);
+                for (int tm = 0; tm < TM; ++tm)
+                    acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wa[fs][tn], xb[fs][tm], acc[tn][tm], 0, 0, 0);
+        };
+        // pair each LDS read of the next k-step with one MFMA of the current one
+        auto interleave = [&]() {
+#pragma unroll
+            for (int i = 0; i < TN + TM; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             }
-        }
-        if (kt + 1 < ktiles) frags(buf ^ 1, 0, 0);
-        mfmas((GK / 16 - 1) & 1);
-    }
+            __builtin_amdgcn_sched_group_barrier(0x008, TN * TM - (TN + TM), 0);
+        };
 
-    if (EPI == EPI_RMSNORM) {
-#pragma unroll
-        for (int i = 0; i < XPASS; ++i) {
-            float v = ssq[i];
-            v += __shfl_xor(v, 1);
-            v += __shfl_xor(v, 2);
-            v += __shfl_xor(v, 4);
-            if (slot == 0) s_r[xunit[i] >> 3] = 1.0f / __builtin_sqrtf(v / (float)K + a.eps);
+        // ---- prologue: k-steps kb and kb+1 into stages 0 and 1; VGPR-path operands run one step further
+        const int nk = ke - kb;
+        load_w(kb, 0); load_x(kb, 0);
+        store_w(0); store_x(0);
+        if (nk > 1) {
+            load_w(kb + 1, 1); load_x(kb + 1, 1);
+            store_w(1); store_x(1);
+        }
+        if (nk > 2) {
+            if (!W_DMA) load_w(kb + 2, 0);
+            if (!X_DMA) load_x(kb + 2, 0);
         }
         __syncthreads();
-    }
+        frags(0, 0, 0);
 
-    // ---- epilogue ------------------------------------------------------------
+        for (int it = 0; it < nk; ++it) {
+            const int buf = it & 1;
 #pragma unroll
-    for (int tm = 0; tm < TM; ++tm) {
-        const int ml = wm * (BM / WM) + tm * 32 + lr;
-        const int m = tile_m * BM + ml;
-        if (m >= a.M) continue;
-        float scale = 1.0f;
-        if (EPI == EPI_RMSNORM) scale = s_r[ml];
-#pragma unroll
-        for (int tn = 0; tn < TN; ++tn) {
-            if (EPI == EPI_SWIGLU) {
-#pragma unroll
-                for (int aa = 0; aa < 4; aa += 2) {
-                    const int v = wn * (BN / WN) + tn * 32 + 8 * aa;
-                    const int j = tile_n * JPT + (v >> 4) * 8 + 4 * lg;
-                    half4 hv;
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        const float g = acc[tn][tm][4 * aa + c], u = acc[tn][tm][4 * (aa + 1) + c];
-                        hv[c] = (_Float16)(g / (1.0f + __expf(-g)) * u);
-                    }
-                    if (j + 3 < a.N && (a.ldo & 3) == 0) {
-                        *reinterpret_cast<half4*>(a.out + (size_t)m * a.ldo + j) = hv;
-                    } else {
-#pragma unroll
-                        for (int c = 0; c < 4; ++c)
-                            if (j + c < a.N) a.out[(size_t)m * a.ldo + j + c] = __builtin_bit_cast(uint16_t, hv[c]);
-                    }
-                }
-            } else {
-#pragma unroll
-                for (int aa = 0; aa < 4; ++aa) {
-                    const int n = tile_n * BN + wn * (BN / WN) + tn * 32 + 8 * aa + 4 * lg;
-                    if (n + 3 < a.N && (a.ldo & 3) == 0) {
-                        half4 hv;
-#pragma unroll
-                        for (int c = 0; c < 4; ++c) hv[c] = (_Float16)(acc[tn][tm][4 * aa + c] * scale);
-                        *reinterpret_cast<half4*>(a.out + (size_t)m * a.ldo + n) = hv;
-                    } else {
-#pragma unroll
-                        for (int c = 0; c < 4; ++c)
-                            if (n + c < a.N)
-                                a.out[(size_t)m * a.ldo + n + c] = to_half_bits(acc[tn][tm][4 * aa + c] * scale);
-                    }
+            for (int kk = 0; kk < GK / 16 - 1; ++kk) {
+                frags(buf, kk + 1, (kk + 1) & 1);
+                mfmas(kk & 1);
+                interleave();
+            }
+            // every read of stage buf has been issued; after the barrier the stage is free and step
+            // it+1 (other stage) is complete.  Its direct-to-LDS loads were issued one iteration ago;
+            // the compiler does not carry them across the loop edge, so wait for them here.
+            if (W_DMA || X_DMA) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (it + 2 < nk) {
+                if (W_DMA) load_w(kb + it + 2, buf); else store_w(buf);
+                if (X_DMA) load_x(kb + it + 2, buf); else store_x(buf);
+                if (it + 3 < nk) {
+                    if (!W_DMA) load_w(kb + it + 3, buf);
+                    if (!X_DMA) load_x(kb + it + 3, buf);
                 }
             }
+            if (it + 1 < nk) frags(buf ^ 1, 0, 0);
+            mfmas((GK / 16 - 1) & 1);
         }
+
+        // ---- this run's sum of squares per token row (RMSNorm) -----------------------------------
+        if (EPI == EPI_RMSNORM) {
+#pragma unroll
+            for (int i = 0; i < XPASS; ++i) {
+                float v = ssq[i];
+                v += __shfl_xor(v, 1);
+                v += __shfl_xor(v, 2);
+                v += __shfl_xor(v, 4);
+                if (vp == 0) s_r[vr0 + ROWS_PER_PASS * i] = v;
+            }
+            __syncthreads();
+        }
+
+        // ---- whole tile: finished below; shared tile: leave the fp32 partial for the fix-up kernel ---
+        const bool whole = (kb == 0 && ke == ktiles);
+        if (!whole) {
+            const int pslot = (t == first_tile) ? 0 : 1;
+            floatx4* ps = reinterpret_cast<floatx4*>(a.partials + ((size_t)worker * 2 + pslot) * (BN * BM));
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        ps[((tn * TM + tm) * 4 + q) * THREADS + tid] =
+                            floatx4{acc[tn][tm][4 * q], acc[tn][tm][4 * q + 1], acc[tn][tm][4 * q + 2], acc[tn][tm][4 * q + 3]};
+            if (EPI == EPI_RMSNORM && tid < BM) a.ssq[((size_t)worker * 2 + pslot) * BM + tid] = s_r[tid];
+        }
+
+        // ---- epilogue ------------------------------------------------------------------------
+        if (whole) {
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
+                float scale = 1.0f;
+                if (EPI == EPI_RMSNORM)
+                    scale = 1.0f / __builtin_sqrtf(s_r[wm * (BM / WM) + tm * 32 + lr] / (float)K + a.eps);
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+                    store_fragment<BN, BM, WN, WM, EPI>(a, tile_n, tile_m, wn, wm, tn, tm, lr, lg, acc[tn][tm], scale);
+            }
+        }
+        // the next run rewrites the LDS stages and s_r only after this barrier
+        __syncthreads();
     }
 }
 
-template <int BN, int BM, int WN, int WM>
-hipError_t launch_cfg(const GemmArgs& a, int epilogue, hipStream_t stream)
+// How many tiles to cut stream-K: none when the tiles fill whole rounds of the grid (or nearly),
+// otherwise the ragged remainder (all tiles when there is less than one round).
+int streamk_tiles(int tiles, int grid)
+{
+    const int rem = tiles % grid;
+    if (rem == 0 || rem * 10 >= grid * 9) return 0;
+    return rem;
+}
+
+// ALL = also build the variants with a transformed activation tile (RMSNorm) or a ragged K; the
+// 256x256 configuration leaves them to the 128x128 one (they would not fit its register budget).
+template <int BN, int BM, int WN, int WM, bool ALL>
+hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream)
 {
     const int per_tile = (epilogue == EPI_SWIGLU) ? BN / 2 : BN;
     const int tiles_n = (a.N + per_tile - 1) / per_tile;
     const int tiles_m = (a.M + BM - 1) / BM;
+    const int ktiles = (a.K + GK - 1) / GK;
+    a.tiles = tiles_n * tiles_m;
+    const long U = (long)a.tiles * ktiles;
+    long grid = grid_cap;
+    if (grid > U) grid = U;
+    static int dbg_sk = getenv("THI_DBG_SK") ? atoi(getenv("THI_DBG_SK")) : -1;
+    const int sk_tiles = dbg_sk == 0 ? 0 : dbg_sk == 1 ? a.tiles % (int)grid : streamk_tiles(a.tiles, (int)grid);
     const size_t lds = (size_t)2 * (BN + BM) * GPIECES * sizeof(uintx4);
-    dim3 g((unsigned)((size_t)tiles_n * tiles_m)), b(64 * WN * WM);
-#define THI_LAUNCH_K(E, KT)                                                                                        \
+    dim3 g((unsigned)grid), b(64 * WN * WM);
+#define THI_LAUNCH_K(E, KT)                                                                                  \
     do {                                                                                                     \
-        auto kern = gemm_tile<BN, BM, WN, WM, E, KT>;                                                            \
+        auto kern = gemm_streamk<BN, BM, WN, WM, E, KT>;                                                     \
         static bool attr_set = false;                                                                        \
         if (!attr_set) {                                                                                     \
             (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                   \
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                 \
             attr_set = true;                                                                                 \
         }                                                                                                    \
-        hipLaunchKernelGGL(kern, g, b, lds, stream, a, tiles_n, tiles_m);                                    \
+        hipLaunchKernelGGL(kern, g, b, lds, stream, a, tiles_m, ktiles, sk_tiles);                           \
+        if (sk_tiles > 0)                                                                                    \
+            hipLaunchKernelGGL((gemm_fixup<BN, BM, WN, WM, E>), dim3(sk_tiles * (BN / WN / 32) * (BM / WM / 32)), \
+                               b, 0, stream, a, tiles_m, ktiles, sk_tiles, (int)grid);                       \
     } while (0)
 #define THI_LAUNCH(E)                                                                                        \
     do {                                                                                                     \
-        if (a.K % GK) THI_LAUNCH_K(E, true);                                                                 \
-        else THI_LAUNCH_K(E, false);                                                                         \
+        if constexpr (ALL) {                                                                                 \
+            if (a.K % GK) THI_LAUNCH_K(E, true);                                                             \
+            else THI_LAUNCH_K(E, false);                                                                     \
+        } else {                                                                                             \
+            THI_LAUNCH_K(E, false);                                                                          \
+        }                                                                                                    \
     } while (0)
     switch (epilogue) {
     case EPI_PLAIN: THI_LAUNCH(EPI_PLAIN); break;
-    case EPI_RMSNORM: THI_LAUNCH(EPI_RMSNORM); break;
+    case EPI_RMSNORM:
+        if constexpr (ALL) THI_LAUNCH(EPI_RMSNORM);
+        break;
     default: THI_LAUNCH(EPI_SWIGLU); break;
     }
 #undef THI_LAUNCH
@@ -352,20 +483,43 @@ hipError_t launch_cfg(const GemmArgs& a, int epilogue, hipStream_t stream)
     return hipGetLastError();
 }
 
+// Rough time model used to pick a configuration: whole-tile rounds plus the stream-K share, at the
+// configuration's measured speed, plus a charge for exchanging partial tiles.
+double config_cost(const GemmArgs& a, int epilogue, int B, int grid, double tflops, double fixup_us)
+{
+    const int per_tile = (epilogue == EPI_SWIGLU) ? B / 2 : B;
+    const long tiles = (long)((a.N + per_tile - 1) / per_tile) * ((a.M + B - 1) / B);
+    const int g = (int)(tiles * ((a.K + GK - 1) / GK) < grid ? tiles * ((a.K + GK - 1) / GK) : grid);
+    const int sk = streamk_tiles((int)tiles, g);
+    const double tile_us = 2.0 * B * B * (double)a.K / (tflops * 1e6 / g);   // one workgroup's speed = total / g
+    const long rounds = (tiles - sk + g - 1) / g;
+    return rounds * tile_us + (double)sk / g * tile_us + (sk ? fixup_us : 0.0);
+}
+
 }  // namespace
+
+size_t gemm_partial_bytes() { return (size_t)GEMM_MAX_GRID * 2 * 128 * 128 * sizeof(float); }
 
 hipError_t launch_gemm(const GemmArgs& a, int epilogue, int num_cus, hipStream_t stream)
 {
     static int dbg_cfg = getenv("THI_DBG_GEMM") ? atoi(getenv("THI_DBG_GEMM")) : 0;
-    (void)num_cus;
     int cfg = dbg_cfg;
-    if (cfg == 0) cfg = (a.M >= 512) ? 1 : 3;
+    int g_big = num_cus, g_small = 2 * num_cus;
+    if (g_big * 4 > GEMM_MAX_GRID) g_big = GEMM_MAX_GRID / 4;
+    if (g_small > GEMM_MAX_GRID) g_small = GEMM_MAX_GRID;
+    const bool big_ok = (epilogue != EPI_RMSNORM) && (a.K % GK == 0);
+    if (cfg == 1 && !big_ok) cfg = 3;
+    if (cfg == 0 && !big_ok) cfg = 3;
+    if (cfg == 0) {
+        // measured: ~1050 / ~900 TFLOP/s on whole tiles; a stream-K pass costs the partial-tile
+        // round trip through HBM plus one more launch
+        const double big = config_cost(a, epilogue, 256, g_big, 1050.0, 45.0);
+        const double small = config_cost(a, epilogue, 128, g_small, 900.0, 40.0);
+        cfg = big <= small ? 1 : 3;
+    }
     switch (cfg) {
-    case 1: return launch_cfg<256, 256, 4, 2>(a, epilogue, stream);
-    case 2: return launch_cfg<256, 256, 2, 4>(a, epilogue, stream);
-    case 4: return launch_cfg<256, 128, 4, 2>(a, epilogue, stream);
-    case 5: return launch_cfg<128, 256, 2, 4>(a, epilogue, stream);
-    default: return launch_cfg<128, 128, 2, 2>(a, epilogue, stream);
+    case 1: return launch_cfg<256, 256, 4, 2, false>(a, epilogue, g_big, stream);
+    default: return launch_cfg<128, 128, 2, 2, true>(a, epilogue, g_small, stream);
     }
 }
 

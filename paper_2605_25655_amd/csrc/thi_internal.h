@@ -55,9 +55,15 @@ struct GemmArgs {
     const uint16_t* w0;      // [N,K]
     const uint16_t* w1;      // up weights for SwiGLU
     uint16_t* out;           // [M,ldo]
+    float* partials;         // [grid][2][tile] fp32 partial tiles (stream-K)
+    float* ssq;              // [grid][2][256]
+    unsigned* counters;      // [tiles]
     int M, N, K, ldo;        // N = physical rows of w0
+    int tiles;               // filled in by the launcher
     float eps;
 };
+constexpr int GEMM_MAX_GRID = 2048;   // in units of 128x128 partial tiles (a 256x256 tile takes four)
+size_t gemm_partial_bytes();
 hipError_t launch_gemm(const GemmArgs& a, int epilogue, int num_cus, hipStream_t stream);
 
 hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream);
