@@ -30,21 +30,25 @@
 // of tiles, token-tile fastest, so the weight panel an XCD streams is shared by
 // the workgroups running on it at that moment.
 #include "thi_internal.h"
-#include <cstdlib>
 
 namespace thi {
 
 namespace {
 
-constexpr int GK = 64;            // k extent of a staged tile
-constexpr int GPIECES = GK / 8;   // 16-byte pieces per tile row
-
-// piece p of tile row `row` lives at 16-byte unit row*8 + (p ^ f(row)); f is a bijection on every
-// aligned group of 8 rows and on the even and the odd rows of every aligned group of 16
-__device__ __forceinline__ int swz(int row, int piece)
+// A staged tile row holds GK halfs = GK/8 16-byte pieces.  Piece p of tile row `row` lives at 16-byte
+// unit row*P + (p ^ f(row)), with f chosen so that 16 consecutive rows reading the same logical piece
+// (an MFMA operand read) and the linear staging writes both spread over all LDS banks:
+//   P = 8 (128-byte rows): f is a bijection on every aligned group of 8 rows and on the even and the odd
+//                          rows of every aligned group of 16;
+//   P = 4 (64-byte rows):  f is a bijection on {r, r+4, r+8, r+12} and on {r, r+2, r+4, r+6}.
+template <int P>
+__device__ __forceinline__ int swz_f(int row)
 {
-    return row * GPIECES + (piece ^ (((row >> 1) & 7) ^ ((row & 1) << 2)));
+    if (P == 8) return ((row >> 1) & 7) ^ ((row & 1) << 2);
+    return (((row >> 1) ^ (row >> 3)) & 1) | (((row >> 2) & 1) << 1);
 }
+template <int P>
+__device__ __forceinline__ int swz(int row, int piece) { return row * P + (piece ^ swz_f<P>(row)); }
 
 __device__ __forceinline__ uint16_t to_half_bits(float v)
 {
@@ -154,11 +158,14 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_fixup(GemmArgs a, int tiles
 
 // BN x BM output tile, WN x WM waves; wave tile (BN/WN) x (BM/WM) built from 32x32 MFMA tiles.
 // KTAIL: K is not a multiple of 64 (pieces past K are zero-filled; operands then go through VGPRs).
-template <int BN, int BM, int WN, int WM, int EPI, bool KTAIL>
+template <int BN, int BM, int WN, int WM, int GK, int NS, int EPI, bool KTAIL>
 __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int tiles_m, int ktiles, int sk_tiles)
 {
     constexpr int NWAVES = WN * WM;
     constexpr int THREADS = 64 * NWAVES;
+    constexpr int GPIECES = GK / 8;             // 16-byte pieces per tile row
+    constexpr int KSTEPS = GK / 16;             // MFMA k-steps per staged tile (even)
+    constexpr int ROWS_PER_DMA = 64 / GPIECES;  // tile rows covered by one wave-wide direct load
     constexpr int ROWS_PER_PASS = THREADS / GPIECES;
     constexpr int WPASS = BN / ROWS_PER_PASS;   // per-thread pieces of the weight tile
     constexpr int XPASS = BM / ROWS_PER_PASS;
@@ -168,6 +175,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
     constexpr bool W_DMA = !KTAIL;                           // weight tile: global -> LDS directly
     constexpr bool X_DMA = !KTAIL && EPI != EPI_RMSNORM;     // activation tile: same unless it is transformed
     constexpr int STAGE = (BN + BM) * GPIECES;   // 16-byte units per stage: weight tile, then activation tile
+    static_assert(NS >= 2 && NS <= 4 && (KSTEPS % 2) == 0, "pipeline shape");
     static_assert(WPASS >= 1 && XPASS >= 1, "tile too small for the thread count");
 
     extern __shared__ uintx4 smem[];
@@ -193,12 +201,12 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
     const int first_tile = u_begin / ktiles;
     int t_whole = sk_tiles + worker;
 
-    // DMA staging role.  A wave instruction covers 8 tile rows x 8 pieces = 64 consecutive LDS units;
-    // lane L owns unit L of it: row (8*block + L/8), physical slot L%8, logical piece slot ^ f(row).
-    // VGPR staging role (operands that are transformed or zero-padded): logical piece tid%8 of rows
-    // tid/8 + ROWS_PER_PASS*i, so that one gamma piece serves all rows of a thread.
-    const int slot = lane & 7;
-    const int vp = tid & 7, vr0 = tid >> 3;
+    // DMA staging role.  A wave instruction covers ROWS_PER_DMA tile rows = 64 consecutive LDS units;
+    // lane L owns unit L of it: row (ROWS_PER_DMA*block + L/P), physical slot L%P, logical piece
+    // slot ^ f(row).  VGPR staging role (operands that are transformed or zero-padded): logical piece
+    // tid%P of rows tid/P + ROWS_PER_PASS*i, so that one gamma piece serves all rows of a thread.
+    const int slot = lane % GPIECES;
+    const int vp = tid % GPIECES, vr0 = tid / GPIECES;
     const uintx4 zero4 = {0u, 0u, 0u, 0u};
 
     for (int u = u_begin;;) {
@@ -222,8 +230,8 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
         const uint16_t* xsrc[XPASS];
 #pragma unroll
         for (int i = 0; i < WPASS; ++i) {
-            const int v = W_DMA ? (wv * WPASS + i) * 8 + (lane >> 3) : vr0 + ROWS_PER_PASS * i;
-            const int piece = W_DMA ? slot ^ (((v >> 1) & 7) ^ ((v & 1) << 2)) : vp;
+            const int v = W_DMA ? (wv * WPASS + i) * ROWS_PER_DMA + lane / GPIECES : vr0 + ROWS_PER_PASS * i;
+            const int piece = W_DMA ? slot ^ swz_f<GPIECES>(v) : vp;
             if (EPI == EPI_SWIGLU) {
                 int j = tile_n * JPT + (v >> 4) * 8 + (v & 7);
                 j = j < a.N ? j : a.N - 1;
@@ -236,8 +244,8 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
         }
 #pragma unroll
         for (int i = 0; i < XPASS; ++i) {
-            const int v = X_DMA ? (wv * XPASS + i) * 8 + (lane >> 3) : vr0 + ROWS_PER_PASS * i;
-            const int piece = X_DMA ? slot ^ (((v >> 1) & 7) ^ ((v & 1) << 2)) : vp;
+            const int v = X_DMA ? (wv * XPASS + i) * ROWS_PER_DMA + lane / GPIECES : vr0 + ROWS_PER_PASS * i;
+            const int piece = X_DMA ? slot ^ swz_f<GPIECES>(v) : vp;
             int m = tile_m * BM + v;
             m = m < a.M ? m : a.M - 1;       // rows past M are loaded from a valid row and never stored
             xsrc[i] = a.x + (size_t)m * K + piece * 8;
@@ -281,7 +289,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
         auto store_w = [&](int buf) {             // VGPR path only
             if (!W_DMA) {
 #pragma unroll
-                for (int i = 0; i < WPASS; ++i) smem[buf * STAGE + swz(vr0 + ROWS_PER_PASS * i, vp)] = wreg[i];
+                for (int i = 0; i < WPASS; ++i) smem[buf * STAGE + swz<GPIECES>(vr0 + ROWS_PER_PASS * i, vp)] = wreg[i];
             }
         };
         auto store_x = [&](int buf) {
@@ -297,7 +305,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
                         half8 pr = xh * gh;      // one rounding: the fp16 product of two fp16 values
                         xv = __builtin_bit_cast(uintx4, pr);
                     }
-                    smem[buf * STAGE + BN * GPIECES + swz(vr0 + ROWS_PER_PASS * i, vp)] = xv;
+                    smem[buf * STAGE + BN * GPIECES + swz<GPIECES>(vr0 + ROWS_PER_PASS * i, vp)] = xv;
                 }
             }
         };
@@ -314,10 +322,10 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
         auto frags = [&](int buf, int kk, int fs) {
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn)
-                wa[fs][tn] = __builtin_bit_cast(half8, smem[buf * STAGE + swz(wn * (BN / WN) + tn * 32 + lr, 2 * kk + lg)]);
+                wa[fs][tn] = __builtin_bit_cast(half8, smem[buf * STAGE + swz<GPIECES>(wn * (BN / WN) + tn * 32 + lr, 2 * kk + lg)]);
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
-                xb[fs][tm] = __builtin_bit_cast(half8, smem[buf * STAGE + BN * GPIECES + swz(wm * (BM / WM) + tm * 32 + lr, 2 * kk + lg)]);
+                xb[fs][tm] = __builtin_bit_cast(half8, smem[buf * STAGE + BN * GPIECES + swz<GPIECES>(wm * (BM / WM) + tm * 32 + lr, 2 * kk + lg)]);
         };
         auto mfmas = [&](int fs) {
 #pragma unroll
@@ -336,44 +344,53 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
             __builtin_amdgcn_sched_group_barrier(0x008, TN * TM - (TN + TM), 0);
         };
 
-        // ---- prologue: k-steps kb and kb+1 into stages 0 and 1; VGPR-path operands run one step further
+        // ---- prologue: the first NS k-tiles into the NS stages; VGPR-path operands run one tile further
         const int nk = ke - kb;
-        load_w(kb, 0); load_x(kb, 0);
-        store_w(0); store_x(0);
-        if (nk > 1) {
-            load_w(kb + 1, 1); load_x(kb + 1, 1);
-            store_w(1); store_x(1);
+#pragma unroll
+        for (int st = 0; st < NS; ++st) {
+            if (st < nk) {
+                load_w(kb + st, st); load_x(kb + st, st);
+                store_w(st); store_x(st);
+            }
         }
-        if (nk > 2) {
-            if (!W_DMA) load_w(kb + 2, 0);
-            if (!X_DMA) load_x(kb + 2, 0);
+        if (nk > NS) {
+            if (!W_DMA) load_w(kb + NS, 0);
+            if (!X_DMA) load_x(kb + NS, 0);
         }
+        if (W_DMA || X_DMA) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         frags(0, 0, 0);
 
+        constexpr int LPT = (W_DMA ? WPASS : 0) + (X_DMA ? XPASS : 0);   // direct loads per k-tile per wave
         for (int it = 0; it < nk; ++it) {
-            const int buf = it & 1;
+            const int st = it % NS;
 #pragma unroll
-            for (int kk = 0; kk < GK / 16 - 1; ++kk) {
-                frags(buf, kk + 1, (kk + 1) & 1);
+            for (int kk = 0; kk < KSTEPS - 1; ++kk) {
+                frags(st, kk + 1, (kk + 1) & 1);
                 mfmas(kk & 1);
                 interleave();
             }
-            // every read of stage buf has been issued; after the barrier the stage is free and step
-            // it+1 (other stage) is complete.  Its direct-to-LDS loads were issued one iteration ago;
-            // the compiler does not carry them across the loop edge, so wait for them here.
-            if (W_DMA || X_DMA) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            // Every read of stage st has been issued.  Before the barrier, k-tile it+1 must have landed:
+            // direct loads complete in order, so it is enough that at most the loads of the k-tiles
+            // behind it (up to NS-2 of them) are still in flight.  The compiler does not carry these
+            // loads across the loop edge, hence the explicit wait.
+            if (LPT > 0) {
+                const int behind = nk - 2 - it;      // k-tiles after it+1 that have been requested
+                if (NS <= 2 || behind <= 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                else if (NS == 3 || behind == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPT) : "memory");
+                else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPT) : "memory");
+            }
             __syncthreads();
-            if (it + 2 < nk) {
-                if (W_DMA) load_w(kb + it + 2, buf); else store_w(buf);
-                if (X_DMA) load_x(kb + it + 2, buf); else store_x(buf);
-                if (it + 3 < nk) {
-                    if (!W_DMA) load_w(kb + it + 3, buf);
-                    if (!X_DMA) load_x(kb + it + 3, buf);
+            if (it + NS < nk) {
+                if (W_DMA) load_w(kb + it + NS, st); else store_w(st);
+                if (X_DMA) load_x(kb + it + NS, st); else store_x(st);
+                if (it + NS + 1 < nk) {
+                    if (!W_DMA) load_w(kb + it + NS + 1, st);
+                    if (!X_DMA) load_x(kb + it + NS + 1, st);
                 }
             }
-            if (it + 1 < nk) frags(buf ^ 1, 0, 0);
-            mfmas((GK / 16 - 1) & 1);
+            if (it + 1 < nk) frags((it + 1) % NS, 0, 0);
+            mfmas((KSTEPS - 1) & 1);
         }
 
         // ---- this run's sum of squares per token row (RMSNorm) -----------------------------------
@@ -433,7 +450,7 @@ int streamk_tiles(int tiles, int grid)
 
 // ALL = also build the variants with a transformed activation tile (RMSNorm) or a ragged K; the
 // 256x256 configuration leaves them to the 128x128 one (they would not fit its register budget).
-template <int BN, int BM, int WN, int WM, bool ALL>
+template <int BN, int BM, int WN, int WM, int GK, int NS, bool ALL>
 hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream)
 {
     const int per_tile = (epilogue == EPI_SWIGLU) ? BN / 2 : BN;
@@ -444,13 +461,12 @@ hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream
     const long U = (long)a.tiles * ktiles;
     long grid = grid_cap;
     if (grid > U) grid = U;
-    static int dbg_sk = getenv("THI_DBG_SK") ? atoi(getenv("THI_DBG_SK")) : -1;
-    const int sk_tiles = dbg_sk == 0 ? 0 : dbg_sk == 1 ? a.tiles % (int)grid : streamk_tiles(a.tiles, (int)grid);
-    const size_t lds = (size_t)2 * (BN + BM) * GPIECES * sizeof(uintx4);
+    const int sk_tiles = streamk_tiles(a.tiles, (int)grid);
+    const size_t lds = (size_t)NS * (BN + BM) * (GK / 8) * sizeof(uintx4);
     dim3 g((unsigned)grid), b(64 * WN * WM);
 #define THI_LAUNCH_K(E, KT)                                                                                  \
     do {                                                                                                     \
-        auto kern = gemm_streamk<BN, BM, WN, WM, E, KT>;                                                     \
+        auto kern = gemm_streamk<BN, BM, WN, WM, GK, NS, E, KT>;                                                    \
         static bool attr_set = false;                                                                        \
         if (!attr_set) {                                                                                     \
             (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                   \
@@ -487,6 +503,7 @@ hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream
 // configuration's measured speed, plus a charge for exchanging partial tiles.
 double config_cost(const GemmArgs& a, int epilogue, int B, int grid, double tflops, double fixup_us)
 {
+    constexpr int GK = 64;
     const int per_tile = (epilogue == EPI_SWIGLU) ? B / 2 : B;
     const long tiles = (long)((a.N + per_tile - 1) / per_tile) * ((a.M + B - 1) / B);
     const int g = (int)(tiles * ((a.K + GK - 1) / GK) < grid ? tiles * ((a.K + GK - 1) / GK) : grid);
@@ -502,25 +519,17 @@ size_t gemm_partial_bytes() { return (size_t)GEMM_MAX_GRID * 2 * 128 * 128 * siz
 
 hipError_t launch_gemm(const GemmArgs& a, int epilogue, int num_cus, hipStream_t stream)
 {
-    static int dbg_cfg = getenv("THI_DBG_GEMM") ? atoi(getenv("THI_DBG_GEMM")) : 0;
-    int cfg = dbg_cfg;
-    int g_big = num_cus, g_small = 2 * num_cus;
+    int g_big = num_cus, g_small = 2 * num_cus;        // workgroups that fit: one resp. two per CU
     if (g_big * 4 > GEMM_MAX_GRID) g_big = GEMM_MAX_GRID / 4;
     if (g_small > GEMM_MAX_GRID) g_small = GEMM_MAX_GRID;
-    const bool big_ok = (epilogue != EPI_RMSNORM) && (a.K % GK == 0);
-    if (cfg == 1 && !big_ok) cfg = 3;
-    if (cfg == 0 && !big_ok) cfg = 3;
-    if (cfg == 0) {
+    bool big = (epilogue != EPI_RMSNORM) && (a.K % 64 == 0);
+    if (big) {
         // measured: ~1050 / ~900 TFLOP/s on whole tiles; a stream-K pass costs the partial-tile
         // round trip through HBM plus one more launch
-        const double big = config_cost(a, epilogue, 256, g_big, 1050.0, 45.0);
-        const double small = config_cost(a, epilogue, 128, g_small, 900.0, 40.0);
-        cfg = big <= small ? 1 : 3;
+        big = config_cost(a, epilogue, 256, g_big, 1050.0, 45.0) <= config_cost(a, epilogue, 128, g_small, 900.0, 40.0);
     }
-    switch (cfg) {
-    case 1: return launch_cfg<256, 256, 4, 2, false>(a, epilogue, g_big, stream);
-    default: return launch_cfg<128, 128, 2, 2, true>(a, epilogue, g_small, stream);
-    }
+    if (big) return launch_cfg<256, 256, 4, 2, 64, 2, false>(a, epilogue, g_big, stream);
+    return launch_cfg<128, 128, 2, 2, 64, 2, true>(a, epilogue, g_small, stream);
 }
 
 }  // namespace thi

@@ -26,7 +26,6 @@
 //              ends up with g and u of the same (token, j); silu(g)*u is applied
 //              to the fp32 accumulators before the fp16 store.
 #include "thi_internal.h"
-#include <cstdlib>
 
 namespace thi {
 
@@ -123,7 +122,6 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
             }
         }
         // activations (+ gamma)
-        if (a.eps == -78.f) return;
         const int kx = k0 + wv * 32 + st_g * 8;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
@@ -169,10 +167,6 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
         __syncthreads();
 
         // ---- weights: two phases of 16 rows x 128 k through the wave buffer --
-        if (a.eps == -79.f) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) acc[0][0] += __builtin_bit_cast(float, cur.w[i].x ^ cur.w[i].y ^ cur.w[i].z ^ cur.w[i].w);
-        } else
 #pragma unroll
         for (int ph = 0; ph < 2; ++ph) {
             __builtin_amdgcn_wave_barrier();
@@ -197,7 +191,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
         if (!run_ends) continue;
 
         const int tile_begin = t * kch;
-        const bool whole = ((run_start == tile_begin) && (u + 1 == tile_begin + kch)) || a.eps <= -77.f;
+        const bool whole = ((run_start == tile_begin) && (u + 1 == tile_begin + kch));
 
         // sum of squares of this run, per token (fixed order: lanes, then waves)
         if (EPI == EPI_RMSNORM) {
@@ -359,15 +353,13 @@ size_t skinny_partial_bytes(int M)
 hipError_t launch_skinny(const SkinnyArgs& a, int epilogue, int num_cus, hipStream_t stream)
 {
     const long U = (long)a.tiles * a.kchunks;
-    static int dbg_grid = getenv("THI_DBG_GRID") ? atoi(getenv("THI_DBG_GRID")) : 0;
-    long grid = dbg_grid > 0 ? dbg_grid : 1L * num_cus;
+    // one workgroup per CU: fewer, larger shares keep the number of workgroups that share a tile
+    // (and so the partial-tile traffic) small; measured faster than two per CU on every shape
+    long grid = num_cus;
     if (grid > SK_MAX_GRID) grid = SK_MAX_GRID;
     if (grid > U) grid = U;
-    static int dbg_nofix = getenv("THI_DBG_NOFIX") ? atoi(getenv("THI_DBG_NOFIX")) : 0;
-    SkinnyArgs b = a;
-    if (dbg_nofix) b.eps = -76.f - dbg_nofix;
-    if (a.M <= 16) return launch_mt<1>(b, epilogue, (int)grid, stream);
-    return launch_mt<2>(b, epilogue, (int)grid, stream);
+    if (a.M <= 16) return launch_mt<1>(a, epilogue, (int)grid, stream);
+    return launch_mt<2>(a, epilogue, (int)grid, stream);
 }
 
 hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream)

@@ -136,6 +136,57 @@ def test_both_kernel_families_cover_every_m(thi, oracle_mod, family, M):
     check(c, y, s, "swiglu", argmax=False)
 
 
+# ------------------------------------------- prefill scheduling corner cases
+# Shapes chosen against the GEMM schedule: fewer tiles than workgroups (every tile is shared and goes
+# through the second pass), one full round plus a ragged remainder, a ragged K, M and N off the tile
+# grid, and the 256x256 configuration with a remainder.  Rows are sampled for the oracle.
+SCHED = [
+    (512, 1280, 2048, "fewer tiles than workgroups"),
+    (640, 5120 + 128, 1024, "full rounds + remainder, small tiles"),
+    (300, 1000, 1096, "ragged M, N, K"),
+    (2048, 2560 + 256, 1024, "256-tile configuration with remainder"),
+    (1024, 8192, 512, "256-tile configuration, whole rounds"),
+]
+
+
+@pytest.mark.parametrize("M,N,K,why", SCHED)
+def test_prefill_schedules(thi, oracle_mod, M, N, K, why):
+    say(f"[case] prefill schedule M={M} N={N} K={K}: {why}")
+    x, w, g = synth.random_problem(9000 + M + N + K, M, N, K)
+    rows = synth.sample_rows(4242, M, 24)
+    r = Runner(M, K, K, N)
+    xd, wd, gd = to_dev(x), to_dev(w), to_dev(g)
+    a1 = to_host(r.linear(xd, wd))
+    a2 = to_host(r.linear(xd, wd))
+    assert np.array_equal(a1.view(np.uint16), a2.view(np.uint16)), "linear is not reproducible"
+    y, s = oracle_mod.linear(x[rows], w)
+    check(a1[rows], y, s, f"linear {M}x{N}x{K}")
+    b1 = to_host(r.rmsnorm_qkv(xd, gd, 1e-6, wd))
+    b2 = to_host(r.rmsnorm_qkv(xd, gd, 1e-6, wd))
+    assert np.array_equal(b1.view(np.uint16), b2.view(np.uint16)), "rmsnorm_qkv is not reproducible"
+    y, s = oracle_mod.rmsnorm_qkv(x[rows], g, 1e-6, w)
+    check(b1[rows], y, s, f"rmsnorm_qkv {M}x{N}x{K}")
+    assert np.isfinite(a1.astype(np.float32)).all() and np.isfinite(b1.astype(np.float32)).all()
+
+
+@pytest.mark.parametrize("M,H,I", [(512, 1024, 2816), (768, 512, 1376), (2048, 1024, 1536)])
+def test_prefill_swiglu_schedules(thi, oracle_mod, M, H, I):
+    say(f"[case] prefill swiglu M={M} H={H} I={I}")
+    rng = np.random.Generator(np.random.Philox(key=7000 + M + H + I))
+    x = f16(rng.standard_normal((M, H)))
+    wg, wu = f16(rng.standard_normal((I, H)) * 0.03), f16(rng.standard_normal((I, H)) * 0.03)
+    wd = f16(rng.standard_normal((H, I)) * 0.03)
+    rows = synth.sample_rows(77, M, 16)
+    r = Runner(M, H, I, H)
+    args = (to_dev(x), to_dev(wg), to_dev(wu), to_dev(wd))
+    c1 = to_host(r.swiglu_mlp(*args))
+    c2 = to_host(r.swiglu_mlp(*args))
+    assert np.array_equal(c1.view(np.uint16), c2.view(np.uint16))
+    y, s = oracle_mod.swiglu_mlp(x[rows], wg, wu, wd)
+    check(c1[rows], y, s, f"swiglu {M}x{H}x{I}")
+    assert np.isfinite(c1.astype(np.float32)).all()
+
+
 # ------------------------------------------------- the five layer configs
 def _layer_case(thi, oracle_mod, cfg_id, rows_limit=32):
     cfg = synth.CONFIGS[cfg_id]
