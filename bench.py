@@ -32,6 +32,10 @@ def parse_args():
     ap.add_argument("--rotate-bytes", type=float, default=1.5e9, help="bytes of distinct weight copies to rotate through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true", help="also time the other configs/M (extra, not the headline)")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="run one plain 1 GiB device copy before the timed region (scales rocprofv3 FETCH_SIZE/WRITE_SIZE)")
+    ap.add_argument("--traffic-kib", type=float, nargs=2, default=None, metavar=("FETCH", "WRITE"),
+                    help="per-launch HBM KiB of the dominant kernel from rocprofv3 --pmc runs, already scaled; reported as roofline.traffic")
     return ap.parse_args()
 
 
@@ -175,6 +179,12 @@ def main():
     host_layer = synth.make_layer(cfg, ms=())
     lb = LayerBench(cfg, M, args.rotate_bytes, host_layer)
 
+    if args.calib_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                       # 1 GiB read + 1 GiB written, a kernel of known size
+        torch.cuda.synchronize()
+        del src, dst
     ms_step, wall_ms = lb.time_loop(lb.step, args.steps, args.warmup)
     tokens_s = M / (ms_step * 1e-3)
     layer_bytes = rf.layer_bytes(M, cfg.hidden, cfg.n_qkv, cfg.inter)
@@ -198,6 +208,9 @@ def main():
         roof = {"bound": "mfma", "kernel": "gate_up (gemm, SwiGLU epilogue)",
                 "achieved": round(gu_flops / (gu_ms * 1e-3) / 1e12, 2), "peak": rf.MI355X_FP16_TFLOPS,
                 "unit": "TFLOP/s", "traffic": None}
+    if args.traffic_kib is not None:
+        roof["traffic"] = {"fetch_bytes": args.traffic_kib[0] * 1024, "write_bytes": args.traffic_kib[1] * 1024,
+                           "algorithmic_bytes": gu_bytes}
     roof["frac"] = round(roof["achieved"] / roof["peak"], 4)
     roof["launch_us"] = ops["gate_up"]["us"]
 
