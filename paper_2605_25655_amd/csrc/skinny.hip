@@ -7,8 +7,8 @@
 // are numbered tile-major and dealt out in equal contiguous shares to a fixed
 // number of workgroups ("stream-K"), so every CU streams the same number of
 // bytes whatever N and K are.  A tile whose k range is shared by several
-// workgroups is finished by whichever of them arrives last; it adds the partial
-// tiles in workgroup order, so the result does not depend on arrival order.
+// workgroups is finished by the one that owns its first k chunk; it adds the
+// partial tiles of the others in workgroup order, so results are reproducible.
 //
 // Per unit and wave: 16 weight rows x 256 k are fetched with fully coalesced
 // 16-byte loads (16 lanes cover 256 contiguous bytes of one row), passed through
@@ -88,7 +88,6 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
     const int u_begin = deal.begin(wg);
     const int u_end = deal.begin(wg + 1);
     if (u_begin >= u_end) return;
-    const int first_tile = u_begin / kch;
 
     const int K = a.K;
     // staging role: this wave stages k-step `wv` (32 k) of each unit; lane -> (token c, k-group g)
@@ -213,80 +212,101 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
             __syncthreads();
         }
 
+        // ---- a tile shared by several workgroups ----------------------------------------------
+        // Shares are contiguous, so the workgroup that owns the tile's first k chunk (w_first)
+        // reaches the tile at the END of its share, every other contributor at the START of its
+        // own.  The others hand in their partial tile (device-coherent stores, then a flag once
+        // the stores are acknowledged) and move on; w_first keeps its part in registers, waits
+        // for the flags -- normally long set -- and adds the partials in workgroup order.
         bool finish = whole;
-        int w_first = wg, w_last = wg;
         if (!whole) {
-            const int slot = (t == first_tile) ? 0 : 1;
-            float* ps = a.partials + ((size_t)wg * 2 + slot) * (SK_WAVES * MT * 4 * 64);
+            const int w_first = deal.owner(tile_begin);
+            const int w_last = deal.owner(tile_begin + kch - 1);
+            constexpr int SLOT_FLOATS = SK_WAVES * MT * 4 * 64;
+            if (wg != w_first) {
+                float* ps = a.partials + (size_t)wg * SLOT_FLOATS;
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
+                for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    __hip_atomic_store(ps + ((wv * MT + mt) * 4 + i) * 64 + lane, acc[mt][i],
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (EPI == EPI_RMSNORM && tid < 32)
-                __hip_atomic_store(a.ssq + ((size_t)wg * 2 + slot) * 32 + tid, s_ssq[tid],
-                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            // The partial tile went out with device-coherent (write-through) stores; once every
-            // wave has seen its stores acknowledged, one thread announces the arrival.
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-            __syncthreads();
-            w_first = deal.owner(tile_begin);
-            w_last = deal.owner(tile_begin + kch - 1);
-            if (tid == 0) {
-                unsigned old = __hip_atomic_fetch_add(a.counters + t, 1u, __ATOMIC_RELAXED,
-                                                      __HIP_MEMORY_SCOPE_AGENT);
-                s_flag = old;
-            }
-            __syncthreads();
-            finish = (s_flag == (unsigned)(w_last - w_first));
-            if (finish) {
+                    for (int i = 0; i < 4; ++i)
+                        __hip_atomic_store(ps + ((wv * MT + mt) * 4 + i) * 64 + lane, acc[mt][i],
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (EPI == EPI_RMSNORM && tid < 32)
+                    __hip_atomic_store(a.ssq + (size_t)wg * 32 + tid, s_ssq[tid], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // stores acknowledged
+                __syncthreads();
                 if (tid == 0)
-                    __hip_atomic_store(a.counters + t, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
-                float sq = 0.f;
-                // contributors are added in workgroup order; their loads are issued four
-                // contributors at a time so the round trips overlap
-                for (int wc0 = w_first; wc0 <= w_last; wc0 += 4) {
-                    float pv[4][MT][4];
-                    float ps4[4];
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        const int wc = wc0 + b;
-                        if (wc <= w_last) {
-                            const int cslot = (deal.begin(wc) / kch == t) ? 0 : 1;
-                            const float* cs = a.partials + ((size_t)wc * 2 + cslot) * (SK_WAVES * MT * 4 * 64);
-#pragma unroll
-                            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                                for (int i = 0; i < 4; ++i)
-                                    pv[b][mt][i] = __hip_atomic_load(cs + ((wv * MT + mt) * 4 + i) * 64 + lane,
-                                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            if (EPI == EPI_RMSNORM && tid < 32)
-                                ps4[b] = __hip_atomic_load(a.ssq + ((size_t)wc * 2 + cslot) * 32 + tid,
-                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        } else {
-#pragma unroll
-                            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                                for (int i = 0; i < 4; ++i) pv[b][mt][i] = 0.f;
-                            ps4[b] = 0.f;
+                    __hip_atomic_store(a.counters + wg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+                if (wv == 0) {
+                    // wave 0 polls the flags, one contributor per lane, so the round trips overlap
+                    unsigned ok = 1u;
+                    for (int wc0 = w_first + 1; wc0 <= w_last; wc0 += 64) {
+                        const int wc = wc0 + lane;
+                        const bool mine = wc <= w_last;
+                        unsigned spins = 0;
+                        bool seen = !mine;
+                        while (true) {
+                            if (!seen)
+                                seen = __hip_atomic_load(a.counters + wc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
+                            if (__builtin_amdgcn_ballot_w64(!seen) == 0ull) break;
+                            __builtin_amdgcn_s_sleep(1);
+                            if (++spins > SK_SPIN_LIMIT) { ok = 0u; break; }      // bounded: every wave exits
                         }
+                        if (mine && seen)
+                            __hip_atomic_store(a.counters + wc, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-#pragma unroll
-                        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                            for (int i = 0; i < 4; ++i) acc[mt][i] += pv[b][mt][i];
-                        if (EPI == EPI_RMSNORM && tid < 32) sq += ps4[b];
+                    if (lane == 0) {
+                        if (!ok) __hip_atomic_store(a.counters + (WS_MAX_COUNTERS - 1), 1u, __ATOMIC_RELAXED,
+                                                    __HIP_MEMORY_SCOPE_AGENT);
+                        s_flag = ok;
                     }
                 }
-                if (EPI == EPI_RMSNORM) {
-                    __syncthreads();
-                    if (tid < 32) s_ssq[tid] = sq;
-                    __syncthreads();
+                __syncthreads();
+                finish = (s_flag != 0u);
+                if (finish) {
+                    float sq = (EPI == EPI_RMSNORM && tid < 32) ? s_ssq[tid] : 0.f;
+                    // loads are issued four contributors at a time so the round trips overlap
+                    for (int wc0 = w_first + 1; wc0 <= w_last; wc0 += 4) {
+                        float pv[4][MT][4];
+                        float ps4[4];
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) {
+                            const int wc = wc0 + b;
+                            if (wc <= w_last) {
+                                const float* cs = a.partials + (size_t)wc * SLOT_FLOATS;
+#pragma unroll
+                                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                                    for (int i = 0; i < 4; ++i)
+                                        pv[b][mt][i] = __hip_atomic_load(cs + ((wv * MT + mt) * 4 + i) * 64 + lane,
+                                                                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                if (EPI == EPI_RMSNORM && tid < 32)
+                                    ps4[b] = __hip_atomic_load(a.ssq + (size_t)wc * 32 + tid, __ATOMIC_RELAXED,
+                                                               __HIP_MEMORY_SCOPE_AGENT);
+                            } else {
+#pragma unroll
+                                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                                    for (int i = 0; i < 4; ++i) pv[b][mt][i] = 0.f;
+                                ps4[b] = 0.f;
+                            }
+                        }
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) {
+#pragma unroll
+                            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) acc[mt][i] += pv[b][mt][i];
+                            if (EPI == EPI_RMSNORM && tid < 32) sq += ps4[b];
+                        }
+                    }
+                    if (EPI == EPI_RMSNORM) {
+                        __syncthreads();
+                        if (tid < 32) s_ssq[tid] = sq;
+                        __syncthreads();
+                    }
                 }
             }
         }

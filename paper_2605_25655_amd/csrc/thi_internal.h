@@ -30,6 +30,7 @@ constexpr int SK_WAVES = 8;
 constexpr int SK_ROWS = 128;        // virtual weight rows per tile (16 per wave)
 constexpr int SK_KC = 256;          // k extent of one work unit
 constexpr int SK_MAX_GRID = 2048;   // upper bound on workgroups (sizes the partial buffers)
+constexpr unsigned SK_SPIN_LIMIT = 1u << 24;   // polls of a contributor's flag before a workgroup gives up
 
 struct SkinnyArgs {
     const uint16_t* x;       // [M,K] activations
@@ -37,9 +38,9 @@ struct SkinnyArgs {
     const uint16_t* w0;      // weights [N,K]  (gate weights for SwiGLU)
     const uint16_t* w1;      // up weights [I,K] for SwiGLU, else nullptr
     uint16_t* out;           // [M,ldo]
-    float* partials;         // [grid][2][slot]
-    float* ssq;              // [grid][2][32]
-    unsigned* counters;      // [tiles]
+    float* partials;         // [grid][slot]: a workgroup's partial tile (fp32 register dump)
+    float* ssq;              // [grid][32]
+    unsigned* counters;      // [grid] hand-over flags, zero between calls; last word: time-out marker
     int M, N, K, ldo;        // N = physical rows of w0 (I for SwiGLU); ldo = out row length
     int tiles, kchunks;      // tiles of SK_ROWS virtual rows; chunks of SK_KC along K
     float eps;
