@@ -142,23 +142,53 @@ def op_bytes_flops(cfg, M, name):
     raise KeyError(name)
 
 
-def cpu_baseline(cfg, M, host_layer, budget_rows=32):
-    """The fp64 oracle, as it stands, timed on this host's cores on a bounded sample."""
+def cpu_baseline(cfg, M, host_layer, target_seconds=12.0):
+    """The fp64 oracle, as it stands, timed on this host's cores on a bounded sample of the workload:
+    token rows of the same layer through all three calls.  A short calibration run sizes the sample to
+    about target_seconds of CPU work (the oracle's cost is linear in rows)."""
     import numpy as np
     import oracle
     from paper_2605_25655_amd import synth
     oracle.build()
-    rows = min(M, budget_rows)
     rng = np.random.Generator(np.random.Philox(key=99))
-    x = (rng.standard_normal((rows, cfg.hidden))).astype(np.float16)
-    t0 = time.perf_counter()
-    oracle.rmsnorm_qkv(x, host_layer["gamma"], synth.EPS, host_layer["w_qkv"])
-    oracle.linear(x, host_layer["w_o"])
-    oracle.swiglu_mlp(x, host_layer["w_gate"], host_layer["w_up"], host_layer["w_down"])
-    dt = time.perf_counter() - t0
-    return {"value": rows / dt, "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
-            "sample": f"{rows} token rows of the same layer (all three calls, all output columns), "
-                      f"{dt:.2f} s of CPU time-to-solution; cost is linear in rows"}
+
+    def run(rows):
+        x = (rng.standard_normal((rows, cfg.hidden))).astype(np.float16)
+        t0 = time.perf_counter()
+        oracle.rmsnorm_qkv(x, host_layer["gamma"], synth.EPS, host_layer["w_qkv"])
+        oracle.linear(x, host_layer["w_o"])
+        oracle.swiglu_mlp(x, host_layer["w_gate"], host_layer["w_up"], host_layer["w_down"])
+        return time.perf_counter() - t0
+
+    probe_rows = 4
+    per_row = run(probe_rows) / probe_rows
+    rows = int(max(8, min(4096, target_seconds / max(per_row, 1e-6))))
+    dt = run(rows)
+    return {"value": round(rows / dt, 2), "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"{rows} token rows of the same layer ({-(-rows // max(M, 1))} batch(es) of M={M}; all three "
+                      f"calls, all output columns), {dt:.1f} s of CPU time"}
+
+
+def measure_ceilings():
+    """What this GPU sustains: streaming HBM read and register-only fp16 MFMA (random operands)."""
+    import torch
+    import paper_2605_25655_amd as thi
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda")
+    buf = torch.empty(1 << 31, dtype=torch.uint8, device="cuda").fill_(1)      # 2 GiB >> last-level cache
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    best = 0.0
+    for _ in range(4):
+        e0.record(); thi.thi_probe_stream_read(buf, sink); e1.record(); torch.cuda.synchronize()
+        best = max(best, buf.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    del buf
+    out = {"hbm_stream_read_GBps": round(best, 1)}
+    gen = torch.Generator(device="cuda"); gen.manual_seed(5)
+    for name, ops in (("mfma_f16_random_operands_TFLOPs", torch.randn(32768, generator=gen, device="cuda").half()),
+                      ("mfma_f16_constant_operands_TFLOPs", torch.full((32768,), 0.0625, device="cuda").half())):
+        thi.thi_probe_mfma_f16(ops, 500, 256, sink); torch.cuda.synchronize()
+        e0.record(); fl = thi.thi_probe_mfma_f16(ops, 20000, 256, sink); e1.record(); torch.cuda.synchronize()
+        out[name] = round(fl / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+    return out
 
 
 def main():
@@ -250,6 +280,10 @@ def main():
             print(f"# sweep {c2.name} M={m}: {extra[f'{c2.name}/M={m}']}", file=sys.stderr, flush=True)
         out["sweep"] = extra
 
+    out["ceilings"] = measure_ceilings()
+    roof["attainable"] = (out["ceilings"]["hbm_stream_read_GBps"] if decode
+                          else out["ceilings"]["mfma_f16_random_operands_TFLOPs"])
+    roof["frac_of_attainable"] = round(roof["achieved"] / roof["attainable"], 4)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, M, host_layer)
     print(json.dumps(out), flush=True)

@@ -20,6 +20,7 @@ _lib = None
 EXPORTED_SYMBOLS = (
     "thi_rmsnorm_qkv", "thi_linear", "thi_swiglu_mlp", "thi_swiglu_gate_up", "thi_workspace_bytes",
     "thi_workspace_init", "thi_status_string", "thi_version", "thi_set_kernel_family",
+    "thi_probe_stream_read", "thi_probe_mfma_f16",
 )
 
 
@@ -62,6 +63,10 @@ def load_library():
     lib.thi_version.restype = ci
     lib.thi_set_kernel_family.argtypes = [ci]
     lib.thi_set_kernel_family.restype = ci
+    lib.thi_probe_stream_read.argtypes = [vp, sz, vp, vp]
+    lib.thi_probe_stream_read.restype = ci
+    lib.thi_probe_mfma_f16.argtypes = [vp, ci, ci, vp, vp]
+    lib.thi_probe_mfma_f16.restype = ci
     _lib = lib
     return lib
 
@@ -171,3 +176,19 @@ def thi_swiglu_gate_up(x, w_gate, w_up, h, workspace, stream=None, check: bool =
     if check and rc != THI_OK:
         raise ThiError(rc, "thi_swiglu_gate_up")
     return rc
+
+
+def thi_probe_stream_read(buffer, sink, stream=None) -> None:
+    """Enqueue one streaming read of `buffer` (device tensor, >= 16 MiB)."""
+    rc = load_library().thi_probe_stream_read(_ptr(buffer), buffer.numel() * buffer.element_size(), _ptr(sink),
+                                              _stream(stream))
+    if rc != THI_OK:
+        raise ThiError(rc, "thi_probe_stream_read")
+
+
+def thi_probe_mfma_f16(operands, iters: int, workgroups: int, sink, stream=None) -> float:
+    """Enqueue the register-only MFMA loop; returns the flops it performs."""
+    rc = load_library().thi_probe_mfma_f16(_ptr(operands), int(iters), int(workgroups), _ptr(sink), _stream(stream))
+    if rc != THI_OK:
+        raise ThiError(rc, "thi_probe_mfma_f16")
+    return float(workgroups) * 8 * iters * 8 * 32768.0
