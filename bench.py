@@ -160,9 +160,10 @@ def cpu_baseline(cfg, M, host_layer, target_seconds=12.0):
         oracle.swiglu_mlp(x, host_layer["w_gate"], host_layer["w_up"], host_layer["w_down"])
         return time.perf_counter() - t0
 
-    probe_rows = 4
-    per_row = run(probe_rows) / probe_rows
-    rows = int(max(8, min(4096, target_seconds / max(per_row, 1e-6))))
+    t_small, t_big = run(4), run(20)                    # cost = fixed (weight widening) + per_row * rows
+    per_row = max((t_big - t_small) / 16.0, 1e-6)
+    fixed = max(t_small - 4 * per_row, 0.0)
+    rows = int(max(8, min(8192, (target_seconds - fixed) / per_row)))
     dt = run(rows)
     return {"value": round(rows / dt, 2), "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
             "sample": f"{rows} token rows of the same layer ({-(-rows // max(M, 1))} batch(es) of M={M}; all three "

@@ -49,6 +49,11 @@ def _load():
         lib.thi_oracle_linear.argtypes = [u16p, u16p, f64p, f64p, L, L, L]
         lib.thi_oracle_rmsnorm_qkv.argtypes = [u16p, u16p, ctypes.c_float, u16p, f64p, f64p, L, L, L]
         lib.thi_oracle_swiglu_mlp.argtypes = [u16p, u16p, u16p, u16p, f64p, f64p, f64p, L, L, L]
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        f32p = ctypes.POINTER(ctypes.c_float)
+        lib.thi_oracle_rope_inplace.argtypes = [f64p, f64p, i32p, f32p, L, L, L, L]
+        lib.thi_oracle_rmsnorm_qkv_rope.argtypes = [u16p, u16p, ctypes.c_float, u16p, i32p, f32p, f64p, f64p,
+                                                    L, L, L, L, L]
         _lib = lib
     return _lib
 
@@ -126,3 +131,26 @@ def swiglu_mlp(x: np.ndarray, wg: np.ndarray, wu: np.ndarray, wd: np.ndarray, re
     if rc:
         raise MemoryError("thi_oracle_swiglu_mlp failed")
     return (y, s, h) if return_h else (y, s)
+
+
+def rope_inplace(y: np.ndarray, s, pos: np.ndarray, theta: np.ndarray, n_rot: int, head_dim: int):
+    """Rotate the interleaved pairs of the first n_rot columns of y (and the magnitudes s) in place."""
+    M, N = y.shape
+    pos = np.ascontiguousarray(pos, dtype=np.int32)
+    theta = np.ascontiguousarray(theta, dtype=np.float32)
+    if pos.shape != (M,) or theta.shape != (head_dim // 2,):
+        raise ValueError("pos must be [M], theta [head_dim/2]")
+    rc = _load().thi_oracle_rope_inplace(
+        _p64(y), _p64(s) if s is not None else None,
+        pos.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), theta.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
+        M, N, n_rot, head_dim)
+    if rc:
+        raise ValueError("thi_oracle_rope_inplace: bad arguments")
+    return y, s
+
+
+def rmsnorm_qkv_rope(x, gamma, eps, w, pos, theta, n_rot: int, head_dim: int):
+    """rmsnorm_qkv followed by the rotation of the Q and K columns, in fp64."""
+    y, s = rmsnorm_qkv(x, gamma, eps, w)
+    rope_inplace(y, s, pos, theta, n_rot, head_dim)
+    return y, s

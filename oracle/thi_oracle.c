@@ -192,3 +192,49 @@ int thi_oracle_swiglu_mlp(const uint16_t *x, const uint16_t *wg, const uint16_t 
     free(up);
     return rc;
 }
+
+/*
+ * Rotary position embedding fused behind the QKV projection (Algorithm 1, "Linear-RoPE fusion":
+ * the rotation is applied to the accumulator tile before it is stored).  Reading taken: the
+ * listing builds its "mix" vector by swapping neighbouring elements with a sign, i.e. the pairs
+ * are the interleaved neighbours (2i, 2i+1) of each head; the angle of pair i at token m is
+ * pos[m] * theta[i], with theta a caller-supplied fp32 table of head_dim/2 entries (the listing
+ * loads theta from memory and multiplies it by the row's position).
+ *
+ *   (a, b) = (y[m, c], y[m, c+1]),  c even, c < n_rot,  i = (c mod head_dim) / 2
+ *   out[m, c]   = a cos(ang) - b sin(ang)
+ *   out[m, c+1] = b cos(ang) + a sin(ang)
+ * Columns >= n_rot (the V projection) are left as they are.  S follows the same linear map with
+ * absolute values: S'[c] = S[c]|cos| + S[c+1]|sin|, S'[c+1] = S[c+1]|cos| + S[c]|sin|.
+ * The angle is formed in fp64 from the exact values of the int32 position and the fp32 theta.
+ */
+int thi_oracle_rope_inplace(double *y, double *s, const int32_t *pos, const float *theta,
+                            long M, long N, long n_rot, long head_dim)
+{
+    if (head_dim <= 0 || (head_dim & 1) || n_rot < 0 || n_rot > N || (n_rot % head_dim)) return -2;
+    for (long m = 0; m < M; ++m) {
+        for (long c = 0; c < n_rot; c += 2) {
+            long i = (c % head_dim) / 2;
+            double ang = (double)pos[m] * (double)theta[i];
+            double cs = cos(ang), sn = sin(ang);
+            double a = y[m * N + c], b = y[m * N + c + 1];
+            y[m * N + c] = a * cs - b * sn;
+            y[m * N + c + 1] = b * cs + a * sn;
+            if (s) {
+                double sa = s[m * N + c], sb = s[m * N + c + 1];
+                s[m * N + c] = sa * fabs(cs) + sb * fabs(sn);
+                s[m * N + c + 1] = sb * fabs(cs) + sa * fabs(sn);
+            }
+        }
+    }
+    return 0;
+}
+
+int thi_oracle_rmsnorm_qkv_rope(const uint16_t *x, const uint16_t *gamma, float eps, const uint16_t *w,
+                                const int32_t *pos, const float *theta, double *y, double *s,
+                                long M, long N, long K, long n_rot, long head_dim)
+{
+    int rc = thi_oracle_rmsnorm_qkv(x, gamma, eps, w, y, s, M, N, K);
+    if (rc) return rc;
+    return thi_oracle_rope_inplace(y, s, pos, theta, M, N, n_rot, head_dim);
+}

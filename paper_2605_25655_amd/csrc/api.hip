@@ -12,7 +12,7 @@ using namespace thi;
 
 constexpr int THI_VERSION = 100;          // 0.1.0
 constexpr int SKINNY_GROUP = 32;          // tokens per skinny launch
-constexpr int SKINNY_MAX_M = 64;          // automatic dispatch: M <= this -> skinny kernels
+constexpr int SKINNY_MAX_M = 32;          // automatic dispatch: M <= this -> skinny kernels (measured crossover)
 
 std::atomic<int> g_family{0};
 
