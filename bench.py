@@ -78,6 +78,11 @@ class LayerBench:
         self.a_o = torch.randn((M, H), generator=gen, device="cuda", dtype=torch.float32).half()
         self.x_mlp = torch.randn((M, H), generator=gen, device="cuda", dtype=torch.float32).half()
         self.gamma = (1 + 0.1 * torch.randn((H,), generator=gen, device="cuda", dtype=torch.float32)).half()
+        self.head_dim = 64 if cfg.index == 1 else 128
+        self.n_rot = cfg.n_qkv - (cfg.n_qkv - H) // 2
+        self.pos = (torch.arange(M, device="cuda", dtype=torch.int32) * 37) % 4096
+        self.theta = (10000.0 ** (-torch.arange(0, self.head_dim, 2, device="cuda", dtype=torch.float64)
+                                  / self.head_dim)).float()
         self.qkv = torch.empty((M, cfg.n_qkv), dtype=torch.float16, device="cuda")
         self.o = torch.empty((M, H), dtype=torch.float16, device="cuda")
         self.y = torch.empty((M, H), dtype=torch.float16, device="cuda")
@@ -98,6 +103,9 @@ class LayerBench:
         t = self.thi
         if name == "rmsnorm_qkv":
             t.thi_rmsnorm_qkv(self.x_qkv, self.gamma, 1e-6, w["w_qkv"], self.qkv, self.ws)
+        elif name == "rmsnorm_qkv_rope":
+            t.thi_rmsnorm_qkv_rope(self.x_qkv, self.gamma, 1e-6, w["w_qkv"], self.pos, self.theta, self.n_rot,
+                                   self.head_dim, self.qkv, self.ws)
         elif name == "o_proj":
             t.thi_linear(self.a_o, w["w_o"], self.o, self.ws)
         elif name == "gate_up":
@@ -129,7 +137,7 @@ class LayerBench:
 def op_bytes_flops(cfg, M, name):
     from paper_2605_25655_amd import roofline as rf
     H, I, Nq = cfg.hidden, cfg.inter, cfg.n_qkv
-    if name == "rmsnorm_qkv":
+    if name in ("rmsnorm_qkv", "rmsnorm_qkv_rope"):
         return rf.linear_bytes(M, Nq, H, True), rf.linear_flops(M, Nq, H)
     if name == "o_proj":
         return rf.linear_bytes(M, H, H), rf.linear_flops(M, H, H)
@@ -222,7 +230,7 @@ def main():
     layer_flops = rf.layer_flops(M, cfg.hidden, cfg.n_qkv, cfg.inter)
 
     ops = {}
-    for name in ("rmsnorm_qkv", "o_proj", "gate_up", "down", "swiglu_mlp"):
+    for name in ("rmsnorm_qkv", "rmsnorm_qkv_rope", "o_proj", "gate_up", "down", "swiglu_mlp"):
         ms, _ = lb.time_loop(lambda i, n=name: lb.op(n, i), max(20, args.steps // 2), max(5, args.warmup // 2))
         b, f = op_bytes_flops(cfg, M, name)
         ops[name] = {"us": round(ms * 1e3, 2), "GBps": round(b / (ms * 1e-3) / 1e9, 1),

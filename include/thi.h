@@ -69,6 +69,24 @@ int thi_rmsnorm_qkv(const void* x, const void* gamma, float eps, const void* w_q
                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * thi_rmsnorm_qkv with the rotary position embedding fused behind it (the paper's worked example
+ * of the fusion rule, Algorithm 1 "Linear-RoPE fusion": the rotation is applied to the accumulator
+ * before the store).  Columns [0, n_rot) of the output -- the Q and K projections -- are rotated in
+ * interleaved pairs (2i, 2i+1) within each head of head_dim columns:
+ *
+ *   ang = positions[m] * theta[i],  i = (n mod head_dim) / 2
+ *   out[m,2i'] = y[2i'] cos(ang) - y[2i'+1] sin(ang),  out[m,2i'+1] = y[2i'+1] cos(ang) + y[2i'] sin(ang)
+ *
+ * with y the thi_rmsnorm_qkv result in fp32.  positions [M] int32 and theta [head_dim/2] fp32 are
+ * device memory (4-byte aligned); n_rot must be a multiple of head_dim (even) and <= N; columns
+ * >= n_rot (V) are not rotated.  Everything else as thi_rmsnorm_qkv.
+ */
+int thi_rmsnorm_qkv_rope(const void* x, const void* gamma, float eps, const void* w_qkv,
+                         const int* positions, const float* theta, int n_rot, int head_dim,
+                         void* out, int M, int N, int K,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * The linear operator (Sec. III-B.1; decode shapes follow the small-M rule of
  * Sec. III-B.2: broadcast X, split N):  out[m,n] = sum_k x[m,k] * w[n,k].
  * x [M,K], w [N,K], out [M,N]; all fp16 device memory.

@@ -18,7 +18,7 @@ _LIB_PATH = os.path.join(_PKG, "libthi.so")
 _lib = None
 
 EXPORTED_SYMBOLS = (
-    "thi_rmsnorm_qkv", "thi_linear", "thi_swiglu_mlp", "thi_swiglu_gate_up", "thi_workspace_bytes",
+    "thi_rmsnorm_qkv", "thi_rmsnorm_qkv_rope", "thi_linear", "thi_swiglu_mlp", "thi_swiglu_gate_up", "thi_workspace_bytes",
     "thi_workspace_init", "thi_status_string", "thi_version", "thi_set_kernel_family",
     "thi_probe_stream_read", "thi_probe_mfma_f16",
 )
@@ -47,6 +47,8 @@ def load_library():
     vp, sz, ci, cf = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_float
     lib.thi_rmsnorm_qkv.argtypes = [vp, vp, cf, vp, vp, ci, ci, ci, vp, sz, vp]
     lib.thi_rmsnorm_qkv.restype = ci
+    lib.thi_rmsnorm_qkv_rope.argtypes = [vp, vp, cf, vp, vp, vp, ci, ci, vp, ci, ci, ci, vp, sz, vp]
+    lib.thi_rmsnorm_qkv_rope.restype = ci
     lib.thi_linear.argtypes = [vp, vp, vp, ci, ci, ci, vp, sz, vp]
     lib.thi_linear.restype = ci
     lib.thi_swiglu_mlp.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, vp, sz, vp]
@@ -192,3 +194,17 @@ def thi_probe_mfma_f16(operands, iters: int, workgroups: int, sink, stream=None)
     if rc != THI_OK:
         raise ThiError(rc, "thi_probe_mfma_f16")
     return float(workgroups) * 8 * iters * 8 * 32768.0
+
+
+def thi_rmsnorm_qkv_rope(x, gamma, eps: float, w_qkv, positions, theta, n_rot: int, head_dim: int, out, workspace,
+                         stream=None, check: bool = True) -> int:
+    """thi_rmsnorm_qkv with rotary embedding on columns [0, n_rot): positions int32 [M], theta fp32 [head_dim/2]."""
+    M, K = x.shape
+    N = w_qkv.shape[0]
+    wp, wb = _ws(workspace)
+    rc = load_library().thi_rmsnorm_qkv_rope(_ptr(x), _ptr(gamma), float(eps), _ptr(w_qkv), _ptr(positions),
+                                             _ptr(theta), int(n_rot), int(head_dim), _ptr(out), M, N, K, wp, wb,
+                                             _stream(stream))
+    if check and rc != THI_OK:
+        raise ThiError(rc, "thi_rmsnorm_qkv_rope")
+    return rc

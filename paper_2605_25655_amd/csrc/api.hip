@@ -77,7 +77,7 @@ bool use_skinny(int M)
 // One fused projection: out[M, ldo] = epilogue( prologue(x)[M,K] * w^T ), any M.
 int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const uint16_t* w0, const uint16_t* w1,
                    uint16_t* out, int M, int N, int K, int ldo, int epilogue, const Workspace& ws,
-                   hipStream_t stream)
+                   hipStream_t stream, RopeArgs rope = RopeArgs{nullptr, nullptr, 0, 2})
 {
     const int cus = device_cu_count();
     if (use_skinny(M)) {
@@ -101,6 +101,8 @@ int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const ui
             a.tiles = tiles;
             a.kchunks = (K + SK_KC - 1) / SK_KC;
             a.eps = eps;
+            a.rope = rope;
+            if (rope.pos) a.rope.pos = rope.pos + m0;
             if (launch_skinny(a, epilogue, cus, stream) != hipSuccess) return THI_ERR_HIP;
         }
         return THI_OK;
@@ -124,6 +126,7 @@ int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const ui
     g.K = K;
     g.ldo = ldo;
     g.eps = eps;
+    g.rope = rope;
     return launch_gemm(g, epilogue, cus, stream) == hipSuccess ? THI_OK : THI_ERR_HIP;
 }
 
@@ -150,6 +153,23 @@ int thi_rmsnorm_qkv(const void* x, const void* gamma, float eps, const void* w_q
     Workspace ws = carve(workspace, M);
     return run_projection((const uint16_t*)x, (const uint16_t*)gamma, eps, (const uint16_t*)w_qkv, nullptr,
                           (uint16_t*)out, M, N, K, N, EPI_RMSNORM, ws, (hipStream_t)hip_stream);
+}
+
+int thi_rmsnorm_qkv_rope(const void* x, const void* gamma, float eps, const void* w_qkv, const int* positions,
+                         const float* theta, int n_rot, int head_dim, void* out, int M, int N, int K,
+                         void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!x || !gamma || !w_qkv || !out || !positions || !theta) return THI_ERR_NULL;
+    int rc = check_common(M, N, K, workspace, workspace_bytes, workspace_need(THI_OP_RMSNORM_QKV, M, N, K));
+    if (rc != THI_OK) return rc;
+    if (head_dim < 2 || (head_dim & 1) || n_rot < 0 || n_rot > N || (n_rot % head_dim)) return THI_ERR_SHAPE;
+    if (misaligned(x, 16) || misaligned(gamma, 16) || misaligned(w_qkv, 16) || misaligned(out, 16) ||
+        misaligned(positions, 4) || misaligned(theta, 4))
+        return THI_ERR_ALIGN;
+    Workspace ws = carve(workspace, M);
+    return run_projection((const uint16_t*)x, (const uint16_t*)gamma, eps, (const uint16_t*)w_qkv, nullptr,
+                          (uint16_t*)out, M, N, K, N, EPI_RMSNORM_ROPE, ws, (hipStream_t)hip_stream,
+                          RopeArgs{positions, theta, n_rot, head_dim});
 }
 
 int thi_linear(const void* x, const void* w, void* out, int M, int N, int K,

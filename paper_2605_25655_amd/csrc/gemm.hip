@@ -106,15 +106,23 @@ __device__ __forceinline__ void store_fragment(const GemmArgs& a, int tile_n, in
 #pragma unroll
         for (int aa = 0; aa < 4; ++aa) {
             const int n = tile_n * BN + wn * (BN / WN) + tn * 32 + 8 * aa + 4 * lg;
+            float v[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) v[c] = f[4 * aa + c] * scale;
+            if (EPI == EPI_RMSNORM_ROPE) {               // the quad holds two complete pairs of one token
+                const int mp = a.rope.pos[m];
+                rope_pair(a.rope, mp, n, v[0], v[1]);
+                rope_pair(a.rope, mp, n + 2, v[2], v[3]);
+            }
             if (n + 3 < a.N && (a.ldo & 3) == 0) {
                 half4 hv;
 #pragma unroll
-                for (int c = 0; c < 4; ++c) hv[c] = (_Float16)(f[4 * aa + c] * scale);
+                for (int c = 0; c < 4; ++c) hv[c] = (_Float16)v[c];
                 *reinterpret_cast<half4*>(a.out + (size_t)m * a.ldo + n) = hv;
             } else {
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
-                    if (n + c < a.N) a.out[(size_t)m * a.ldo + n + c] = to_half_bits(f[4 * aa + c] * scale);
+                    if (n + c < a.N) a.out[(size_t)m * a.ldo + n + c] = to_half_bits(v[c]);
             }
         }
     }
@@ -149,10 +157,10 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_fixup(GemmArgs a, int tiles
 #pragma unroll
             for (int c = 0; c < 4; ++c) f[4 * q + c] += v[c];
         }
-        if (EPI == EPI_RMSNORM) sq += a.ssq[((size_t)wc * 2 + cslot) * BM + ml];
+        if (is_rms(EPI)) sq += a.ssq[((size_t)wc * 2 + cslot) * BM + ml];
     }
     float scale = 1.0f;
-    if (EPI == EPI_RMSNORM) scale = 1.0f / __builtin_sqrtf(sq / (float)a.K + a.eps);
+    if (is_rms(EPI)) scale = 1.0f / __builtin_sqrtf(sq / (float)a.K + a.eps);
     store_fragment<BN, BM, WN, WM, EPI>(a, t / tiles_m, t % tiles_m, wn, wm, tn, tm, lr, lg, f, scale);
 }
 
@@ -173,7 +181,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
     constexpr int TM = BM / WM / 32;
     constexpr int JPT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;   // physical weight rows per tile
     constexpr bool W_DMA = !KTAIL;                           // weight tile: global -> LDS directly
-    constexpr bool X_DMA = !KTAIL && EPI != EPI_RMSNORM;     // activation tile: same unless it is transformed
+    constexpr bool X_DMA = !KTAIL && !is_rms(EPI);     // activation tile: same unless it is transformed
     constexpr int STAGE = (BN + BM) * GPIECES;   // 16-byte units per stage: weight tile, then activation tile
     static_assert(NS >= 2 && NS <= 4 && (KSTEPS % 2) == 0, "pipeline shape");
     static_assert(WPASS >= 1 && XPASS >= 1, "tile too small for the thread count");
@@ -281,7 +289,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
                     xreg[i] = kok ? v : zero4;
                 }
             }
-            if (!X_DMA && EPI == EPI_RMSNORM) {
+            if (!X_DMA && is_rms(EPI)) {
                 const bool kok = !KTAIL || kt * GK + vp * 8 < K;
                 greg = *reinterpret_cast<const uintx4*>(a.gamma + (kok ? kt * GK + vp * 8 : 0));
             }
@@ -297,7 +305,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
 #pragma unroll
                 for (int i = 0; i < XPASS; ++i) {
                     uintx4 xv = xreg[i];
-                    if (EPI == EPI_RMSNORM) {
+                    if (is_rms(EPI)) {
                         half8 xh = __builtin_bit_cast(half8, xv);
                         half8 gh = __builtin_bit_cast(half8, greg);
 #pragma unroll
@@ -394,7 +402,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
         }
 
         // ---- this run's sum of squares per token row (RMSNorm) -----------------------------------
-        if (EPI == EPI_RMSNORM) {
+        if (is_rms(EPI)) {
 #pragma unroll
             for (int i = 0; i < XPASS; ++i) {
                 float v = ssq[i];
@@ -419,7 +427,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
                     for (int q = 0; q < 4; ++q)
                         ps[((tn * TM + tm) * 4 + q) * THREADS + tid] =
                             floatx4{acc[tn][tm][4 * q], acc[tn][tm][4 * q + 1], acc[tn][tm][4 * q + 2], acc[tn][tm][4 * q + 3]};
-            if (EPI == EPI_RMSNORM && tid < BM) a.ssq[((size_t)worker * 2 + pslot) * BM + tid] = s_r[tid];
+            if (is_rms(EPI) && tid < BM) a.ssq[((size_t)worker * 2 + pslot) * BM + tid] = s_r[tid];
         }
 
         // ---- epilogue ------------------------------------------------------------------------
@@ -427,7 +435,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm) {
                 float scale = 1.0f;
-                if (EPI == EPI_RMSNORM)
+                if (is_rms(EPI))
                     scale = 1.0f / __builtin_sqrtf(s_r[wm * (BM / WM) + tm * 32 + lr] / (float)K + a.eps);
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn)
@@ -492,6 +500,9 @@ hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream
     case EPI_RMSNORM:
         if constexpr (ALL) THI_LAUNCH(EPI_RMSNORM);
         break;
+    case EPI_RMSNORM_ROPE:
+        if constexpr (ALL) THI_LAUNCH(EPI_RMSNORM_ROPE);
+        break;
     default: THI_LAUNCH(EPI_SWIGLU); break;
     }
 #undef THI_LAUNCH
@@ -522,7 +533,7 @@ hipError_t launch_gemm(const GemmArgs& a, int epilogue, int num_cus, hipStream_t
     int g_big = num_cus, g_small = 2 * num_cus;        // workgroups that fit: one resp. two per CU
     if (g_big * 4 > GEMM_MAX_GRID) g_big = GEMM_MAX_GRID / 4;
     if (g_small > GEMM_MAX_GRID) g_small = GEMM_MAX_GRID;
-    bool big = (epilogue != EPI_RMSNORM) && (a.K % 64 == 0);
+    bool big = !is_rms(epilogue) && (a.K % 64 == 0);
     if (big) {
         // measured: ~1050 / ~900 TFLOP/s on whole tiles; a stream-K pass costs the partial-tile
         // round trip through HBM plus one more launch

@@ -128,7 +128,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
             if (m < a.M && kx < K) r.x[mt] = ld_cached(a.x + (size_t)m * K + kx);
             else r.x[mt] = uintx4{0u, 0u, 0u, 0u};
         }
-        if (EPI == EPI_RMSNORM) {
+        if (is_rms(EPI)) {
             if (kx < K) r.g = ld_cached(a.gamma + kx);
             else r.g = uintx4{0u, 0u, 0u, 0u};
         }
@@ -153,7 +153,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             uintx4 xv = cur.x[mt];
-            if (EPI == EPI_RMSNORM) {
+            if (is_rms(EPI)) {
                 half8 xh = __builtin_bit_cast(half8, xv);
                 half8 gh = __builtin_bit_cast(half8, cur.g);
 #pragma unroll
@@ -193,7 +193,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
         const bool whole = ((run_start == tile_begin) && (u + 1 == tile_begin + kch));
 
         // sum of squares of this run, per token (fixed order: lanes, then waves)
-        if (EPI == EPI_RMSNORM) {
+        if (is_rms(EPI)) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 float v = ssq[mt];
@@ -231,10 +231,12 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
                     for (int i = 0; i < 4; ++i)
                         __hip_atomic_store(ps + ((wv * MT + mt) * 4 + i) * 64 + lane, acc[mt][i],
                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (EPI == EPI_RMSNORM && tid < 32)
+                if (is_rms(EPI) && tid < 32)
                     __hip_atomic_store(a.ssq + (size_t)wg * 32 + tid, s_ssq[tid], __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // stores acknowledged
+                // every thread waits until its write-through stores are acknowledged (a workgroup-scope
+                // fence alone does not wait for that); only then may the flag go up
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 __syncthreads();
                 if (tid == 0)
                     __hip_atomic_store(a.counters + wg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -266,7 +268,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
                 __syncthreads();
                 finish = (s_flag != 0u);
                 if (finish) {
-                    float sq = (EPI == EPI_RMSNORM && tid < 32) ? s_ssq[tid] : 0.f;
+                    float sq = (is_rms(EPI) && tid < 32) ? s_ssq[tid] : 0.f;
                     // loads are issued four contributors at a time so the round trips overlap
                     for (int wc0 = w_first + 1; wc0 <= w_last; wc0 += 4) {
                         float pv[4][MT][4];
@@ -282,7 +284,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
                                     for (int i = 0; i < 4; ++i)
                                         pv[b][mt][i] = __hip_atomic_load(cs + ((wv * MT + mt) * 4 + i) * 64 + lane,
                                                                          __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                                if (EPI == EPI_RMSNORM && tid < 32)
+                                if (is_rms(EPI) && tid < 32)
                                     ps4[b] = __hip_atomic_load(a.ssq + (size_t)wc * 32 + tid, __ATOMIC_RELAXED,
                                                                __HIP_MEMORY_SCOPE_AGENT);
                             } else {
@@ -299,10 +301,10 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
                             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                                 for (int i = 0; i < 4; ++i) acc[mt][i] += pv[b][mt][i];
-                            if (EPI == EPI_RMSNORM && tid < 32) sq += ps4[b];
+                            if (is_rms(EPI) && tid < 32) sq += ps4[b];
                         }
                     }
-                    if (EPI == EPI_RMSNORM) {
+                    if (is_rms(EPI)) {
                         __syncthreads();
                         if (tid < 32) s_ssq[tid] = sq;
                         __syncthreads();
@@ -325,12 +327,19 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
                             a.out[(size_t)m * a.ldo + j + i] = to_half_bits(silu_mul(acc[mt][i], acc[mt][i + 2]));
                 } else {
                     float scale = 1.0f;
-                    if (EPI == EPI_RMSNORM) scale = 1.0f / __builtin_sqrtf(s_ssq[m] / (float)K + a.eps);
+                    if (is_rms(EPI)) scale = 1.0f / __builtin_sqrtf(s_ssq[m] / (float)K + a.eps);
                     const int n = t * SK_ROWS + wv * 16 + 4 * q;
+                    float v[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[i] = acc[mt][i] * scale;
+                    if (EPI == EPI_RMSNORM_ROPE) {       // the lane holds two complete pairs of one token
+                        const int mp = a.rope.pos[m];
+                        rope_pair(a.rope, mp, n, v[0], v[1]);
+                        rope_pair(a.rope, mp, n + 2, v[2], v[3]);
+                    }
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
-                        if (n + i < a.N)
-                            a.out[(size_t)m * a.ldo + n + i] = to_half_bits(acc[mt][i] * scale);
+                        if (n + i < a.N) a.out[(size_t)m * a.ldo + n + i] = to_half_bits(v[i]);
                 }
             }
         }
@@ -350,6 +359,7 @@ hipError_t launch_mt(const SkinnyArgs& a, int epilogue, int grid, hipStream_t st
     switch (epilogue) {
     case EPI_PLAIN: hipLaunchKernelGGL((skinny_streamk<MT, EPI_PLAIN>), g, b, 0, stream, a); break;
     case EPI_RMSNORM: hipLaunchKernelGGL((skinny_streamk<MT, EPI_RMSNORM>), g, b, 0, stream, a); break;
+    case EPI_RMSNORM_ROPE: hipLaunchKernelGGL((skinny_streamk<MT, EPI_RMSNORM_ROPE>), g, b, 0, stream, a); break;
     default: hipLaunchKernelGGL((skinny_streamk<MT, EPI_SWIGLU>), g, b, 0, stream, a); break;
     }
     return hipGetLastError();

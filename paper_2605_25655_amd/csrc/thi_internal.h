@@ -13,7 +13,16 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 
-enum Epilogue { EPI_PLAIN = 0, EPI_RMSNORM = 1, EPI_SWIGLU = 2 };
+enum Epilogue { EPI_PLAIN = 0, EPI_RMSNORM = 1, EPI_SWIGLU = 2, EPI_RMSNORM_ROPE = 3 };
+constexpr bool is_rms(int epi) { return epi == EPI_RMSNORM || epi == EPI_RMSNORM_ROPE; }
+
+// Rotary embedding applied in the epilogue (EPI_RMSNORM_ROPE): interleaved pairs (2i, 2i+1) of every
+// head in columns [0, n_rot); angle = pos[m] * theta[i].
+struct RopeArgs {
+    const int* pos;          // [M] token positions
+    const float* theta;      // [head_dim / 2]
+    int n_rot, head_dim;
+};
 
 // ---- workspace layout (bytes from the workspace base) ----------------------
 // [0, 64 KiB)            : arrival counters (uint32), zero between calls
@@ -44,6 +53,7 @@ struct SkinnyArgs {
     int M, N, K, ldo;        // N = physical rows of w0 (I for SwiGLU); ldo = out row length
     int tiles, kchunks;      // tiles of SK_ROWS virtual rows; chunks of SK_KC along K
     float eps;
+    RopeArgs rope;
 };
 
 size_t skinny_partial_bytes(int M);
@@ -62,10 +72,24 @@ struct GemmArgs {
     int M, N, K, ldo;        // N = physical rows of w0
     int tiles;               // filled in by the launcher
     float eps;
+    RopeArgs rope;
 };
 constexpr int GEMM_MAX_GRID = 2048;   // in units of 128x128 partial tiles (a 256x256 tile takes four)
 size_t gemm_partial_bytes();
 hipError_t launch_gemm(const GemmArgs& a, int epilogue, int num_cus, hipStream_t stream);
+
+// Rotate one interleaved pair (a, b) = (y[c], y[c+1]), c even: Algorithm 1's  y*cos + mix*sin  with
+// mix = (-b, a).  fp32 angle and full-range sinf/cosf (positions reach thousands of radians).
+__device__ __forceinline__ void rope_pair(const RopeArgs& r, int m_pos, int c, float& a, float& b)
+{
+    if (c >= r.n_rot) return;
+    const float ang = (float)m_pos * r.theta[(c % r.head_dim) >> 1];
+    float sn, cs;
+    sincosf(ang, &sn, &cs);
+    const float na = a * cs - b * sn, nb = b * cs + a * sn;
+    a = na;
+    b = nb;
+}
 
 hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream);
 

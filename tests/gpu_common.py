@@ -55,3 +55,8 @@ class Runner:
         out = new_out(x.shape[0], wd.shape[0])
         self.thi.thi_swiglu_mlp(x, wg, wu, wd, out, self.ws)
         return out
+
+    def rmsnorm_qkv_rope(self, x, gamma, eps, w, pos, theta, n_rot, head_dim):
+        out = new_out(x.shape[0], w.shape[0])
+        self.thi.thi_rmsnorm_qkv_rope(x, gamma, eps, w, pos, theta, n_rot, head_dim, out, self.ws)
+        return out

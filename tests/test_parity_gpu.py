@@ -136,6 +136,30 @@ def test_both_kernel_families_cover_every_m(thi, oracle_mod, family, M):
     check(c, y, s, "swiglu", argmax=False)
 
 
+# ----------------------------------------------- shared-tile hand-over (decode)
+@pytest.mark.parametrize("M,N,K", [(1, 4096, 4096), (32, 4096, 4096), (32, 4096, 11008), (16, 512, 8192)])
+def test_shared_tile_handover_is_reproducible(thi, oracle_mod, M, N, K):
+    """Few row tiles and a long K: every tile is shared by many workgroups.  The partial tiles must be
+    complete when the finishing workgroup reads them: 40 repeats have to agree bit for bit."""
+    say(f"[case] hand-over repeat M={M} N={N} K={K}")
+    import torch
+    x, w, g = synth.random_problem(8800 + M + N + K, M, N, K)
+    r = Runner(M, K, K, N)
+    xd, wd, gd = to_dev(x), to_dev(w), to_dev(g)
+    outs = [r.linear(xd, wd) for _ in range(20)] + [r.rmsnorm_qkv(xd, gd, 1e-6, wd) for _ in range(20)]
+    torch.cuda.synchronize()
+    lin = [to_host(o) for o in outs[:20]]
+    rms = [to_host(o) for o in outs[20:]]
+    for o in lin[1:]:
+        assert np.array_equal(o.view(np.uint16), lin[0].view(np.uint16))
+    for o in rms[1:]:
+        assert np.array_equal(o.view(np.uint16), rms[0].view(np.uint16))
+    y, s = oracle_mod.linear(x, w)
+    check(lin[0], y, s, "linear")
+    y, s = oracle_mod.rmsnorm_qkv(x, g, 1e-6, w)
+    check(rms[0], y, s, "rmsnorm_qkv")
+
+
 # ------------------------------------------- prefill scheduling corner cases
 # Shapes chosen against the GEMM schedule: fewer tiles than workgroups (every tile is shared and goes
 # through the second pass), one full round plus a ragged remainder, a ragged K, M and N off the tile
@@ -185,6 +209,85 @@ def test_prefill_swiglu_schedules(thi, oracle_mod, M, H, I):
     y, s = oracle_mod.swiglu_mlp(x[rows], wg, wu, wd)
     check(c1[rows], y, s, f"swiglu {M}x{H}x{I}")
     assert np.isfinite(c1.astype(np.float32)).all()
+
+
+# ----------------------------------------------- rotary embedding epilogue
+def _theta(head_dim, base=10000.0):
+    i = np.arange(head_dim // 2, dtype=np.float64)
+    return (base ** (-2.0 * i / head_dim)).astype(np.float32)
+
+
+def _dev_i32(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+
+def _dev_f32(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+@pytest.mark.parametrize("M,N,K,n_rot,hd", [(1, 96, 64, 64, 32), (7, 200, 136, 128, 64), (32, 384, 520, 256, 128),
+                                            (40, 192, 256, 192, 64), (300, 520, 328, 512, 128), (600, 256, 512, 128, 8)])
+def test_rope_epilogue_shapes(thi, oracle_mod, M, N, K, n_rot, hd):
+    say(f"[case] rope M={M} N={N} K={K} n_rot={n_rot} head_dim={hd}")
+    x, w, g = synth.random_problem(3100 + M + N + K, M, N, K)
+    rng = np.random.default_rng(M + N)
+    pos = rng.integers(0, 4096, size=M).astype(np.int32)
+    pos[0] = 0
+    th = _theta(hd)
+    r = Runner(M, K, K, N)
+    got = to_host(r.rmsnorm_qkv_rope(to_dev(x), to_dev(g), 1e-6, to_dev(w), _dev_i32(pos), _dev_f32(th), n_rot, hd))
+    y, s = oracle_mod.rmsnorm_qkv_rope(x, g, 1e-6, w, pos, th, n_rot, hd)
+    check(got, y, s, f"rope {M}x{N}x{K}", argmax=False)
+    # position 0 and the unrotated columns are the plain fused projection (the two kernels may round
+    # the scale factor differently: allow one fp16 unit in the last place)
+    plain = to_host(r.rmsnorm_qkv(to_dev(x), to_dev(g), 1e-6, to_dev(w)))
+
+    def ulp_apart(a, b):
+        ia, ib = a.view(np.int16).astype(np.int32), b.view(np.int16).astype(np.int32)
+        ia = np.where(ia < 0, -32768 - ia, ia)
+        ib = np.where(ib < 0, -32768 - ib, ib)
+        return np.abs(ia - ib).max() if a.size else 0
+
+    assert ulp_apart(got[0], plain[0]) <= 1
+    assert ulp_apart(got[:, n_rot:], plain[:, n_rot:]) <= 1
+
+
+def test_rope_argument_errors(thi):
+    import torch
+    M, N, K = 2, 64, 64
+    r = Runner(M, K, K, N)
+    x = torch.zeros((M, K), dtype=torch.float16, device="cuda")
+    w = torch.zeros((N, K), dtype=torch.float16, device="cuda")
+    g = torch.ones((K,), dtype=torch.float16, device="cuda")
+    out = torch.zeros((M, N), dtype=torch.float16, device="cuda")
+    pos, th = _dev_i32(np.zeros(M)), _dev_f32(np.ones(8))
+    assert thi.thi_rmsnorm_qkv_rope(x, g, 1e-6, w, pos, th, 24, 16, out, r.ws, check=False) == 2   # n_rot % head_dim
+    assert thi.thi_rmsnorm_qkv_rope(x, g, 1e-6, w, pos, th, 128, 16, out, r.ws, check=False) == 2  # n_rot > N
+    assert thi.thi_rmsnorm_qkv_rope(x, g, 1e-6, w, pos, th, 32, 15, out, r.ws, check=False) == 2   # odd head_dim
+    assert thi.thi_rmsnorm_qkv_rope(x, g, 1e-6, w, None, th, 32, 16, out, r.ws, check=False) == 1
+
+
+@pytest.mark.parametrize("cfg_id,ms", [(1, (1,)), (2, (1, 8, 32)), (5, (32,)), (3, (512,))])
+def test_rope_on_layer_configs(thi, oracle_mod, cfg_id, ms):
+    cfg = synth.CONFIGS[cfg_id]
+    heads = {1: 8, 2: 32, 3: 40, 5: 64}[cfg_id]
+    hd = cfg.hidden // heads
+    n_rot = cfg.n_qkv - (cfg.n_qkv - cfg.hidden) // 2          # Q and K columns (K and V are equally wide)
+    say(f"[case] rope config {cfg_id} {cfg.name}: head_dim={hd} n_rot={n_rot}")
+    L = synth.make_layer(cfg, ms=ms)
+    wq, gd, th = to_dev(L["w_qkv"]), to_dev(L["gamma"]), _theta(hd)
+    for M in ms:
+        x = L["acts"][M]["x_qkv"]
+        pos = (np.arange(M) * 37 % 4096).astype(np.int32) if M > 1 else np.array([1234], np.int32)
+        r = Runner(M, cfg.hidden, cfg.inter, cfg.n_qkv)
+        got = to_host(r.rmsnorm_qkv_rope(to_dev(x), gd, L["eps"], wq, _dev_i32(pos), _dev_f32(th), n_rot, hd))
+        rows = synth.sample_rows(555 + cfg_id, M, 16)
+        y, s = oracle_mod.rmsnorm_qkv_rope(x[rows], L["gamma"], L["eps"], L["w_qkv"], pos[rows], th, n_rot, hd)
+        info = check(got[rows], y, s, f"cfg{cfg_id} M={M} rmsnorm_qkv_rope")
+        say(f"    M={M} worst |err|/S = {info['worst_rel']:.2e}")
+        assert np.isfinite(got.astype(np.float32)).all()
 
 
 # ------------------------------------------------- the five layer configs
