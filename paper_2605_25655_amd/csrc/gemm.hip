@@ -447,13 +447,27 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
     }
 }
 
-// How many tiles to cut stream-K: none when the tiles fill whole rounds of the grid (or nearly),
-// otherwise the ragged remainder (all tiles when there is less than one round).
-int streamk_tiles(int tiles, int grid)
+// Time model of the two ways to run `tiles` tiles of edge B on `grid` workgroups (measured speeds:
+// ~1050 TFLOP/s with 256-tiles, ~900 with 128-tiles, for the whole chip):
+//   whole tiles only : ceil(tiles / grid) rounds;
+//   stream-K remainder: floor(tiles / grid) rounds, the ragged remainder shared equally, plus the second
+//                       pass -- one more launch and the partial tiles' round trip through memory (about
+//                       grid + remainder partial tiles written and read, ~4 TB/s).
+struct Schedule {
+    int sk_tiles;      // tiles cut into k-steps and dealt stream-K (0: whole tiles only)
+    double us;         // modelled time
+};
+Schedule plan_schedule(int tiles, int grid, int B, int K)
 {
+    const double tflops = (B == 256) ? 1050.0 : 900.0;
+    const double tile_us = 2.0 * B * B * (double)K / (tflops * 1e6 / grid);   // one workgroup's speed = total / grid
     const int rem = tiles % grid;
-    if (rem == 0 || rem * 10 >= grid * 9) return 0;
-    return rem;
+    const double whole = (double)((tiles + grid - 1) / grid) * tile_us;
+    if (rem == 0) return Schedule{0, whole};
+    const double fixup_us = 5.0 + (double)(grid + rem) * ((double)B * B * 4.0) * 2.0 / 4.0e6;
+    // short shares suit the 128-tile kernel badly (measured ~1.6x the model): price that in
+    const double shared = (((double)(tiles / grid) + (double)rem / grid) * tile_us + fixup_us) * (B == 256 ? 1.0 : 1.6);
+    return shared < whole ? Schedule{rem, shared} : Schedule{0, whole};
 }
 
 // ALL = also build the variants with a transformed activation tile (RMSNorm) or a ragged K; the
@@ -469,7 +483,7 @@ hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream
     const long U = (long)a.tiles * ktiles;
     long grid = grid_cap;
     if (grid > U) grid = U;
-    const int sk_tiles = streamk_tiles(a.tiles, (int)grid);
+    const int sk_tiles = plan_schedule(a.tiles, (int)grid, BN, a.K).sk_tiles;
     const size_t lds = (size_t)NS * (BN + BM) * (GK / 8) * sizeof(uintx4);
     dim3 g((unsigned)grid), b(64 * WN * WM);
 #define THI_LAUNCH_K(E, KT)                                                                                  \
@@ -510,18 +524,13 @@ hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream
     return hipGetLastError();
 }
 
-// Rough time model used to pick a configuration: whole-tile rounds plus the stream-K share, at the
-// configuration's measured speed, plus a charge for exchanging partial tiles.
-double config_cost(const GemmArgs& a, int epilogue, int B, int grid, double tflops, double fixup_us)
+double config_cost(const GemmArgs& a, int epilogue, int B, int grid)
 {
-    constexpr int GK = 64;
     const int per_tile = (epilogue == EPI_SWIGLU) ? B / 2 : B;
     const long tiles = (long)((a.N + per_tile - 1) / per_tile) * ((a.M + B - 1) / B);
-    const int g = (int)(tiles * ((a.K + GK - 1) / GK) < grid ? tiles * ((a.K + GK - 1) / GK) : grid);
-    const int sk = streamk_tiles((int)tiles, g);
-    const double tile_us = 2.0 * B * B * (double)a.K / (tflops * 1e6 / g);   // one workgroup's speed = total / g
-    const long rounds = (tiles - sk + g - 1) / g;
-    return rounds * tile_us + (double)sk / g * tile_us + (sk ? fixup_us : 0.0);
+    const long units = tiles * ((a.K + 63) / 64);
+    const int g = (int)(units < grid ? units : grid);
+    return plan_schedule((int)tiles, g, B, a.K).us;
 }
 
 }  // namespace
@@ -535,9 +544,7 @@ hipError_t launch_gemm(const GemmArgs& a, int epilogue, int num_cus, hipStream_t
     if (g_small > GEMM_MAX_GRID) g_small = GEMM_MAX_GRID;
     bool big = !is_rms(epilogue) && (a.K % 64 == 0);
     if (big) {
-        // measured: ~1050 / ~900 TFLOP/s on whole tiles; a stream-K pass costs the partial-tile
-        // round trip through HBM plus one more launch
-        big = config_cost(a, epilogue, 256, g_big, 1050.0, 45.0) <= config_cost(a, epilogue, 128, g_small, 900.0, 40.0);
+        big = config_cost(a, epilogue, 256, g_big) <= config_cost(a, epilogue, 128, g_small);
     }
     if (big) return launch_cfg<256, 256, 4, 2, 64, 2, false>(a, epilogue, g_big, stream);
     return launch_cfg<128, 128, 2, 2, 64, 2, true>(a, epilogue, g_small, stream);
