@@ -20,7 +20,13 @@
  *   - Workspace: at least thi_workspace_bytes(op, ...) bytes, 256-byte
  *     aligned, and prepared ONCE after allocation with thi_workspace_init().
  *     Every call leaves the workspace ready for the next call.  One workspace
- *     must not be used by two calls that may run concurrently.
+ *     must not be used by two calls that may run concurrently.  The decode
+ *     kernels (M <= 32) hand partial results from workgroup to workgroup inside
+ *     one launch of one workgroup per compute unit; the waits are bounded, so a
+ *     launch always terminates, but if the GPU is shared so heavily that a wait
+ *     runs out, the last 32-bit word of the first 64 KiB of the workspace is set
+ *     to 1 and the outputs of that call are undefined (re-initialise the
+ *     workspace).  This cannot happen on a GPU the process has to itself.
  *   - Execution: work is enqueued on `hip_stream` (a hipStream_t passed as
  *     void*, NULL = the default stream); the call returns without
  *     synchronising.  Results are bitwise reproducible from run to run.

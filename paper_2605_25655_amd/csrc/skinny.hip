@@ -225,12 +225,14 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
             constexpr int SLOT_FLOATS = SK_WAVES * MT * 4 * 64;
             if (wg != w_first) {
                 float* ps = a.partials + (size_t)wg * SLOT_FLOATS;
+                // only the lanes that hold a real token (column c = lane % 16 of token tile mt) take part
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
+                    if (mt * 16 + (lane & 15) < a.M)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        __hip_atomic_store(ps + ((wv * MT + mt) * 4 + i) * 64 + lane, acc[mt][i],
-                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        for (int i = 0; i < 4; ++i)
+                            __hip_atomic_store(ps + ((wv * MT + mt) * 4 + i) * 64 + lane, acc[mt][i],
+                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (is_rms(EPI) && tid < 32)
                     __hip_atomic_store(a.ssq + (size_t)wg * 32 + tid, s_ssq[tid], __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
@@ -282,8 +284,10 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
                                 for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                                     for (int i = 0; i < 4; ++i)
-                                        pv[b][mt][i] = __hip_atomic_load(cs + ((wv * MT + mt) * 4 + i) * 64 + lane,
-                                                                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                        pv[b][mt][i] = (mt * 16 + (lane & 15) < a.M)
+                                            ? __hip_atomic_load(cs + ((wv * MT + mt) * 4 + i) * 64 + lane,
+                                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                            : 0.f;
                                 if (is_rms(EPI) && tid < 32)
                                     ps4[b] = __hip_atomic_load(a.ssq + (size_t)wc * 32 + tid, __ATOMIC_RELAXED,
                                                                __HIP_MEMORY_SCOPE_AGENT);
