@@ -64,6 +64,19 @@ __device__ __forceinline__ void dma16(const uint16_t* src, uintx4* lds_base)
                                      (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
 }
 
+// The same load with the address split into a wave-uniform base (scalar registers) and a 32-bit
+// per-lane byte offset: no vector ALU work per load.  Written in assembly because the builtin always
+// takes the 64-bit per-lane form.  The kernels that use it use M0 for nothing else and wait for these
+// loads explicitly (s_waitcnt vmcnt) before the barrier that publishes the stage.
+__device__ __forceinline__ void dma16_sbase(const void* base_uniform, unsigned lane_byte_offset, uintx4* lds_base)
+{
+    const unsigned lds_addr = (unsigned)(size_t)(__attribute__((address_space(3))) void*)lds_base;
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(lane_byte_offset), "s"(base_uniform), "s"(lds_addr)
+                 : "memory");
+}
+
 // U work units dealt to G workers in contiguous shares: the first `rem` take q+1, the others q.
 struct Deal {
     int q, rem;
@@ -184,12 +197,14 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
     constexpr bool X_DMA = !KTAIL && !is_rms(EPI);     // activation tile: same unless it is transformed
     constexpr int STAGE = (BN + BM) * GPIECES;   // 16-byte units per stage: weight tile, then activation tile
     static_assert(NS >= 2 && NS <= 4 && (KSTEPS % 2) == 0, "pipeline shape");
+    static_assert(EPI != EPI_SWIGLU || KTAIL || ROWS_PER_DMA == 8, "gate/up interleave assumes 8-row direct loads");
     static_assert(WPASS >= 1 && XPASS >= 1, "tile too small for the thread count");
 
     extern __shared__ uintx4 smem[];
     __shared__ float s_r[BM];
 
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid / 64;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid / 64);     // wave index, known uniform to the compiler
     const int wn = wv % WN, wm = wv / WN;
     const int lr = lane & 31, lg = lane >> 5;
     const int K = a.K;
@@ -234,29 +249,56 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
         }
         const int tile_m = t % tiles_m, tile_n = t / tiles_m;
 
+        // Operand sources.  Direct loads: a wave-uniform base pointer per wave instruction (scalar
+        // registers, advanced by scalar adds) plus a 32-bit per-lane byte offset that never changes,
+        // so that issuing a k-tile's loads costs no vector ALU work.  Staged loads: per-thread pointers.
         const uint16_t* wsrc[WPASS];
         const uint16_t* xsrc[XPASS];
+        unsigned woff[WPASS], xoff[XPASS];
 #pragma unroll
         for (int i = 0; i < WPASS; ++i) {
-            const int v = W_DMA ? (wv * WPASS + i) * ROWS_PER_DMA + lane / GPIECES : vr0 + ROWS_PER_PASS * i;
+            const int blk = wv * WPASS + i;                          // (uniform) block of ROWS_PER_DMA rows
+            const int v = W_DMA ? blk * ROWS_PER_DMA + lane / GPIECES : vr0 + ROWS_PER_PASS * i;
             const int piece = W_DMA ? slot ^ swz_f<GPIECES>(v) : vp;
             if (EPI == EPI_SWIGLU) {
-                int j = tile_n * JPT + (v >> 4) * 8 + (v & 7);
+                const int j0 = tile_n * JPT;                         // first row of the tile: always valid
+                int j = j0 + (v >> 4) * 8 + (v & 7);
                 j = j < a.N ? j : a.N - 1;
-                wsrc[i] = (((v >> 3) & 1) ? a.w1 : a.w0) + (size_t)j * K + piece * 8;
+                if (W_DMA) {
+                    // ROWS_PER_DMA = 8: a wave instruction covers 8 gate rows or the 8 matching up rows
+                    wsrc[i] = ((blk & 1) ? a.w1 : a.w0) + (size_t)j0 * K;
+                    woff[i] = (unsigned)((j - j0) * K + piece * 8) * 2u;
+                } else {
+                    wsrc[i] = (((v >> 3) & 1) ? a.w1 : a.w0) + (size_t)j * K + piece * 8;
+                    woff[i] = 0;
+                }
             } else {
-                int n = tile_n * BN + v;
+                const int n0 = tile_n * BN;
+                int n = n0 + v;
                 n = n < a.N ? n : a.N - 1;
-                wsrc[i] = a.w0 + (size_t)n * K + piece * 8;
+                if (W_DMA) {
+                    wsrc[i] = a.w0 + (size_t)n0 * K;
+                    woff[i] = (unsigned)((n - n0) * K + piece * 8) * 2u;
+                } else {
+                    wsrc[i] = a.w0 + (size_t)n * K + piece * 8;
+                    woff[i] = 0;
+                }
             }
         }
 #pragma unroll
         for (int i = 0; i < XPASS; ++i) {
             const int v = X_DMA ? (wv * XPASS + i) * ROWS_PER_DMA + lane / GPIECES : vr0 + ROWS_PER_PASS * i;
             const int piece = X_DMA ? slot ^ swz_f<GPIECES>(v) : vp;
-            int m = tile_m * BM + v;
+            const int m0 = tile_m * BM;
+            int m = m0 + v;
             m = m < a.M ? m : a.M - 1;       // rows past M are loaded from a valid row and never stored
-            xsrc[i] = a.x + (size_t)m * K + piece * 8;
+            if (X_DMA) {
+                xsrc[i] = a.x + (size_t)m0 * K;
+                xoff[i] = (unsigned)((m - m0) * K + piece * 8) * 2u;
+            } else {
+                xsrc[i] = a.x + (size_t)m * K + piece * 8;
+                xoff[i] = 0;
+            }
         }
 
         uintx4 wreg[W_DMA ? 1 : WPASS], xreg[X_DMA ? 1 : XPASS], greg;
@@ -270,7 +312,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
 #pragma unroll
             for (int i = 0; i < WPASS; ++i) {
                 if (W_DMA) {
-                    dma16(wsrc[i] + kt * GK, smem + buf * STAGE + (wv * WPASS + i) * 64);
+                    dma16_sbase(wsrc[i] + kt * GK, woff[i], smem + buf * STAGE + (wv * WPASS + i) * 64);
                 } else {
                     const bool kok = kt * GK + vp * 8 < K;
                     uintx4 v = *reinterpret_cast<const uintx4*>(wsrc[i] + (kok ? kt * GK : -vp * 8));
@@ -282,7 +324,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
 #pragma unroll
             for (int i = 0; i < XPASS; ++i) {
                 if (X_DMA) {
-                    dma16(xsrc[i] + kt * GK, smem + buf * STAGE + BN * GPIECES + (wv * XPASS + i) * 64);
+                    dma16_sbase(xsrc[i] + kt * GK, xoff[i], smem + buf * STAGE + BN * GPIECES + (wv * XPASS + i) * 64);
                 } else {
                     const bool kok = !KTAIL || kt * GK + vp * 8 < K;
                     uintx4 v = *reinterpret_cast<const uintx4*>(xsrc[i] + (kok ? kt * GK : -vp * 8));
