@@ -27,6 +27,8 @@
 //              to the fp32 accumulators before the fp16 store.
 #include "thi_internal.h"
 
+#include <type_traits>
+
 namespace thi {
 
 namespace {
@@ -96,10 +98,12 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
     const int ld_i = lane >> 4, ld_p = lane & 15;
 
     // ---- issue the global loads of one unit --------------------------------
+    // Every load is unconditional (no control flow around it, so the hardware wait counters can be
+    // reasoned about exactly): addresses that would fall outside the matrix are redirected to a valid
+    // element of the same row and the value is replaced by zero when the unit is consumed.
     auto issue = [&](int u, UnitRegs<MT>& r) {
         const int t = u / kch;
         const int k0 = (u - t * kch) * SK_KC;
-        const bool full = (k0 + SK_KC <= K);
         // weights
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
@@ -116,22 +120,36 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
 #pragma unroll
             for (int ph = 0; ph < 2; ++ph) {
                 const int k = k0 + ph * 128 + ld_p * 8;
-                if (full || k < K) r.w[ph * 4 + jj] = ld_stream(base + k);
-                else r.w[ph * 4 + jj] = uintx4{0u, 0u, 0u, 0u};
+                r.w[ph * 4 + jj] = ld_stream(base + (k < K ? k : 0));
             }
         }
         // activations (+ gamma)
         const int kx = k0 + wv * 32 + st_g * 8;
+        const int kxc = kx < K ? kx : 0;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             const int m = mt * 16 + st_c;
-            if (m < a.M && kx < K) r.x[mt] = ld_cached(a.x + (size_t)m * K + kx);
-            else r.x[mt] = uintx4{0u, 0u, 0u, 0u};
+            r.x[mt] = ld_cached(a.x + (size_t)(m < a.M ? m : a.M - 1) * K + kxc);
         }
-        if (is_rms(EPI)) {
-            if (kx < K) r.g = ld_cached(a.gamma + kx);
-            else r.g = uintx4{0u, 0u, 0u, 0u};
+        if (is_rms(EPI)) r.g = ld_cached(a.gamma + kxc);
+    };
+    // zero what `issue` loaded from a redirected address
+    auto mask_unit = [&](int u, UnitRegs<MT>& r) {
+        const uintx4 zero4 = {0u, 0u, 0u, 0u};
+        const int t = u / kch;
+        const int k0 = (u - t * kch) * SK_KC;
+        if (k0 + SK_KC > K) {
+#pragma unroll
+            for (int ph = 0; ph < 2; ++ph)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj)
+                    if (k0 + ph * 128 + ld_p * 8 >= K) r.w[ph * 4 + jj] = zero4;
         }
+        const bool kok = k0 + wv * 32 + st_g * 8 < K;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+            if (!kok || mt * 16 + st_c >= a.M) r.x[mt] = zero4;
+        if (is_rms(EPI) && !kok) r.g = zero4;
     };
 
     floatx4 acc[MT];
@@ -144,9 +162,12 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
     int run_start = u_begin;         // first unit of the current tile run
     int buf = 0;
 
-    for (int u = u_begin; u < u_end; ++u) {
+    // One unit.  HAS_NEXT is a compile-time fact so that the prefetch sits in straight-line code: the
+    // wait for the current unit's loads then leaves exactly the prefetched unit's loads in flight.
+    auto step = [&](int u, auto has_next) {
         UnitRegs<MT> cur = nxt;
-        if (u + 1 < u_end) issue(u + 1, nxt);
+        if constexpr (decltype(has_next)::value) issue(u + 1, nxt);
+        mask_unit(u, cur);
 
         const int t = u / kch;
         // ---- stage activations (apply gamma, accumulate sum of squares) -----
@@ -187,7 +208,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
 
         // ---- end of this workgroup's run over tile t? ------------------------
         const bool run_ends = (u + 1 == u_end) || ((u + 1) % kch == 0);
-        if (!run_ends) continue;
+        if (!run_ends) return;
 
         const int tile_begin = t * kch;
         const bool whole = ((run_start == tile_begin) && (u + 1 == tile_begin + kch));
@@ -353,7 +374,9 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
         for (int mt = 0; mt < MT; ++mt) { acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f}; ssq[mt] = 0.f; }
         run_start = u + 1;
         // s_red / s_ssq / s_flag are rewritten only after the next __syncthreads of the unit loop
-    }
+    };
+    for (int u = u_begin; u + 1 < u_end; ++u) step(u, std::true_type{});
+    step(u_end - 1, std::false_type{});
 }
 
 template <int MT>
