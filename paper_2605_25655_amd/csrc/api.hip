@@ -36,33 +36,32 @@ inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Workspace {
     unsigned* counters;
     float* ssq;
+    unsigned* handover;
     float* partials;
     uint16_t* h;
 };
 
-// one region serves both kernel families (either may be forced for any M)
-size_t partial_region_bytes(int M)
-{
-    const size_t sk = skinny_partial_bytes(M < SKINNY_GROUP ? M : SKINNY_GROUP), ge = gemm_partial_bytes();
-    return sk > ge ? sk : ge;
-}
+// Both kernel families keep their own regions (either may be forced for any M, and the decode
+// kernels' hand-over slots must stay in their "empty" state between calls).
+size_t fixed_bytes() { return WS_COUNTER_BYTES + WS_SSQ_BYTES + round_up(skinny_handover_bytes(), 256); }
 
 size_t workspace_need(int op, int M, int a, int b)
 {
-    size_t need = WS_COUNTER_BYTES + WS_SSQ_BYTES + partial_region_bytes(M);
+    size_t need = fixed_bytes() + gemm_partial_bytes();
     if (op == THI_OP_SWIGLU_MLP) need += round_up((size_t)M * (size_t)b * 2, 256);
     (void)a;
     return need;
 }
 
-Workspace carve(void* base, int M)
+Workspace carve(void* base)
 {
     char* p = static_cast<char*>(base);
     Workspace w;
     w.counters = reinterpret_cast<unsigned*>(p);
     w.ssq = reinterpret_cast<float*>(p + WS_COUNTER_BYTES);
-    w.partials = reinterpret_cast<float*>(p + WS_COUNTER_BYTES + WS_SSQ_BYTES);
-    w.h = reinterpret_cast<uint16_t*>(p + WS_COUNTER_BYTES + WS_SSQ_BYTES + partial_region_bytes(M));
+    w.handover = reinterpret_cast<unsigned*>(p + WS_COUNTER_BYTES + WS_SSQ_BYTES);
+    w.partials = reinterpret_cast<float*>(p + fixed_bytes());
+    w.h = reinterpret_cast<uint16_t*>(p + fixed_bytes() + gemm_partial_bytes());
     return w;
 }
 
@@ -91,8 +90,7 @@ int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const ui
             a.w0 = w0;
             a.w1 = w1;
             a.out = out + (size_t)m0 * ldo;
-            a.partials = ws.partials;
-            a.ssq = ws.ssq;
+            a.handover = ws.handover;
             a.counters = ws.counters;
             a.M = (M - m0 < SKINNY_GROUP) ? M - m0 : SKINNY_GROUP;
             a.N = N;
@@ -150,7 +148,7 @@ int thi_rmsnorm_qkv(const void* x, const void* gamma, float eps, const void* w_q
     int rc = check_common(M, N, K, workspace, workspace_bytes, workspace_need(THI_OP_RMSNORM_QKV, M, N, K));
     if (rc != THI_OK) return rc;
     if (misaligned(x, 16) || misaligned(gamma, 16) || misaligned(w_qkv, 16) || misaligned(out, 16)) return THI_ERR_ALIGN;
-    Workspace ws = carve(workspace, M);
+    Workspace ws = carve(workspace);
     return run_projection((const uint16_t*)x, (const uint16_t*)gamma, eps, (const uint16_t*)w_qkv, nullptr,
                           (uint16_t*)out, M, N, K, N, EPI_RMSNORM, ws, (hipStream_t)hip_stream);
 }
@@ -166,7 +164,7 @@ int thi_rmsnorm_qkv_rope(const void* x, const void* gamma, float eps, const void
     if (misaligned(x, 16) || misaligned(gamma, 16) || misaligned(w_qkv, 16) || misaligned(out, 16) ||
         misaligned(positions, 4) || misaligned(theta, 4))
         return THI_ERR_ALIGN;
-    Workspace ws = carve(workspace, M);
+    Workspace ws = carve(workspace);
     return run_projection((const uint16_t*)x, (const uint16_t*)gamma, eps, (const uint16_t*)w_qkv, nullptr,
                           (uint16_t*)out, M, N, K, N, EPI_RMSNORM_ROPE, ws, (hipStream_t)hip_stream,
                           RopeArgs{positions, theta, n_rot, head_dim});
@@ -179,7 +177,7 @@ int thi_linear(const void* x, const void* w, void* out, int M, int N, int K,
     int rc = check_common(M, N, K, workspace, workspace_bytes, workspace_need(THI_OP_LINEAR, M, N, K));
     if (rc != THI_OK) return rc;
     if (misaligned(x, 16) || misaligned(w, 16) || misaligned(out, 16)) return THI_ERR_ALIGN;
-    Workspace ws = carve(workspace, M);
+    Workspace ws = carve(workspace);
     return run_projection((const uint16_t*)x, nullptr, 0.f, (const uint16_t*)w, nullptr, (uint16_t*)out,
                           M, N, K, N, EPI_PLAIN, ws, (hipStream_t)hip_stream);
 }
@@ -194,7 +192,7 @@ int thi_swiglu_mlp(const void* x, const void* w_gate, const void* w_up, const vo
     if (misaligned(x, 16) || misaligned(w_gate, 16) || misaligned(w_up, 16) || misaligned(w_down, 16) ||
         misaligned(out, 16))
         return THI_ERR_ALIGN;
-    Workspace ws = carve(workspace, M);
+    Workspace ws = carve(workspace);
     hipStream_t stream = (hipStream_t)hip_stream;
     rc = run_projection((const uint16_t*)x, nullptr, 0.f, (const uint16_t*)w_gate, (const uint16_t*)w_up, ws.h,
                         M, I, H, I, EPI_SWIGLU, ws, stream);
@@ -211,7 +209,7 @@ int thi_swiglu_gate_up(const void* x, const void* w_gate, const void* w_up, void
     int rc = check_common(M, H, H, workspace, workspace_bytes, workspace_need(THI_OP_SWIGLU_MLP, M, H, I));
     if (rc != THI_OK) return rc;
     if (misaligned(x, 16) || misaligned(w_gate, 16) || misaligned(w_up, 16) || misaligned(h, 16)) return THI_ERR_ALIGN;
-    Workspace ws = carve(workspace, M);
+    Workspace ws = carve(workspace);
     return run_projection((const uint16_t*)x, nullptr, 0.f, (const uint16_t*)w_gate, (const uint16_t*)w_up,
                           (uint16_t*)h, M, I, H, I, EPI_SWIGLU, ws, (hipStream_t)hip_stream);
 }
@@ -227,8 +225,11 @@ int thi_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream
 {
     if (!workspace) return THI_ERR_NULL;
     if (misaligned(workspace, 256)) return THI_ERR_ALIGN;
-    if (workspace_bytes < WS_COUNTER_BYTES) return THI_ERR_WORKSPACE;
-    return launch_fill_zero(workspace, WS_COUNTER_BYTES, (hipStream_t)hip_stream) == hipSuccess ? THI_OK : THI_ERR_HIP;
+    if (workspace_bytes < fixed_bytes()) return THI_ERR_WORKSPACE;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (launch_fill_words(workspace, WS_COUNTER_BYTES, 0u, stream) != hipSuccess) return THI_ERR_HIP;
+    Workspace ws = carve(workspace);
+    return launch_fill_words(ws.handover, skinny_handover_bytes(), HANDOVER_EMPTY, stream) == hipSuccess ? THI_OK : THI_ERR_HIP;
 }
 
 const char* thi_status_string(int status)

@@ -47,6 +47,12 @@ __device__ __forceinline__ float silu_mul(float g, float u) {
     return g / (1.0f + __expf(-g)) * u;
 }
 
+// a partial sum as it travels through a hand-over slot: any bit pattern but the "empty" one
+__device__ __forceinline__ unsigned handover_word(float v) {
+    const unsigned b = __builtin_bit_cast(unsigned, v);
+    return b == HANDOVER_EMPTY ? 0x7fc00000u : b;      // both are NaNs
+}
+
 __device__ __forceinline__ uint16_t to_half_bits(float v) {
     _Float16 h = (_Float16)v;   // round-to-nearest-even
     return __builtin_bit_cast(uint16_t, h);
@@ -77,7 +83,6 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
     __shared__ uintx4 wt[SK_WAVES][WT_UNITS];      // wave-private transposition buffers
     __shared__ float s_red[SK_WAVES][32];
     __shared__ float s_ssq[32];
-    __shared__ unsigned s_flag;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -236,104 +241,111 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
         // ---- a tile shared by several workgroups ----------------------------------------------
         // Shares are contiguous, so the workgroup that owns the tile's first k chunk (w_first)
         // reaches the tile at the END of its share, every other contributor at the START of its
-        // own.  The others hand in their partial tile (device-coherent stores, then a flag once
-        // the stores are acknowledged) and move on; w_first keeps its part in registers, waits
-        // for the flags -- normally long set -- and adds the partials in workgroup order.
+        // own.  The others write their partial tile into their hand-over slot and move on; w_first
+        // keeps its part in registers and adds the partials in workgroup order.  There is no flag:
+        // a slot holds HANDOVER_EMPTY in every word between uses, a contributor never writes that
+        // value, and the finisher re-reads a slot until none of its words is empty, then empties
+        // the words it took.  Every word vouches for itself, so no ordering between the stores is
+        // needed and the hand-over costs one store and one load across the chip.
         bool finish = whole;
         if (!whole) {
             const int w_first = deal.owner(tile_begin);
             const int w_last = deal.owner(tile_begin + kch - 1);
-            constexpr int SLOT_FLOATS = SK_WAVES * MT * 4 * 64;
+            const bool lane_ssq = is_rms(EPI) && tid < 32;
             if (wg != w_first) {
-                float* ps = a.partials + (size_t)wg * SLOT_FLOATS;
+                unsigned* ps = a.handover + (size_t)wg * SK_SLOT_WORDS;
                 // only the lanes that hold a real token (column c = lane % 16 of token tile mt) take part
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
                     if (mt * 16 + (lane & 15) < a.M)
 #pragma unroll
                         for (int i = 0; i < 4; ++i)
-                            __hip_atomic_store(ps + ((wv * MT + mt) * 4 + i) * 64 + lane, acc[mt][i],
+                            __hip_atomic_store(ps + ((wv * 2 + mt) * 4 + i) * 64 + lane, handover_word(acc[mt][i]),
                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (is_rms(EPI) && tid < 32)
-                    __hip_atomic_store(a.ssq + (size_t)wg * 32 + tid, s_ssq[tid], __ATOMIC_RELAXED,
+                if (lane_ssq)
+                    __hip_atomic_store(ps + SK_SLOT_SSQ + tid, handover_word(s_ssq[tid]), __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
-                // every thread waits until its write-through stores are acknowledged (a workgroup-scope
-                // fence alone does not wait for that); only then may the flag go up
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                __syncthreads();
-                if (tid == 0)
-                    __hip_atomic_store(a.counters + wg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             } else {
-                if (wv == 0) {
-                    // wave 0 polls the flags, one contributor per lane, so the round trips overlap
-                    unsigned ok = 1u;
-                    for (int wc0 = w_first + 1; wc0 <= w_last; wc0 += 64) {
-                        const int wc = wc0 + lane;
-                        const bool mine = wc <= w_last;
-                        unsigned spins = 0;
-                        bool seen = !mine;
-                        while (true) {
-                            if (!seen)
-                                seen = __hip_atomic_load(a.counters + wc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
-                            if (__builtin_amdgcn_ballot_w64(!seen) == 0ull) break;
-                            __builtin_amdgcn_s_sleep(1);
-                            if (++spins > SK_SPIN_LIMIT) { ok = 0u; break; }      // bounded: every wave exits
-                        }
-                        if (mine && seen)
-                            __hip_atomic_store(a.counters + wc, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                float sq = lane_ssq ? s_ssq[tid] : 0.f;
+                bool ok = true;
+                // four contributors at a time so that the round trips overlap
+                for (int wc0 = w_first + 1; wc0 <= w_last && ok; wc0 += 4) {
+                    unsigned pv[4][MT][4];
+                    unsigned ps4[4];
+                    unsigned spins = 0;
+                    // light wait first: lane b watches one word of contributor b's slot (the last one this
+                    // wave's part of it receives); the full read below then nearly always succeeds at once
+                    while (true) {
+                        bool waiting = false;
+                        if (lane < 4 && wc0 + lane <= w_last)
+                            waiting = __hip_atomic_load(a.handover + (size_t)(wc0 + lane) * SK_SLOT_WORDS +
+                                                            ((wv * 2 + MT - 1) * 4 + 3) * 64,
+                                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == HANDOVER_EMPTY;
+                        if (__builtin_amdgcn_ballot_w64(waiting) == 0ull) break;
+                        __builtin_amdgcn_s_sleep(1);
+                        if (++spins > SK_SPIN_LIMIT) { ok = false; break; }      // bounded: every wave exits
                     }
-                    if (lane == 0) {
-                        if (!ok) __hip_atomic_store(a.counters + (WS_MAX_COUNTERS - 1), 1u, __ATOMIC_RELAXED,
-                                                    __HIP_MEMORY_SCOPE_AGENT);
-                        s_flag = ok;
-                    }
-                }
-                __syncthreads();
-                finish = (s_flag != 0u);
-                if (finish) {
-                    float sq = (is_rms(EPI) && tid < 32) ? s_ssq[tid] : 0.f;
-                    // loads are issued four contributors at a time so the round trips overlap
-                    for (int wc0 = w_first + 1; wc0 <= w_last; wc0 += 4) {
-                        float pv[4][MT][4];
-                        float ps4[4];
+                    if (!ok) break;
+                    while (true) {
+                        // all loads first (their round trips overlap), the checks afterwards
 #pragma unroll
                         for (int b = 0; b < 4; ++b) {
                             const int wc = wc0 + b;
-                            if (wc <= w_last) {
-                                const float* cs = a.partials + (size_t)wc * SLOT_FLOATS;
+                            const unsigned* cs = a.handover + (size_t)(wc <= w_last ? wc : w_last) * SK_SLOT_WORDS;
 #pragma unroll
-                                for (int mt = 0; mt < MT; ++mt)
+                            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                                    for (int i = 0; i < 4; ++i)
-                                        pv[b][mt][i] = (mt * 16 + (lane & 15) < a.M)
-                                            ? __hip_atomic_load(cs + ((wv * MT + mt) * 4 + i) * 64 + lane,
-                                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                                            : 0.f;
-                                if (is_rms(EPI) && tid < 32)
-                                    ps4[b] = __hip_atomic_load(a.ssq + (size_t)wc * 32 + tid, __ATOMIC_RELAXED,
-                                                               __HIP_MEMORY_SCOPE_AGENT);
-                            } else {
-#pragma unroll
-                                for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                                    for (int i = 0; i < 4; ++i) pv[b][mt][i] = 0.f;
-                                ps4[b] = 0.f;
-                            }
+                                for (int i = 0; i < 4; ++i)
+                                    pv[b][mt][i] = (wc <= w_last && mt * 16 + (lane & 15) < a.M)
+                                        ? __hip_atomic_load(cs + ((wv * 2 + mt) * 4 + i) * 64 + lane, __ATOMIC_RELAXED,
+                                                            __HIP_MEMORY_SCOPE_AGENT)
+                                        : 0u;      // +0.0f
+                            ps4[b] = (wc <= w_last && lane_ssq)
+                                ? __hip_atomic_load(cs + SK_SLOT_SSQ + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                : 0u;
                         }
+                        bool empty = false;
 #pragma unroll
                         for (int b = 0; b < 4; ++b) {
 #pragma unroll
                             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                                for (int i = 0; i < 4; ++i) acc[mt][i] += pv[b][mt][i];
-                            if (is_rms(EPI) && tid < 32) sq += ps4[b];
+                                for (int i = 0; i < 4; ++i) empty |= (pv[b][mt][i] == HANDOVER_EMPTY);
+                            empty |= (ps4[b] == HANDOVER_EMPTY);
+                        }
+                        if (__builtin_amdgcn_ballot_w64(empty) == 0ull) break;
+                        __builtin_amdgcn_s_sleep(2);
+                        if (++spins > SK_SPIN_LIMIT) { ok = false; break; }      // bounded: every wave exits
+                    }
+                    if (!ok) break;
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const int wc = wc0 + b;
+                        if (wc > w_last) continue;
+                        unsigned* cs = a.handover + (size_t)wc * SK_SLOT_WORDS;
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+                            if (mt * 16 + (lane & 15) < a.M)
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) {
+                                    acc[mt][i] += __builtin_bit_cast(float, pv[b][mt][i]);
+                                    __hip_atomic_store(cs + ((wv * 2 + mt) * 4 + i) * 64 + lane, HANDOVER_EMPTY,
+                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                }
+                        if (lane_ssq) {
+                            sq += __builtin_bit_cast(float, ps4[b]);
+                            __hip_atomic_store(cs + SK_SLOT_SSQ + tid, HANDOVER_EMPTY, __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_AGENT);
                         }
                     }
-                    if (is_rms(EPI)) {
-                        __syncthreads();
-                        if (tid < 32) s_ssq[tid] = sq;
-                        __syncthreads();
-                    }
+                }
+                if (!ok && lane == 0)
+                    __hip_atomic_store(a.counters + (WS_MAX_COUNTERS - 1), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                finish = ok;
+                if (is_rms(EPI)) {
+                    __syncthreads();
+                    if (tid < 32) s_ssq[tid] = sq;
+                    __syncthreads();
                 }
             }
         }
@@ -392,20 +404,16 @@ hipError_t launch_mt(const SkinnyArgs& a, int epilogue, int grid, hipStream_t st
     return hipGetLastError();
 }
 
-__global__ void fill_zero_kernel(uint32_t* p, size_t words)
+__global__ void fill_words_kernel(uint32_t* p, size_t words, uint32_t value)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (; i < words; i += stride) p[i] = 0u;
+    for (; i < words; i += stride) p[i] = value;
 }
 
 }  // namespace
 
-size_t skinny_partial_bytes(int M)
-{
-    const int mt = (M <= 16) ? 1 : 2;
-    return (size_t)SK_MAX_GRID * 2 * (SK_WAVES * mt * 4 * 64) * sizeof(float);
-}
+size_t skinny_handover_bytes() { return (size_t)SK_MAX_GRID * SK_SLOT_WORDS * sizeof(unsigned); }
 
 hipError_t launch_skinny(const SkinnyArgs& a, int epilogue, int num_cus, hipStream_t stream)
 {
@@ -419,13 +427,13 @@ hipError_t launch_skinny(const SkinnyArgs& a, int epilogue, int num_cus, hipStre
     return launch_mt<2>(a, epilogue, (int)grid, stream);
 }
 
-hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream)
+hipError_t launch_fill_words(void* ptr, size_t bytes, uint32_t value, hipStream_t stream)
 {
     const size_t words = bytes / 4;
     int blocks = (int)((words + 255) / 256);
     if (blocks > 1024) blocks = 1024;
     if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, stream, (uint32_t*)ptr, words);
+    hipLaunchKernelGGL(fill_words_kernel, dim3(blocks), dim3(256), 0, stream, (uint32_t*)ptr, words, value);
     return hipGetLastError();
 }
 
