@@ -152,7 +152,9 @@ int thi_version(void);
 /*
  * Tuning/diagnostic hook used by the benchmark and tests: force a kernel
  * family for subsequent calls from this process.  family: 0 = automatic
- * (default), 1 = weight-streaming skinny kernels, 2 = MFMA GEMM kernels.
+ * (default), 1 = weight-streaming decode kernel with stream-K units,
+ * 2 = MFMA GEMM kernels, 3 = weight-streaming decode kernel with row slabs
+ * (falls back to 1 where K < 1024).
  * Returns the previous setting.  Not needed for normal use.
  */
 int thi_set_kernel_family(int family);

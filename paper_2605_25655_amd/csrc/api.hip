@@ -68,9 +68,36 @@ Workspace carve(void* base)
 bool use_skinny(int M)
 {
     const int fam = g_family.load(std::memory_order_relaxed);
-    if (fam == 1) return true;
+    if (fam == 1 || fam == 3) return true;
     if (fam == 2) return false;
     return M <= SKINNY_MAX_M;
+}
+
+// Decode: row slabs (no hand-over between workgroups, but every workgroup reads all of x and the
+// slabs must divide well among the compute units) or stream-K units (perfect balance, a hand-over at
+// the end)?  Decided by a time model in microseconds whose constants were measured on MI355X:
+//   both stream the weights at ~7.0 TB/s;
+//   row slabs : ~2.5 us fixed; slowed by the slots a ragged last round leaves empty, by a last unit
+//               of a wave that is only partly full, by the activation traffic (x1.02 at M<=4, x1.07
+//               at M<=8, x1.28 at M<=16, x2.0 above) and by ~5 % for the RMSNorm prologue;
+//   stream-K  : ~5.5 us fixed plus the hand-over, 0.5 + 0.05 M us up to M = 16 and ~5 us above.
+bool use_rowslab(int M, int N, int K, int epilogue, int cus)
+{
+    if (K < 1024 || K > ROWSLAB_MAX_K) return false;
+    const int fam = g_family.load(std::memory_order_relaxed);
+    if (fam == 3) return true;
+    if (fam == 1) return false;
+    const bool swiglu = (epilogue == EPI_SWIGLU);
+    const double t_w = (swiglu ? 2.0 : 1.0) * (double)N * (double)K * 2.0 / 7.0e6;
+    const long slabs = ((long)N + (swiglu ? 7 : 15)) / (swiglu ? 8 : 16);
+    const long rounds = (slabs + cus - 1) / cus;
+    const double fill = (double)slabs / (double)(rounds * cus);
+    const int groups = (K + 127) / 128, groups_max = (groups + 7) / 8, units_max = (groups_max + 1) / 2;
+    const double ragged = (double)units_max * SK_KC * SK_WAVES / (double)K;
+    const double x_cost = M <= 1 ? 1.0 : M <= 4 ? 1.02 : M <= 8 ? 1.07 : M <= 16 ? 1.28 : 2.0;
+    const double t_slab = 2.5 + t_w * x_cost * (ragged > 1.0 ? ragged : 1.0) / fill * (is_rms(epilogue) ? 1.05 : 1.0);
+    const double t_sk = 5.5 + t_w + (M <= 16 ? 0.5 + 0.05 * M : 5.0);
+    return t_slab < t_sk;
 }
 
 // One fused projection: out[M, ldo] = epilogue( prologue(x)[M,K] * w^T ), any M.
@@ -80,9 +107,10 @@ int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const ui
 {
     const int cus = device_cu_count();
     if (use_skinny(M)) {
-        const int rows_per_tile = (epilogue == EPI_SWIGLU) ? SK_ROWS / 2 : SK_ROWS;
+        const bool slab = use_rowslab(M < SKINNY_GROUP ? M : SKINNY_GROUP, N, K, epilogue, cus);
+        const int rows_per_tile = slab ? ((epilogue == EPI_SWIGLU) ? 8 : 16) : ((epilogue == EPI_SWIGLU) ? SK_ROWS / 2 : SK_ROWS);
         const int tiles = (N + rows_per_tile - 1) / rows_per_tile;
-        if (tiles > WS_MAX_COUNTERS || (long)tiles * ((K + SK_KC - 1) / SK_KC) > (1L << 30)) return THI_ERR_SHAPE;
+        if ((long)tiles * ((K + SK_KC - 1) / SK_KC) > (1L << 30)) return THI_ERR_SHAPE;
         for (int m0 = 0; m0 < M; m0 += SKINNY_GROUP) {
             SkinnyArgs a;
             a.x = x + (size_t)m0 * K;
@@ -101,7 +129,8 @@ int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const ui
             a.eps = eps;
             a.rope = rope;
             if (rope.pos) a.rope.pos = rope.pos + m0;
-            if (launch_skinny(a, epilogue, cus, stream) != hipSuccess) return THI_ERR_HIP;
+            if ((slab ? launch_rowslab(a, epilogue, cus, stream) : launch_skinny(a, epilogue, cus, stream)) != hipSuccess)
+                return THI_ERR_HIP;
         }
         return THI_OK;
     }
@@ -249,7 +278,7 @@ int thi_version(void) { return THI_VERSION; }
 
 int thi_set_kernel_family(int family)
 {
-    if (family < 0 || family > 2) family = 0;
+    if (family < 0 || family > 3) family = 0;
     return g_family.exchange(family);
 }
 

@@ -1,0 +1,292 @@
+// Row-slab decode kernel (M <= 32 tokens per launch) on gfx950: weight streaming with no
+// workgroup-to-workgroup hand-over.
+//
+// The paper's small-M rule (Sec. III-B.2: broadcast X, split the work along N) taken literally:
+// a workgroup owns a slab of 16 output features over the WHOLE reduction dimension, so nothing is
+// shared between workgroups.  Inside the workgroup the k range is cut into eight contiguous pieces,
+// one per wave; a wave streams its 16 rows x (K/8) k of weights in units of 256 k with fully
+// coalesced 16-byte loads (one or two units ahead of the arithmetic), passes them through a wave-private
+// LDS buffer to reach the MFMA operand layout, and takes its slice of the activations straight from
+// memory in operand layout (they stay cache resident: every workgroup reads the same M x K block).
+// The eight partial tiles meet in LDS, are added in wave order (reproducible) and finished by the
+// fused epilogue (Sec. III-C.1: RMSNorm scale, rotary embedding, SwiGLU).
+//
+// Chosen over the stream-K kernel when the slabs divide evenly enough among the compute units:
+// there the hand-over between workgroups (several microseconds across the chip) is the larger loss.
+#include "thi_internal.h"
+
+#include <type_traits>
+
+namespace thi {
+
+namespace {
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+template <int MT, int EPI>
+__global__ __launch_bounds__(SK_THREADS) void skinny_rowslab(SkinnyArgs a)
+{
+    __shared__ uintx4 wt[SK_WAVES][WT_UNITS];          // wave-private transposition buffers
+    __shared__ float s_part[SK_WAVES][MT * 4 * 64];    // the waves' partial tiles
+    __shared__ float s_sum[32][17];                    // finished sums [token][row]
+    __shared__ float s_red[SK_WAVES][32];
+    __shared__ float s_ssq[32];
+    extern __shared__ uintx4 s_gamma[];                // RMSNorm: each wave's slice of gamma
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int G = gridDim.x;
+    const int K = a.K;
+
+    // this wave's k range: whole groups of 128 k, so that every range starts on a 256-byte boundary of
+    // its rows (K >= 1024: every wave has at least one group)
+    const int S4 = (K + 127) >> 7;
+    const int k_begin = ((wv * S4) >> 3) * 128;
+    const int k_stop = (((wv + 1) * S4) >> 3) * 128;
+    const int k_end = k_stop < K ? k_stop : K;
+    const int nU = (k_end - k_begin + SK_KC - 1) / SK_KC;            // units of 256 k per slab
+    const int n_slabs = (a.tiles - (int)blockIdx.x + G - 1) / G;     // slabs of this workgroup
+    const int total = n_slabs * nU;
+
+    // RMSNorm: this wave's slice of gamma goes to LDS once (wave-private: no workgroup barrier)
+    const int g_pieces = (((S4 >> 3) + 1) * 128) >> 3;               // 16-byte pieces reserved per wave
+    if (is_rms(EPI)) {
+        for (int p = lane; p * 8 < k_end - k_begin; p += 64)
+            s_gamma[wv * g_pieces + p] = ld_cached(a.gamma + k_begin + p * 8);
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    // weight-load role: load jj of a phase covers MFMA rows 4*jj + lane/16, piece lane%16
+    const int ld_i = lane >> 4, ld_p = lane & 15;
+    // operand role: token column c, k group kg
+    const int c = lane & 15, kg = lane >> 4;
+    const uintx4 zero4 = {0u, 0u, 0u, 0u};
+
+    // row pointers of a slab for this lane's four load rows
+    auto row_base = [&](int slab, int jj) -> const uint16_t* {
+        const int v = 4 * jj + ld_i;                   // virtual row within the slab
+        if (EPI == EPI_SWIGLU) {
+            int j = slab * 8 + (v & 7);
+            j = j < a.N ? j : a.N - 1;
+            return ((v >> 3) ? a.w1 : a.w0) + (size_t)j * K;
+        }
+        int n = slab * 16 + v;
+        n = n < a.N ? n : a.N - 1;
+        return a.w0 + (size_t)n * K;
+    };
+    // Every load is unconditional; one that would leave the wave's k range is redirected to the first
+    // piece of the unit (same cache line as a neighbour's load) and zeroed when the unit is consumed.
+    // A prefetch past the workgroup's last unit (valid = false) sends every lane to the first piece of
+    // its row (a few cached sectors, no traffic to speak of): the code stays free of branches around
+    // loads, which keeps the hardware wait counters exact.
+    auto issue_w = [&](int slab, int uu, bool valid, uintx4 (&w)[8]) {
+        const int k0 = k_begin + uu * SK_KC;
+        const int k_lim = valid ? k_end : 0;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const uint16_t* base = row_base(slab, jj);
+#pragma unroll
+            for (int ph = 0; ph < 2; ++ph) {
+                const int k = k0 + ph * 128 + ld_p * 8;
+                w[ph * 4 + jj] = ld_stream(base + (k < k_lim ? k : k0));
+            }
+        }
+    };
+
+    floatx4 acc[MT];
+    float ssq[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) { acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f}; ssq[mt] = 0.f; }
+
+    // PD units of weights are in flight ahead of the one being consumed (register buffers in rotation)
+    constexpr int PD = 1;
+    int slab = blockIdx.x, uu = 0;           // the unit being consumed
+    int p_slab = blockIdx.x, p_uu = 0;       // the unit last requested
+    int requested = 1;
+    uintx4 wb0[8], wb1[8], wb2[PD == 2 ? 8 : 1];
+    issue_w(p_slab, p_uu, true, wb0);
+    if (PD == 2) {
+        if (++p_uu == nU) { p_uu = 0; p_slab += G; }
+        issue_w(p_slab, p_uu, requested < total, wb1);
+        ++requested;
+    }
+
+    auto step = [&](uintx4 (&cur)[8], uintx4 (&pre)[8]) {
+        const int k0 = k_begin + uu * SK_KC;
+        const bool first_slab = (slab == (int)blockIdx.x);
+
+        // activations (and gamma) of this unit, in operand layout; issued before the prefetch so that
+        // waiting for them leaves the prefetched weights in flight
+        uintx4 xr[8][MT];
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const int kx = k0 + s * 32 + kg * 8;
+            const int kxc = kx < k_end ? kx : k0;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const int m = mt * 16 + c;
+                xr[s][mt] = ld_cached(a.x + (size_t)(m < a.M ? m : a.M - 1) * K + kxc);
+            }
+        }
+        if (++p_uu == nU) { p_uu = 0; p_slab += G; }
+        issue_w(p_slab, p_uu, requested < total, pre);
+        ++requested;
+
+        // zero what came from a redirected address
+        if (k0 + SK_KC > k_end) {
+#pragma unroll
+            for (int ph = 0; ph < 2; ++ph)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj)
+                    if (k0 + ph * 128 + ld_p * 8 >= k_end) cur[ph * 4 + jj] = zero4;
+        }
+
+#pragma unroll
+        for (int ph = 0; ph < 2; ++ph) {
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) wt[wv][(4 * jj + ld_i) * WT_STRIDE + ld_p] = cur[ph * 4 + jj];
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) {
+                const int s = ph * 4 + s4;
+                half8 wa = __builtin_bit_cast(half8, wt[wv][c * WT_STRIDE + 4 * s4 + kg]);
+                const bool kok = k0 + s * 32 + kg * 8 < k_end;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    uintx4 xv = (kok && mt * 16 + c < a.M) ? xr[s][mt] : zero4;
+                    if (is_rms(EPI)) {
+                        half8 xh = __builtin_bit_cast(half8, xv);
+                        half8 gh = __builtin_bit_cast(half8, s_gamma[wv * g_pieces + (((kok ? k0 + s * 32 : k_begin) - k_begin) >> 3) + (kok ? kg : 0)]);
+                        if (first_slab) {      // the same x serves every slab: its sum of squares is taken once
+#pragma unroll
+                            for (int e = 0; e < 8; e += 2) {
+                                const half2_t h2 = {xh[e], xh[e + 1]};
+                                ssq[mt] = __builtin_amdgcn_fdot2(h2, h2, ssq[mt], false);
+                            }
+                        }
+                        half8 p = xh * gh;       // one rounding: the fp16 product of two fp16 values
+                        xv = kok ? __builtin_bit_cast(uintx4, p) : zero4;
+                    }
+                    acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wa, __builtin_bit_cast(half8, xv), acc[mt], 0, 0, 0);
+                }
+            }
+        }
+
+        const bool slab_ends = (uu + 1 == nU);
+        const int this_slab = slab;
+        if (++uu == nU) { uu = 0; slab += G; }
+        if (!slab_ends) return;
+
+        // ---- the eight partial tiles meet in LDS ---------------------------------------------------
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) s_part[wv][(mt * 4 + i) * 64 + lane] = acc[mt][i];
+            if (is_rms(EPI) && first_slab) {
+                float v = ssq[mt];
+                v += __shfl_xor(v, 16);
+                v += __shfl_xor(v, 32);
+                if (kg == 0) s_red[wv][mt * 16 + c] = v;
+            }
+            acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+        }
+        if (is_rms(EPI) && first_slab && MT == 1 && kg == 0) s_red[wv][16 + c] = 0.f;
+        __syncthreads();
+        if (tid < MT * 256) {
+            // fixed order: waves 0..7
+            float v = 0.f;
+#pragma unroll
+            for (int w = 0; w < SK_WAVES; ++w) v += s_part[w][tid];
+            const int l = tid & 63, i = (tid >> 6) & 3, mt = tid >> 8;
+            s_sum[mt * 16 + (l & 15)][4 * (l >> 4) + i] = v;
+        }
+        if (is_rms(EPI) && first_slab && tid < 32) {      // kept in s_ssq for the later slabs
+            float v = 0.f;
+#pragma unroll
+            for (int w = 0; w < SK_WAVES; ++w) v += s_red[w][tid];
+            s_ssq[tid] = v;
+        }
+        __syncthreads();
+
+        // ---- epilogue: thread -> (token m, row r) ----------------------------------------------------
+        const int r = tid & 15, m = tid >> 4;
+        if (m < a.M) {
+            if (EPI == EPI_SWIGLU) {
+                const int j = this_slab * 8 + r;
+                if (r < 8 && j < a.N) a.out[(size_t)m * a.ldo + j] = to_half_bits(silu_mul(s_sum[m][r], s_sum[m][r + 8]));
+            } else {
+                float scale = 1.0f;
+                if (is_rms(EPI)) scale = 1.0f / __builtin_sqrtf(s_ssq[m] / (float)K + a.eps);
+                const int n = this_slab * 16 + r;
+                if (EPI == EPI_RMSNORM_ROPE) {
+                    if ((r & 1) == 0) {       // this thread finishes the pair (n, n + 1)
+                        float v0 = s_sum[m][r] * scale, v1 = s_sum[m][r + 1] * scale;
+                        rope_pair(a.rope, a.rope.pos[m], n, v0, v1);
+                        if (n < a.N) a.out[(size_t)m * a.ldo + n] = to_half_bits(v0);
+                        if (n + 1 < a.N) a.out[(size_t)m * a.ldo + n + 1] = to_half_bits(v1);
+                    }
+                } else if (n < a.N) {
+                    a.out[(size_t)m * a.ldo + n] = to_half_bits(s_sum[m][r] * scale);
+                }
+            }
+        }
+        // s_part / s_red are rewritten only after every thread has passed the second barrier above, and
+        // s_sum / s_ssq only after the next slab's first barrier, which follows this epilogue
+    };
+
+    if constexpr (PD == 2) {
+        for (int i = 0; i < total; i += 3) {
+            step(wb0, wb2);
+            if (i + 1 >= total) break;
+            step(wb1, wb0);
+            if (i + 2 >= total) break;
+            step(wb2, wb1);
+        }
+    } else {
+        for (int i = 0; i < total; i += 2) {
+            step(wb0, wb1);
+            if (i + 1 >= total) break;
+            step(wb1, wb0);
+        }
+    }
+}
+
+// 16-byte pieces of LDS per wave for its slice of gamma (same arithmetic as in the kernel)
+int rowslab_gamma_pieces(int K) { return ((((K + 127) >> 7) >> 3) + 1) * 128 >> 3; }
+
+template <int MT>
+hipError_t launch_mt(const SkinnyArgs& a, int epilogue, int grid, hipStream_t stream)
+{
+    dim3 g(grid), b(SK_THREADS);
+    const size_t gamma_lds = (size_t)SK_WAVES * rowslab_gamma_pieces(a.K) * sizeof(uintx4);
+    static bool attr_set = false;       // static + dynamic LDS can pass 64 KiB for large K
+    if (!attr_set) {
+        const int most = (int)((size_t)SK_WAVES * rowslab_gamma_pieces(ROWSLAB_MAX_K) * sizeof(uintx4));
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowslab<MT, EPI_RMSNORM>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, most);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowslab<MT, EPI_RMSNORM_ROPE>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, most);
+        attr_set = true;
+    }
+    switch (epilogue) {
+    case EPI_PLAIN: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_PLAIN>), g, b, 0, stream, a); break;
+    case EPI_RMSNORM: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_RMSNORM>), g, b, gamma_lds, stream, a); break;
+    case EPI_RMSNORM_ROPE: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_RMSNORM_ROPE>), g, b, gamma_lds, stream, a); break;
+    default: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_SWIGLU>), g, b, 0, stream, a); break;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_rowslab(const SkinnyArgs& a, int epilogue, int num_cus, hipStream_t stream)
+{
+    if (a.K < 1024 || a.K > ROWSLAB_MAX_K || a.tiles < 1) return hipErrorInvalidValue;
+    int grid = num_cus < a.tiles ? num_cus : a.tiles;
+    if (a.M <= 16) return launch_mt<1>(a, epilogue, grid, stream);
+    return launch_mt<2>(a, epilogue, grid, stream);
+}
+
+}  // namespace thi

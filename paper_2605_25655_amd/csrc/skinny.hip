@@ -33,29 +33,10 @@ namespace thi {
 
 namespace {
 
-constexpr int WT_STRIDE = 17;                  // 16-byte units per transposition row (256 B + 16 B pad)
-constexpr int WT_UNITS = 16 * WT_STRIDE;       // per wave
-
-__device__ __forceinline__ uintx4 ld_stream(const uint16_t* p) {
-    return __builtin_nontemporal_load(reinterpret_cast<const uintx4*>(p));
-}
-__device__ __forceinline__ uintx4 ld_cached(const uint16_t* p) {
-    return *reinterpret_cast<const uintx4*>(p);
-}
-
-__device__ __forceinline__ float silu_mul(float g, float u) {
-    return g / (1.0f + __expf(-g)) * u;
-}
-
 // a partial sum as it travels through a hand-over slot: any bit pattern but the "empty" one
 __device__ __forceinline__ unsigned handover_word(float v) {
     const unsigned b = __builtin_bit_cast(unsigned, v);
     return b == HANDOVER_EMPTY ? 0x7fc00000u : b;      // both are NaNs
-}
-
-__device__ __forceinline__ uint16_t to_half_bits(float v) {
-    _Float16 h = (_Float16)v;   // round-to-nearest-even
-    return __builtin_bit_cast(uint16_t, h);
 }
 
 // U work units are dealt to G workgroups in contiguous shares: the first `rem`
@@ -273,19 +254,6 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
                     unsigned pv[4][MT][4];
                     unsigned ps4[4];
                     unsigned spins = 0;
-                    // light wait first: lane b watches one word of contributor b's slot (the last one this
-                    // wave's part of it receives); the full read below then nearly always succeeds at once
-                    while (true) {
-                        bool waiting = false;
-                        if (lane < 4 && wc0 + lane <= w_last)
-                            waiting = __hip_atomic_load(a.handover + (size_t)(wc0 + lane) * SK_SLOT_WORDS +
-                                                            ((wv * 2 + MT - 1) * 4 + 3) * 64,
-                                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == HANDOVER_EMPTY;
-                        if (__builtin_amdgcn_ballot_w64(waiting) == 0ull) break;
-                        __builtin_amdgcn_s_sleep(1);
-                        if (++spins > SK_SPIN_LIMIT) { ok = false; break; }      // bounded: every wave exits
-                    }
-                    if (!ok) break;
                     while (true) {
                         // all loads first (their round trips overlap), the checks afterwards
 #pragma unroll

@@ -64,6 +64,10 @@ struct SkinnyArgs {
 
 size_t skinny_handover_bytes();
 hipError_t launch_skinny(const SkinnyArgs& a, int epilogue, int num_cus, hipStream_t stream);
+// Row-slab decode kernel: a.tiles = slabs of 16 virtual rows; needs 1024 <= K <= ROWSLAB_MAX_K (a
+// wave's slice of gamma must fit its share of LDS); uses no workspace.
+constexpr int ROWSLAB_MAX_K = 32768;
+hipError_t launch_rowslab(const SkinnyArgs& a, int epilogue, int num_cus, hipStream_t stream);
 
 // ---- GEMM (prefill) kernel ---------------------------------------------------
 struct GemmArgs {
@@ -95,6 +99,24 @@ __device__ __forceinline__ void rope_pair(const RopeArgs& r, int m_pos, int c, f
     const float na = a * cs - b * sn, nb = b * cs + a * sn;
     a = na;
     b = nb;
+}
+
+// ---- small device helpers shared by the decode kernels -----------------------
+constexpr int WT_STRIDE = 17;                  // 16-byte units per transposition row (256 B + 16 B pad)
+constexpr int WT_UNITS = 16 * WT_STRIDE;       // per wave
+
+__device__ __forceinline__ uintx4 ld_stream(const uint16_t* p) {      // weights: read once, keep out of the caches
+    return __builtin_nontemporal_load(reinterpret_cast<const uintx4*>(p));
+}
+__device__ __forceinline__ uintx4 ld_cached(const uint16_t* p) {
+    return *reinterpret_cast<const uintx4*>(p);
+}
+__device__ __forceinline__ float silu_mul(float g, float u) {
+    return g / (1.0f + __expf(-g)) * u;
+}
+__device__ __forceinline__ uint16_t to_half_bits(float v) {
+    _Float16 h = (_Float16)v;   // round-to-nearest-even
+    return __builtin_bit_cast(uint16_t, h);
 }
 
 hipError_t launch_fill_words(void* ptr, size_t bytes, uint32_t value, hipStream_t stream);

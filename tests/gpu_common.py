@@ -56,6 +56,11 @@ class Runner:
         self.thi.thi_swiglu_mlp(x, wg, wu, wd, out, self.ws)
         return out
 
+    def swiglu_gate_up(self, x, wg, wu):
+        out = new_out(x.shape[0], wg.shape[0])
+        self.thi.thi_swiglu_gate_up(x, wg, wu, out, self.ws)
+        return out
+
     def rmsnorm_qkv_rope(self, x, gamma, eps, w, pos, theta, n_rot, head_dim):
         out = new_out(x.shape[0], w.shape[0])
         self.thi.thi_rmsnorm_qkv_rope(x, gamma, eps, w, pos, theta, n_rot, head_dim, out, self.ws)

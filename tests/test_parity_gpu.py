@@ -111,7 +111,7 @@ def test_swiglu_odd_shapes(thi, oracle_mod, M, H, I):
     check(got, y, s, f"swiglu {M}x{H}x{I}", argmax=False)
 
 
-@pytest.mark.parametrize("family", [1, 2])
+@pytest.mark.parametrize("family", [1, 2, 3])
 @pytest.mark.parametrize("M", [1, 20, 48, 160])
 def test_both_kernel_families_cover_every_m(thi, oracle_mod, family, M):
     say(f"[case] family={family} M={M}")
@@ -215,6 +215,51 @@ def test_prefill_swiglu_schedules(thi, oracle_mod, M, H, I):
 def _theta(head_dim, base=10000.0):
     i = np.arange(head_dim // 2, dtype=np.float64)
     return (base ** (-2.0 * i / head_dim)).astype(np.float32)
+
+
+# the row-slab decode kernel: slabs of 16 rows, the k range cut among the eight waves of a workgroup
+ROWSLAB = [
+    (1, 16, 1024), (1, 1000, 1376), (3, 129, 1032), (5, 4099, 1160), (16, 384, 1800), (17, 100, 1024),
+    (32, 640, 2056), (32, 4096, 4096), (31, 513, 11008), (40, 272, 3080), (8, 23, 8200), (2, 48, 32768),
+    (4, 64, 264),       # K < 1024: served by the stream-K kernel
+]
+
+
+@pytest.mark.parametrize("M,N,K", ROWSLAB)
+def test_rowslab_kernel_all_epilogues(thi, oracle_mod, M, N, K):
+    say(f"[case] row slabs M={M} N={N} K={K}")
+    x, w, g = synth.random_problem(4200 + M * 5 + N + K, M, N, K)
+    rng = np.random.Generator(np.random.Philox(key=4300 + M + N + K))
+    I = min(N, 1376) // 8 * 8                          # gate/up rows
+    wu = f16(rng.standard_normal((I, K)) * 0.05)
+    hd = 8
+    n_rot = (N // 2) // hd * hd
+    pos = rng.integers(0, 4096, size=M).astype(np.int32)
+    th = _theta(hd)
+    r = Runner(M, K, max(I, K), N)
+    xd, wd, gd = to_dev(x), to_dev(w), to_dev(g)
+    prev = thi.thi_set_kernel_family(3)
+    try:
+        a = to_host(r.linear(xd, wd))
+        a2 = to_host(r.linear(xd, wd))
+        b = to_host(r.rmsnorm_qkv(xd, gd, 1e-6, wd))
+        c = to_host(r.rmsnorm_qkv_rope(xd, gd, 1e-6, wd, _dev_i32(pos), _dev_f32(th), n_rot, hd))
+        h = to_host(r.swiglu_gate_up(xd, to_dev(w[:I]), to_dev(wu)))
+    finally:
+        thi.thi_set_kernel_family(prev)
+    assert np.array_equal(a.view(np.uint16), a2.view(np.uint16))
+    y, s = oracle_mod.linear(x, w)
+    check(a, y, s, "linear", argmax=False)
+    y, s = oracle_mod.rmsnorm_qkv(x, g, 1e-6, w)
+    check(b, y, s, "rmsnorm_qkv", argmax=False)
+    y, s = oracle_mod.rmsnorm_qkv_rope(x, g, 1e-6, w, pos, th, n_rot, hd)
+    check(c, y, s, "rmsnorm_qkv_rope", argmax=False)
+    # gate/up alone: h = silu(x Wg^T) * (x Wu^T) is the MLP oracle's intermediate; the kernel's fp32 sums
+    # are rounded once to fp16
+    _, _, hh = oracle_mod.swiglu_mlp(x, w[:I], wu, np.zeros((K, I), np.float16), return_h=True)
+    err = np.abs(h.astype(np.float64) - hh)
+    bound = 2e-3 * np.abs(hh) + 2e-3 * np.sqrt((hh ** 2).mean())
+    assert (err <= bound).all(), f"gate/up worst excess {(err - bound).max()}"
 
 
 def _dev_i32(a):
