@@ -135,8 +135,8 @@ size_t thi_workspace_bytes(int op, int M, int N_or_H, int K_or_I);
 
 /*
  * Prepare a freshly allocated workspace (device pointer, 256-byte aligned):
- * enqueues small fill kernels on `hip_stream` that put the status words and
- * the hand-over slots of the split-K reductions into their idle state.
+ * enqueues a small fill kernel on `hip_stream` that zeroes the status words
+ * (hand-over flags, arrival counters) the split-K reductions use.
  * `workspace_bytes` must be what thi_workspace_bytes() returned (at least its
  * fixed part, about 18 MiB; THI_ERR_WORKSPACE otherwise).  Needed once per
  * allocation (and again only if a call on that workspace was aborted half-way).

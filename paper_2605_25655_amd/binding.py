@@ -43,6 +43,9 @@ def load_library():
         raise FileNotFoundError(
             f"{_LIB_PATH} is missing: build it with `python -m paper_2605_25655_amd.build` "
             "(there is no fallback path)")
+    # The tensors and streams handed to the library belong to the HIP runtime that PyTorch loaded;
+    # libthi must bind to that same copy of the runtime, so PyTorch's is loaded first.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(_LIB_PATH)
     vp, sz, ci, cf = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_float
     lib.thi_rmsnorm_qkv.argtypes = [vp, vp, cf, vp, vp, ci, ci, ci, vp, sz, vp]

@@ -33,10 +33,45 @@ namespace thi {
 
 namespace {
 
-// a partial sum as it travels through a hand-over slot: any bit pattern but the "empty" one
-__device__ __forceinline__ unsigned handover_word(float v) {
-    const unsigned b = __builtin_bit_cast(unsigned, v);
-    return b == HANDOVER_EMPTY ? 0x7fc00000u : b;      // both are NaNs
+// Device-scope (sc1) 16-byte accesses for the hand-over slots: write-through stores, loads that see
+// other workgroups' stores.  They are not atomic as a whole (a reader can see a store half landed),
+// so they are only used on data that a flag has announced.
+__device__ __forceinline__ void store_device_x4(unsigned* p, uintx4 v) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
+// Four (MT = 1) or eight (MT = 2) such loads and the wait for them in ONE statement: the registers
+// are written asynchronously, so the compiler must not see them before the wait has passed.
+// p0..p3: a lane's word group in four slots; with MT = 2 the second token tile lies 1024 bytes on.
+template <int MT>
+__device__ __forceinline__ void load_device_x4_batch(const unsigned* p0, const unsigned* p1, const unsigned* p2,
+                                                     const unsigned* p3, uintx4 (&v)[4][MT])
+{
+    if constexpr (MT == 1) {
+        asm volatile(
+            "global_load_dwordx4 %0, %4, off sc1\n\t"
+            "global_load_dwordx4 %1, %5, off sc1\n\t"
+            "global_load_dwordx4 %2, %6, off sc1\n\t"
+            "global_load_dwordx4 %3, %7, off sc1\n\t"
+            "s_waitcnt vmcnt(0)"
+            : "=&v"(v[0][0]), "=&v"(v[1][0]), "=&v"(v[2][0]), "=&v"(v[3][0])
+            : "v"(p0), "v"(p1), "v"(p2), "v"(p3)
+            : "memory");
+    } else {
+        asm volatile(
+            "global_load_dwordx4 %0, %8, off sc1\n\t"
+            "global_load_dwordx4 %1, %8, off offset:1024 sc1\n\t"
+            "global_load_dwordx4 %2, %9, off sc1\n\t"
+            "global_load_dwordx4 %3, %9, off offset:1024 sc1\n\t"
+            "global_load_dwordx4 %4, %10, off sc1\n\t"
+            "global_load_dwordx4 %5, %10, off offset:1024 sc1\n\t"
+            "global_load_dwordx4 %6, %11, off sc1\n\t"
+            "global_load_dwordx4 %7, %11, off offset:1024 sc1\n\t"
+            "s_waitcnt vmcnt(0)"
+            : "=&v"(v[0][0]), "=&v"(v[0][1]), "=&v"(v[1][0]), "=&v"(v[1][1]), "=&v"(v[2][0]), "=&v"(v[2][1]),
+              "=&v"(v[3][0]), "=&v"(v[3][1])
+            : "v"(p0), "v"(p1), "v"(p2), "v"(p3)
+            : "memory");
+    }
 }
 
 // U work units are dealt to G workgroups in contiguous shares: the first `rem`
@@ -64,6 +99,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
     __shared__ uintx4 wt[SK_WAVES][WT_UNITS];      // wave-private transposition buffers
     __shared__ float s_red[SK_WAVES][32];
     __shared__ float s_ssq[32];
+    __shared__ unsigned s_flag;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -222,98 +258,98 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
         // ---- a tile shared by several workgroups ----------------------------------------------
         // Shares are contiguous, so the workgroup that owns the tile's first k chunk (w_first)
         // reaches the tile at the END of its share, every other contributor at the START of its
-        // own.  The others write their partial tile into their hand-over slot and move on; w_first
-        // keeps its part in registers and adds the partials in workgroup order.  There is no flag:
-        // a slot holds HANDOVER_EMPTY in every word between uses, a contributor never writes that
-        // value, and the finisher re-reads a slot until none of its words is empty, then empties
-        // the words it took.  Every word vouches for itself, so no ordering between the stores is
-        // needed and the hand-over costs one store and one load across the chip.
+        // own.  The others hand in their partial tile -- device-scope stores into their hand-over
+        // slot, then a flag once the stores are acknowledged -- and move on; w_first keeps its part
+        // in registers, waits for the flags (normally long set) and adds the partials in workgroup
+        // order.  A lane's four accumulator registers of a token tile travel as one 16-byte group:
+        // the hand-over is bound by the number of device-scope memory instructions, not by bytes.
+        // (The data is only read after the flag: a 16-byte access is not atomic as a whole.)
         bool finish = whole;
         if (!whole) {
             const int w_first = deal.owner(tile_begin);
             const int w_last = deal.owner(tile_begin + kch - 1);
             const bool lane_ssq = is_rms(EPI) && tid < 32;
+            const int own = (wv * 2 * 64 + lane) * 4;       // this lane's word group (token tile 0) in a slot
             if (wg != w_first) {
                 unsigned* ps = a.handover + (size_t)wg * SK_SLOT_WORDS;
                 // only the lanes that hold a real token (column c = lane % 16 of token tile mt) take part
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
                     if (mt * 16 + (lane & 15) < a.M)
-#pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            __hip_atomic_store(ps + ((wv * 2 + mt) * 4 + i) * 64 + lane, handover_word(acc[mt][i]),
-                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        store_device_x4(ps + own + mt * 256, __builtin_bit_cast(uintx4, acc[mt]));
                 if (lane_ssq)
-                    __hip_atomic_store(ps + SK_SLOT_SSQ + tid, handover_word(s_ssq[tid]), __ATOMIC_RELAXED,
+                    __hip_atomic_store(ps + SK_SLOT_SSQ + tid, __builtin_bit_cast(unsigned, s_ssq[tid]), __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
+                // every thread waits until its write-through stores are acknowledged (a workgroup-scope
+                // fence alone does not wait for that); only then may the flag go up
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __syncthreads();
+                if (tid == 0)
+                    __hip_atomic_store(a.counters + wg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             } else {
-                float sq = lane_ssq ? s_ssq[tid] : 0.f;
-                bool ok = true;
-                // four contributors at a time so that the round trips overlap
-                for (int wc0 = w_first + 1; wc0 <= w_last && ok; wc0 += 4) {
-                    unsigned pv[4][MT][4];
-                    unsigned ps4[4];
-                    unsigned spins = 0;
-                    while (true) {
-                        // all loads first (their round trips overlap), the checks afterwards
+                if (wv == 0) {
+                    // wave 0 polls the flags, one contributor per lane, so the round trips overlap
+                    unsigned ok = 1u;
+                    for (int wc0 = w_first + 1; wc0 <= w_last; wc0 += 64) {
+                        const int wc = wc0 + lane;
+                        const bool mine = wc <= w_last;
+                        unsigned spins = 0;
+                        bool seen = !mine;
+                        while (true) {
+                            if (!seen)
+                                seen = __hip_atomic_load(a.counters + wc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
+                            if (__builtin_amdgcn_ballot_w64(!seen) == 0ull) break;
+                            __builtin_amdgcn_s_sleep(1);
+                            if (++spins > SK_SPIN_LIMIT) { ok = 0u; break; }      // bounded: every wave exits
+                        }
+                        if (mine && seen)
+                            __hip_atomic_store(a.counters + wc, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                    if (lane == 0) {
+                        if (!ok) __hip_atomic_store(a.counters + (WS_MAX_COUNTERS - 1), 1u, __ATOMIC_RELAXED,
+                                                    __HIP_MEMORY_SCOPE_AGENT);
+                        s_flag = ok;
+                    }
+                }
+                __syncthreads();
+                finish = (s_flag != 0u);
+                if (finish) {
+                    float sq = lane_ssq ? s_ssq[tid] : 0.f;
+                    // four contributors at a time so that the round trips overlap; every lane loads (from
+                    // the last contributor's slot if there is no b-th one) and discards what is not its own
+                    for (int wc0 = w_first + 1; wc0 <= w_last; wc0 += 4) {
+                        uintx4 pv[4][MT];
+                        unsigned ps4[4];
+                        const unsigned* cs[4];
 #pragma unroll
                         for (int b = 0; b < 4; ++b) {
                             const int wc = wc0 + b;
-                            const unsigned* cs = a.handover + (size_t)(wc <= w_last ? wc : w_last) * SK_SLOT_WORDS;
-#pragma unroll
-                            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                                for (int i = 0; i < 4; ++i)
-                                    pv[b][mt][i] = (wc <= w_last && mt * 16 + (lane & 15) < a.M)
-                                        ? __hip_atomic_load(cs + ((wv * 2 + mt) * 4 + i) * 64 + lane, __ATOMIC_RELAXED,
-                                                            __HIP_MEMORY_SCOPE_AGENT)
-                                        : 0u;      // +0.0f
+                            cs[b] = a.handover + (size_t)(wc <= w_last ? wc : w_last) * SK_SLOT_WORDS;
                             ps4[b] = (wc <= w_last && lane_ssq)
-                                ? __hip_atomic_load(cs + SK_SLOT_SSQ + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                                : 0u;
+                                ? __hip_atomic_load(cs[b] + SK_SLOT_SSQ + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                : 0u;      // +0.0f
                         }
-                        bool empty = false;
+                        load_device_x4_batch<MT>(cs[0] + own, cs[1] + own, cs[2] + own, cs[3] + own, pv);
 #pragma unroll
                         for (int b = 0; b < 4; ++b) {
+                            if (wc0 + b > w_last) continue;
 #pragma unroll
                             for (int mt = 0; mt < MT; ++mt)
+                                if (mt * 16 + (lane & 15) < a.M) {
 #pragma unroll
-                                for (int i = 0; i < 4; ++i) empty |= (pv[b][mt][i] == HANDOVER_EMPTY);
-                            empty |= (ps4[b] == HANDOVER_EMPTY);
-                        }
-                        if (__builtin_amdgcn_ballot_w64(empty) == 0ull) break;
-                        __builtin_amdgcn_s_sleep(2);
-                        if (++spins > SK_SPIN_LIMIT) { ok = false; break; }      // bounded: every wave exits
-                    }
-                    if (!ok) break;
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        const int wc = wc0 + b;
-                        if (wc > w_last) continue;
-                        unsigned* cs = a.handover + (size_t)wc * SK_SLOT_WORDS;
-#pragma unroll
-                        for (int mt = 0; mt < MT; ++mt)
-                            if (mt * 16 + (lane & 15) < a.M)
-#pragma unroll
-                                for (int i = 0; i < 4; ++i) {
-                                    acc[mt][i] += __builtin_bit_cast(float, pv[b][mt][i]);
-                                    __hip_atomic_store(cs + ((wv * 2 + mt) * 4 + i) * 64 + lane, HANDOVER_EMPTY,
-                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                    for (int i = 0; i < 4; ++i) {
+                                        const unsigned word = pv[b][mt][i];      // (a bit_cast straight from a vector element miscompiles)
+                                        acc[mt][i] += __builtin_bit_cast(float, word);
+                                    }
                                 }
-                        if (lane_ssq) {
-                            sq += __builtin_bit_cast(float, ps4[b]);
-                            __hip_atomic_store(cs + SK_SLOT_SSQ + tid, HANDOVER_EMPTY, __ATOMIC_RELAXED,
-                                               __HIP_MEMORY_SCOPE_AGENT);
+                            if (lane_ssq) sq += __builtin_bit_cast(float, ps4[b]);
                         }
                     }
-                }
-                if (!ok && lane == 0)
-                    __hip_atomic_store(a.counters + (WS_MAX_COUNTERS - 1), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                finish = ok;
-                if (is_rms(EPI)) {
-                    __syncthreads();
-                    if (tid < 32) s_ssq[tid] = sq;
-                    __syncthreads();
+                    if (is_rms(EPI)) {
+                        __syncthreads();
+                        if (tid < 32) s_ssq[tid] = sq;
+                        __syncthreads();
+                    }
                 }
             }
         }

@@ -25,10 +25,10 @@ struct RopeArgs {
 };
 
 // ---- workspace layout (bytes from the workspace base) ----------------------
-// [0, 64 KiB)             : status words (uint32), zero between calls; last word: time-out marker
+// [0, 64 KiB)             : status words (uint32), zero between calls: the decode kernels' hand-over
+//                           flags (one per workgroup), the GEMM's tile counters; last word: time-out marker
 // [64 KiB, 64 KiB + 1 MiB): prefill GEMM: per-workgroup partial sums of squares for RMSNorm
-// [.., + hand-over bytes) : decode kernels: one hand-over slot per workgroup, every word
-//                           HANDOVER_EMPTY between calls
+// [.., + hand-over bytes) : decode kernels: one hand-over slot per workgroup
 // [.., + partial bytes)   : prefill GEMM: per-workgroup partial accumulator tiles (fp32)
 // [.., + M*I*2)           : h = silu(gate)*up of the MLP (fp16)
 constexpr size_t WS_COUNTER_BYTES = 64 * 1024;
@@ -41,12 +41,11 @@ constexpr int SK_WAVES = 8;
 constexpr int SK_ROWS = 128;        // virtual weight rows per tile (16 per wave)
 constexpr int SK_KC = 256;          // k extent of one work unit
 constexpr int SK_MAX_GRID = 1024;   // upper bound on workgroups (sizes the hand-over slots)
-constexpr unsigned SK_SPIN_LIMIT = 1u << 22;   // reads of a contributor's slot before a wave gives up
-// hand-over slot of one workgroup: its partial tile (8 waves x 2 token tiles x 4 registers x 64 lanes,
+constexpr unsigned SK_SPIN_LIMIT = 1u << 24;   // polls of a contributor's flag before a workgroup gives up
+// hand-over slot of one workgroup: its partial tile (8 waves x 2 token tiles x 64 lanes x 4 registers,
 // fp32 bit patterns), then 32 partial sums of squares, padded to a multiple of 64 words
 constexpr int SK_SLOT_SSQ = SK_WAVES * 2 * 4 * 64;
 constexpr int SK_SLOT_WORDS = SK_SLOT_SSQ + 64;
-constexpr unsigned HANDOVER_EMPTY = 0xffffffffu;   // a NaN pattern that no partial sum is ever stored as
 
 struct SkinnyArgs {
     const uint16_t* x;       // [M,K] activations
@@ -54,8 +53,8 @@ struct SkinnyArgs {
     const uint16_t* w0;      // weights [N,K]  (gate weights for SwiGLU)
     const uint16_t* w1;      // up weights [I,K] for SwiGLU, else nullptr
     uint16_t* out;           // [M,ldo]
-    unsigned* handover;      // [grid][SK_SLOT_WORDS] hand-over slots, HANDOVER_EMPTY between calls
-    unsigned* counters;      // status words; last word: time-out marker
+    unsigned* handover;      // [grid][SK_SLOT_WORDS] hand-over slots
+    unsigned* counters;      // [grid] hand-over flags, zero between calls; last word: time-out marker
     int M, N, K, ldo;        // N = physical rows of w0 (I for SwiGLU); ldo = out row length
     int tiles, kchunks;      // tiles of SK_ROWS virtual rows; chunks of SK_KC along K
     float eps;
