@@ -49,6 +49,9 @@ def _load():
         lib.thi_oracle_linear.argtypes = [u16p, u16p, f64p, f64p, L, L, L]
         lib.thi_oracle_rmsnorm_qkv.argtypes = [u16p, u16p, ctypes.c_float, u16p, f64p, f64p, L, L, L]
         lib.thi_oracle_swiglu_mlp.argtypes = [u16p, u16p, u16p, u16p, f64p, f64p, f64p, L, L, L]
+        lib.thi_oracle_linear_residual.argtypes = [u16p, u16p, u16p, f64p, f64p, L, L, L]
+        lib.thi_oracle_rmsnorm_swiglu_mlp.argtypes = [u16p, u16p, ctypes.c_float, u16p, u16p, u16p, u16p, f64p, f64p,
+                                                      f64p, L, L, L]
         i32p = ctypes.POINTER(ctypes.c_int32)
         f32p = ctypes.POINTER(ctypes.c_float)
         lib.thi_oracle_rope_inplace.argtypes = [f64p, f64p, i32p, f32p, L, L, L, L]
@@ -130,6 +133,37 @@ def swiglu_mlp(x: np.ndarray, wg: np.ndarray, wu: np.ndarray, wd: np.ndarray, re
     )
     if rc:
         raise MemoryError("thi_oracle_swiglu_mlp failed")
+    return (y, s, h) if return_h else (y, s)
+
+
+def linear_residual(x: np.ndarray, w: np.ndarray, res: np.ndarray):
+    """y = res + x w^T and S = |res| + sum_k |x w|, in fp64."""
+    M, K = x.shape
+    N = w.shape[0]
+    xb, wb, rb = _bits(x, (M, K)), _bits(w, (N, K)), _bits(res, (M, N))
+    y = np.empty((M, N), np.float64)
+    s = np.empty((M, N), np.float64)
+    rc = _load().thi_oracle_linear_residual(_p16(xb), _p16(wb), _p16(rb), _p64(y), _p64(s), M, N, K)
+    if rc:
+        raise MemoryError("thi_oracle_linear_residual failed")
+    return y, s
+
+
+def rmsnorm_swiglu_mlp(x, gamma, eps, wg, wu, wd, res=None, return_h: bool = False):
+    """y = [res +] (silu(n wg^T) * (n wu^T)) wd^T with n = rmsnorm(x; gamma, eps), in fp64."""
+    M, H = x.shape
+    I = wg.shape[0]
+    xb, gmb = _bits(x, (M, H)), _bits(gamma, (H,))
+    gb, ub, db = _bits(wg, (I, H)), _bits(wu, (I, H)), _bits(wd, (H, I))
+    rb = _bits(res, (M, H)) if res is not None else None
+    y = np.empty((M, H), np.float64)
+    s = np.empty((M, H), np.float64)
+    h = np.empty((M, I), np.float64) if return_h else None
+    rc = _load().thi_oracle_rmsnorm_swiglu_mlp(
+        _p16(xb), _p16(gmb), ctypes.c_float(eps), _p16(gb), _p16(ub), _p16(db),
+        _p16(rb) if rb is not None else None, _p64(y), _p64(s), _p64(h) if return_h else None, M, H, I)
+    if rc:
+        raise MemoryError("thi_oracle_rmsnorm_swiglu_mlp failed")
     return (y, s, h) if return_h else (y, s)
 
 

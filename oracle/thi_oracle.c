@@ -32,8 +32,9 @@
  * weights, RMSNorm of constant vectors, RMSNorm scale invariance and
  * factorisation, SiLU reference values and identities, SwiGLU with selector
  * matrices, exact rational brute force on tiny shapes, a numpy fp64 witness on
- * mid-size shapes, linearity, and the paper's Eq. 1-3 / Eq. 7 arithmetic for
- * the roofline helpers used by the benchmark.
+ * mid-size shapes, linearity, residuals that cancel the product exactly, the
+ * normalised MLP against its pinned parts, and the paper's Eq. 1-3 / Eq. 7
+ * arithmetic for the roofline helpers used by the benchmark.
  */
 #include <math.h>
 #include <stdint.h>
@@ -188,6 +189,69 @@ int thi_oracle_swiglu_mlp(const uint16_t *x, const uint16_t *wg, const uint16_t 
         }
     }
     free(a);
+    free(gate);
+    free(up);
+    return rc;
+}
+
+/*
+ * The decoder layer of Sec. III-D.3 (norm -> attention -> norm -> FFN, each block wrapped in a
+ * residual connection as in the Llama layer the paper takes as given) closes two fusion units with
+ * an addition and opens the second one with a normalisation:
+ *   linear_residual     : y = res + x * w^T                      (O projection, down projection)
+ *   rmsnorm_swiglu_mlp  : n = rmsnorm(x; gamma, eps) (never rounded), h = silu(n wg^T) * (n wu^T),
+ *                         y = res + h * wd^T                     (res may be NULL: no addition)
+ * The residual is fp16 like every activation and is widened exactly; S gains |res[m,n]|.
+ */
+int thi_oracle_linear_residual(const uint16_t *x, const uint16_t *w, const uint16_t *res, double *y, double *s,
+                               long M, long N, long K)
+{
+    int rc = thi_oracle_linear(x, w, y, s, M, N, K);
+    if (rc) return rc;
+    for (long i = 0; i < M * N; ++i) {
+        const double r = half_bits_to_double(res[i]);
+        y[i] += r;
+        if (s) s[i] += fabs(r);
+    }
+    return 0;
+}
+
+int thi_oracle_rmsnorm_swiglu_mlp(const uint16_t *x, const uint16_t *gamma, float eps, const uint16_t *wg,
+                                  const uint16_t *wu, const uint16_t *wd, const uint16_t *res, double *y,
+                                  double *s, double *h_out, long M, long H, long I)
+{
+    double *a = (double *)malloc((size_t)M * H * sizeof(double));
+    double *g = (double *)malloc((size_t)H * sizeof(double));
+    double *gate = (double *)malloc((size_t)M * I * sizeof(double));
+    double *up = (double *)malloc((size_t)M * I * sizeof(double));
+    int rc = -1;
+    if (a && g && gate && up) {
+        widen_row(x, a, M * H);
+        widen_row(gamma, g, H);
+        for (long m = 0; m < M; ++m) {
+            double *row = a + m * H;
+            double sumsq = 0.0;
+            for (long k = 0; k < H; ++k) sumsq += row[k] * row[k];
+            double r = 1.0 / sqrt(sumsq / (double)H + (double)eps);
+            for (long k = 0; k < H; ++k) row[k] = row[k] * r * g[k];
+        }
+        rc = dense_rows(a, wg, gate, NULL, M, I, H);
+        if (rc == 0) rc = dense_rows(a, wu, up, NULL, M, I, H);
+        if (rc == 0) {
+            for (long i = 0; i < M * I; ++i) gate[i] = thi_oracle_silu(gate[i]) * up[i];
+            if (h_out) memcpy(h_out, gate, (size_t)M * I * sizeof(double));
+            rc = dense_rows(gate, wd, y, s, M, H, I);
+        }
+        if (rc == 0 && res) {
+            for (long i = 0; i < M * H; ++i) {
+                const double r = half_bits_to_double(res[i]);
+                y[i] += r;
+                if (s) s[i] += fabs(r);
+            }
+        }
+    }
+    free(a);
+    free(g);
     free(gate);
     free(up);
     return rc;
