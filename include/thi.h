@@ -127,6 +127,31 @@ int thi_swiglu_gate_up(const void* x, const void* w_gate, const void* w_up, void
                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The two operators that close the residual blocks of the decoder layer
+ * (Sec. III-D.3: norm -> attention -> norm -> FFN; Sec. III-C.1: a low-density
+ * operator behind the linear one is applied to the accumulator before the store).
+ *
+ * thi_linear_residual:   out[M,N] = residual[M,N] + x[M,K] * w[N,K]^T
+ *     the O projection and any projection that ends a residual block; the sum
+ *     is formed in fp32 and rounded once.
+ * thi_rmsnorm_swiglu_mlp: out[M,H] = residual[M,H] + (silu(n Wg^T) * (n Wu^T)) Wd^T
+ *     with n = rmsnorm(x; gamma, eps) never materialised (the post-attention
+ *     normalisation fused in front of the gate/up projections, as RMSNorm is in
+ *     thi_rmsnorm_qkv).  residual may be NULL (nothing is added).
+ * `residual` is fp16 [M,N] resp. [M,H], 16-byte aligned; it MAY be the same
+ * buffer as `out` (every element is read before it is written, by the same
+ * thread), but must not otherwise overlap it.  Workspace: as for thi_linear
+ * resp. thi_swiglu_mlp.  Everything else as in the common conventions.
+ */
+int thi_linear_residual(const void* x, const void* w, const void* residual, void* out,
+                        int M, int N, int K,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+int thi_rmsnorm_swiglu_mlp(const void* x, const void* gamma, float eps, const void* w_gate, const void* w_up,
+                           const void* w_down, const void* residual, void* out,
+                           int M, int H, int I,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Bytes of workspace the given operator needs for the given shape
  * (op = thi_op; (M, N, K) for the first two operators, (M, H, I) for the MLP).
  * Pure host arithmetic: touches no device.  Returns 0 for invalid arguments.

@@ -18,7 +18,8 @@ _LIB_PATH = os.path.join(_PKG, "libthi.so")
 _lib = None
 
 EXPORTED_SYMBOLS = (
-    "thi_rmsnorm_qkv", "thi_rmsnorm_qkv_rope", "thi_linear", "thi_swiglu_mlp", "thi_swiglu_gate_up", "thi_workspace_bytes",
+    "thi_rmsnorm_qkv", "thi_rmsnorm_qkv_rope", "thi_linear", "thi_swiglu_mlp", "thi_swiglu_gate_up",
+    "thi_linear_residual", "thi_rmsnorm_swiglu_mlp", "thi_workspace_bytes",
     "thi_workspace_init", "thi_status_string", "thi_version", "thi_set_kernel_family",
     "thi_probe_stream_read", "thi_probe_mfma_f16",
 )
@@ -58,6 +59,10 @@ def load_library():
     lib.thi_swiglu_mlp.restype = ci
     lib.thi_swiglu_gate_up.argtypes = [vp, vp, vp, vp, ci, ci, ci, vp, sz, vp]
     lib.thi_swiglu_gate_up.restype = ci
+    lib.thi_linear_residual.argtypes = [vp, vp, vp, vp, ci, ci, ci, vp, sz, vp]
+    lib.thi_linear_residual.restype = ci
+    lib.thi_rmsnorm_swiglu_mlp.argtypes = [vp, vp, cf, vp, vp, vp, vp, vp, ci, ci, ci, vp, sz, vp]
+    lib.thi_rmsnorm_swiglu_mlp.restype = ci
     lib.thi_workspace_bytes.argtypes = [ci, ci, ci, ci]
     lib.thi_workspace_bytes.restype = sz
     lib.thi_workspace_init.argtypes = [vp, sz, vp]
@@ -168,6 +173,32 @@ def thi_swiglu_mlp(x, w_gate, w_up, w_down, out, workspace, stream=None, check: 
                                        M, H, I, wp, wb, _stream(stream))
     if check and rc != THI_OK:
         raise ThiError(rc, "thi_swiglu_mlp")
+    return rc
+
+
+def thi_linear_residual(x, w, residual, out, workspace, stream=None, check: bool = True) -> int:
+    """out[M,N] = residual[M,N] + x[M,K] @ w[N,K]^T  (fp16 device tensors; residual may be out)."""
+    M, K = x.shape
+    N = w.shape[0]
+    wp, wb = _ws(workspace)
+    rc = load_library().thi_linear_residual(_ptr(x), _ptr(w), _ptr(residual), _ptr(out), M, N, K, wp, wb,
+                                            _stream(stream))
+    if check and rc != THI_OK:
+        raise ThiError(rc, "thi_linear_residual")
+    return rc
+
+
+def thi_rmsnorm_swiglu_mlp(x, gamma, eps, w_gate, w_up, w_down, residual, out, workspace, stream=None,
+                           check: bool = True) -> int:
+    """out[M,H] = [residual +] (silu(n @ w_gate^T) * (n @ w_up^T)) @ w_down^T, n = rmsnorm(x; gamma, eps)."""
+    M, H = x.shape
+    I = w_gate.shape[0]
+    wp, wb = _ws(workspace)
+    rc = load_library().thi_rmsnorm_swiglu_mlp(_ptr(x), _ptr(gamma), ctypes.c_float(eps), _ptr(w_gate), _ptr(w_up),
+                                               _ptr(w_down), _ptr(residual), _ptr(out), M, H, I, wp, wb,
+                                               _stream(stream))
+    if check and rc != THI_OK:
+        raise ThiError(rc, "thi_rmsnorm_swiglu_mlp")
     return rc
 
 

@@ -86,7 +86,7 @@ bool use_rowslab(int M, int N, int K, int epilogue, int cus)
     const int fam = g_family.load(std::memory_order_relaxed);
     if (fam == 3) return true;
     if (fam == 1) return false;
-    const bool swiglu = (epilogue == EPI_SWIGLU);
+    const bool swiglu = is_swiglu(epilogue);
     const double t_w = (swiglu ? 2.0 : 1.0) * (double)N * (double)K * 2.0 / 7.0e6;
     const long slabs = ((long)N + (swiglu ? 7 : 15)) / (swiglu ? 8 : 16);
     const long rounds = (slabs + cus - 1) / cus;
@@ -102,13 +102,14 @@ bool use_rowslab(int M, int N, int K, int epilogue, int cus)
 // One fused projection: out[M, ldo] = epilogue( prologue(x)[M,K] * w^T ), any M.
 int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const uint16_t* w0, const uint16_t* w1,
                    uint16_t* out, int M, int N, int K, int ldo, int epilogue, const Workspace& ws,
-                   hipStream_t stream, RopeArgs rope = RopeArgs{nullptr, nullptr, 0, 2})
+                   hipStream_t stream, RopeArgs rope = RopeArgs{nullptr, nullptr, 0, 2},
+                   const uint16_t* residual = nullptr)
 {
     const int cus = device_cu_count();
     (void)hipGetLastError();      // an error another user of the runtime left behind is not ours to report
     if (use_skinny(M)) {
         const bool slab = use_rowslab(M < SKINNY_GROUP ? M : SKINNY_GROUP, N, K, epilogue, cus);
-        const int rows_per_tile = slab ? ((epilogue == EPI_SWIGLU) ? 8 : 16) : ((epilogue == EPI_SWIGLU) ? SK_ROWS / 2 : SK_ROWS);
+        const int rows_per_tile = slab ? (is_swiglu(epilogue) ? 8 : 16) : (is_swiglu(epilogue) ? SK_ROWS / 2 : SK_ROWS);
         const int tiles = (N + rows_per_tile - 1) / rows_per_tile;
         if ((long)tiles * ((K + SK_KC - 1) / SK_KC) > (1L << 30)) return THI_ERR_SHAPE;
         for (int m0 = 0; m0 < M; m0 += SKINNY_GROUP) {
@@ -118,6 +119,7 @@ int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const ui
             a.w0 = w0;
             a.w1 = w1;
             a.out = out + (size_t)m0 * ldo;
+            a.residual = residual ? residual + (size_t)m0 * ldo : nullptr;
             a.handover = ws.handover;
             a.counters = ws.counters;
             a.M = (M - m0 < SKINNY_GROUP) ? M - m0 : SKINNY_GROUP;
@@ -144,6 +146,7 @@ int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const ui
     g.w0 = w0;
     g.w1 = w1;
     g.out = out;
+    g.residual = residual;
     g.partials = ws.partials;
     g.ssq = ws.ssq;
     g.counters = ws.counters;
@@ -241,6 +244,39 @@ int thi_swiglu_gate_up(const void* x, const void* w_gate, const void* w_up, void
     Workspace ws = carve(workspace);
     return run_projection((const uint16_t*)x, nullptr, 0.f, (const uint16_t*)w_gate, (const uint16_t*)w_up,
                           (uint16_t*)h, M, I, H, I, EPI_SWIGLU, ws, (hipStream_t)hip_stream);
+}
+
+int thi_linear_residual(const void* x, const void* w, const void* residual, void* out, int M, int N, int K,
+                        void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!x || !w || !residual || !out) return THI_ERR_NULL;
+    int rc = check_common(M, N, K, workspace, workspace_bytes, workspace_need(THI_OP_LINEAR, M, N, K));
+    if (rc != THI_OK) return rc;
+    if (misaligned(x, 16) || misaligned(w, 16) || misaligned(residual, 16) || misaligned(out, 16)) return THI_ERR_ALIGN;
+    Workspace ws = carve(workspace);
+    return run_projection((const uint16_t*)x, nullptr, 0.f, (const uint16_t*)w, nullptr, (uint16_t*)out,
+                          M, N, K, N, EPI_PLAIN, ws, (hipStream_t)hip_stream, RopeArgs{nullptr, nullptr, 0, 2},
+                          (const uint16_t*)residual);
+}
+
+int thi_rmsnorm_swiglu_mlp(const void* x, const void* gamma, float eps, const void* w_gate, const void* w_up,
+                           const void* w_down, const void* residual, void* out, int M, int H, int I,
+                           void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!x || !gamma || !w_gate || !w_up || !w_down || !out) return THI_ERR_NULL;
+    if (I < 1 || (I & 7)) return THI_ERR_SHAPE;
+    int rc = check_common(M, H, H, workspace, workspace_bytes, workspace_need(THI_OP_SWIGLU_MLP, M, H, I));
+    if (rc != THI_OK) return rc;
+    if (misaligned(x, 16) || misaligned(gamma, 16) || misaligned(w_gate, 16) || misaligned(w_up, 16) ||
+        misaligned(w_down, 16) || misaligned(out, 16) || (residual && misaligned(residual, 16)))
+        return THI_ERR_ALIGN;
+    Workspace ws = carve(workspace);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    rc = run_projection((const uint16_t*)x, (const uint16_t*)gamma, eps, (const uint16_t*)w_gate,
+                        (const uint16_t*)w_up, ws.h, M, I, H, I, EPI_RMSNORM_SWIGLU, ws, stream);
+    if (rc != THI_OK) return rc;
+    return run_projection(ws.h, nullptr, 0.f, (const uint16_t*)w_down, nullptr, (uint16_t*)out, M, H, I, H,
+                          EPI_PLAIN, ws, stream, RopeArgs{nullptr, nullptr, 0, 2}, (const uint16_t*)residual);
 }
 
 size_t thi_workspace_bytes(int op, int M, int N_or_H, int K_or_I)

@@ -93,10 +93,10 @@ template <int BN, int BM, int WN, int WM, int EPI>
 __device__ __forceinline__ void store_fragment(const GemmArgs& a, int tile_n, int tile_m, int wn, int wm, int tn,
                                                int tm, int lr, int lg, const floatx16& f, float scale)
 {
-    constexpr int JPT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
+    constexpr int JPT = is_swiglu(EPI) ? BN / 2 : BN;
     const int m = tile_m * BM + wm * (BM / WM) + tm * 32 + lr;
     if (m >= a.M) return;
-    if (EPI == EPI_SWIGLU) {
+    if (is_swiglu(EPI)) {      // scale: the 1/rms factor when RMSNorm sits in front (else 1)
 #pragma unroll
         for (int aa = 0; aa < 4; aa += 2) {
             const int v = wn * (BN / WN) + tn * 32 + 8 * aa;
@@ -104,7 +104,7 @@ __device__ __forceinline__ void store_fragment(const GemmArgs& a, int tile_n, in
             half4 hv;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                const float g = f[4 * aa + c], uu = f[4 * (aa + 1) + c];
+                const float g = f[4 * aa + c] * scale, uu = f[4 * (aa + 1) + c] * scale;
                 hv[c] = (_Float16)(g / (1.0f + __expf(-g)) * uu);
             }
             if (j + 3 < a.N && (a.ldo & 3) == 0) {
@@ -129,13 +129,21 @@ __device__ __forceinline__ void store_fragment(const GemmArgs& a, int tile_n, in
             }
             if (n + 3 < a.N && (a.ldo & 3) == 0) {
                 half4 hv;
+                if (a.residual) {
+                    const half4 rv = *reinterpret_cast<const half4*>(a.residual + (size_t)m * a.ldo + n);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) v[c] += (float)rv[c];
+                }
 #pragma unroll
                 for (int c = 0; c < 4; ++c) hv[c] = (_Float16)v[c];
                 *reinterpret_cast<half4*>(a.out + (size_t)m * a.ldo + n) = hv;
             } else {
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
-                    if (n + c < a.N) a.out[(size_t)m * a.ldo + n + c] = to_half_bits(v[c]);
+                    if (n + c < a.N) {
+                        if (a.residual) v[c] += half_bits_to_float(a.residual[(size_t)m * a.ldo + n + c]);
+                        a.out[(size_t)m * a.ldo + n + c] = to_half_bits(v[c]);
+                    }
             }
         }
     }
@@ -192,12 +200,12 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
     constexpr int XPASS = BM / ROWS_PER_PASS;
     constexpr int TN = BN / WN / 32;            // MFMA tiles per wave along n
     constexpr int TM = BM / WM / 32;
-    constexpr int JPT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;   // physical weight rows per tile
+    constexpr int JPT = is_swiglu(EPI) ? BN / 2 : BN;   // physical weight rows per tile
     constexpr bool W_DMA = !KTAIL;                           // weight tile: global -> LDS directly
     constexpr bool X_DMA = !KTAIL && !is_rms(EPI);     // activation tile: same unless it is transformed
     constexpr int STAGE = (BN + BM) * GPIECES;   // 16-byte units per stage: weight tile, then activation tile
     static_assert(NS >= 2 && NS <= 4 && (KSTEPS % 2) == 0, "pipeline shape");
-    static_assert(EPI != EPI_SWIGLU || KTAIL || ROWS_PER_DMA == 8, "gate/up interleave assumes 8-row direct loads");
+    static_assert(!is_swiglu(EPI) || KTAIL || ROWS_PER_DMA == 8, "gate/up interleave assumes 8-row direct loads");
     static_assert(WPASS >= 1 && XPASS >= 1, "tile too small for the thread count");
 
     extern __shared__ uintx4 smem[];
@@ -260,7 +268,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
             const int blk = wv * WPASS + i;                          // (uniform) block of ROWS_PER_DMA rows
             const int v = W_DMA ? blk * ROWS_PER_DMA + lane / GPIECES : vr0 + ROWS_PER_PASS * i;
             const int piece = W_DMA ? slot ^ swz_f<GPIECES>(v) : vp;
-            if (EPI == EPI_SWIGLU) {
+            if (is_swiglu(EPI)) {
                 const int j0 = tile_n * JPT;                         // first row of the tile: always valid
                 int j = j0 + (v >> 4) * 8 + (v & 7);
                 j = j < a.N ? j : a.N - 1;
@@ -517,7 +525,7 @@ Schedule plan_schedule(int tiles, int grid, int B, int K)
 template <int BN, int BM, int WN, int WM, int GK, int NS, bool ALL>
 hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream)
 {
-    const int per_tile = (epilogue == EPI_SWIGLU) ? BN / 2 : BN;
+    const int per_tile = is_swiglu(epilogue) ? BN / 2 : BN;
     const int tiles_n = (a.N + per_tile - 1) / per_tile;
     const int tiles_m = (a.M + BM - 1) / BM;
     const int ktiles = (a.K + GK - 1) / GK;
@@ -559,6 +567,9 @@ hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream
     case EPI_RMSNORM_ROPE:
         if constexpr (ALL) THI_LAUNCH(EPI_RMSNORM_ROPE);
         break;
+    case EPI_RMSNORM_SWIGLU:
+        if constexpr (ALL) THI_LAUNCH(EPI_RMSNORM_SWIGLU);
+        break;
     default: THI_LAUNCH(EPI_SWIGLU); break;
     }
 #undef THI_LAUNCH
@@ -568,7 +579,7 @@ hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream
 
 double config_cost(const GemmArgs& a, int epilogue, int B, int grid)
 {
-    const int per_tile = (epilogue == EPI_SWIGLU) ? B / 2 : B;
+    const int per_tile = is_swiglu(epilogue) ? B / 2 : B;
     const long tiles = (long)((a.N + per_tile - 1) / per_tile) * ((a.M + B - 1) / B);
     const long units = tiles * ((a.K + 63) / 64);
     const int g = (int)(units < grid ? units : grid);

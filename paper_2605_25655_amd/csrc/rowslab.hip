@@ -66,7 +66,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowslab(SkinnyArgs a)
     // row pointers of a slab for this lane's four load rows
     auto row_base = [&](int slab, int jj) -> const uint16_t* {
         const int v = 4 * jj + ld_i;                   // virtual row within the slab
-        if (EPI == EPI_SWIGLU) {
+        if (is_swiglu(EPI)) {
             int j = slab * 8 + (v & 7);
             j = j < a.N ? j : a.N - 1;
             return ((v >> 3) ? a.w1 : a.w0) + (size_t)j * K;
@@ -213,9 +213,12 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowslab(SkinnyArgs a)
         // ---- epilogue: thread -> (token m, row r) ----------------------------------------------------
         const int r = tid & 15, m = tid >> 4;
         if (m < a.M) {
-            if (EPI == EPI_SWIGLU) {
+            if (is_swiglu(EPI)) {
                 const int j = this_slab * 8 + r;
-                if (r < 8 && j < a.N) a.out[(size_t)m * a.ldo + j] = to_half_bits(silu_mul(s_sum[m][r], s_sum[m][r + 8]));
+                float scale = 1.0f;      // RMSNorm in front: gate and up both carry the 1/rms factor
+                if (is_rms(EPI)) scale = 1.0f / __builtin_sqrtf(s_ssq[m] / (float)K + a.eps);
+                if (r < 8 && j < a.N)
+                    a.out[(size_t)m * a.ldo + j] = to_half_bits(silu_mul(s_sum[m][r] * scale, s_sum[m][r + 8] * scale));
             } else {
                 float scale = 1.0f;
                 if (is_rms(EPI)) scale = 1.0f / __builtin_sqrtf(s_ssq[m] / (float)K + a.eps);
@@ -224,11 +227,19 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowslab(SkinnyArgs a)
                     if ((r & 1) == 0) {       // this thread finishes the pair (n, n + 1)
                         float v0 = s_sum[m][r] * scale, v1 = s_sum[m][r + 1] * scale;
                         rope_pair(a.rope, a.rope.pos[m], n, v0, v1);
-                        if (n < a.N) a.out[(size_t)m * a.ldo + n] = to_half_bits(v0);
-                        if (n + 1 < a.N) a.out[(size_t)m * a.ldo + n + 1] = to_half_bits(v1);
+                        if (n < a.N) {
+                            if (a.residual) v0 += half_bits_to_float(a.residual[(size_t)m * a.ldo + n]);
+                            a.out[(size_t)m * a.ldo + n] = to_half_bits(v0);
+                        }
+                        if (n + 1 < a.N) {
+                            if (a.residual) v1 += half_bits_to_float(a.residual[(size_t)m * a.ldo + n + 1]);
+                            a.out[(size_t)m * a.ldo + n + 1] = to_half_bits(v1);
+                        }
                     }
                 } else if (n < a.N) {
-                    a.out[(size_t)m * a.ldo + n] = to_half_bits(s_sum[m][r] * scale);
+                    float v = s_sum[m][r] * scale;
+                    if (a.residual) v += half_bits_to_float(a.residual[(size_t)m * a.ldo + n]);
+                    a.out[(size_t)m * a.ldo + n] = to_half_bits(v);
                 }
             }
         }
@@ -268,12 +279,15 @@ hipError_t launch_mt(const SkinnyArgs& a, int epilogue, int grid, hipStream_t st
                                   hipFuncAttributeMaxDynamicSharedMemorySize, most);
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowslab<MT, EPI_RMSNORM_ROPE>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, most);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowslab<MT, EPI_RMSNORM_SWIGLU>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, most);
         attr_set = true;
     }
     switch (epilogue) {
     case EPI_PLAIN: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_PLAIN>), g, b, 0, stream, a); break;
     case EPI_RMSNORM: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_RMSNORM>), g, b, gamma_lds, stream, a); break;
     case EPI_RMSNORM_ROPE: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_RMSNORM_ROPE>), g, b, gamma_lds, stream, a); break;
+    case EPI_RMSNORM_SWIGLU: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_RMSNORM_SWIGLU>), g, b, gamma_lds, stream, a); break;
     default: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_SWIGLU>), g, b, 0, stream, a); break;
     }
     return hipGetLastError();

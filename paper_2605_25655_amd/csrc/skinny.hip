@@ -130,7 +130,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
             const uint16_t* base;
-            if (EPI == EPI_SWIGLU) {
+            if (is_swiglu(EPI)) {
                 int j = t * 64 + wv * 8 + 2 * jj + (ld_i & 1);
                 j = j < a.N ? j : a.N - 1;
                 base = ((ld_i >> 1) ? a.w1 : a.w0) + (size_t)j * K;
@@ -360,12 +360,15 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
             for (int mt = 0; mt < MT; ++mt) {
                 const int m = mt * 16 + c;
                 if (m >= a.M) continue;
-                if (EPI == EPI_SWIGLU) {
+                if (is_swiglu(EPI)) {
                     const int j = t * 64 + wv * 8 + 2 * q;
+                    float scale = 1.0f;      // RMSNorm in front: gate and up both carry the 1/rms factor
+                    if (is_rms(EPI)) scale = 1.0f / __builtin_sqrtf(s_ssq[m] / (float)K + a.eps);
 #pragma unroll
                     for (int i = 0; i < 2; ++i)
                         if (j + i < a.N)
-                            a.out[(size_t)m * a.ldo + j + i] = to_half_bits(silu_mul(acc[mt][i], acc[mt][i + 2]));
+                            a.out[(size_t)m * a.ldo + j + i] =
+                                to_half_bits(silu_mul(acc[mt][i] * scale, acc[mt][i + 2] * scale));
                 } else {
                     float scale = 1.0f;
                     if (is_rms(EPI)) scale = 1.0f / __builtin_sqrtf(s_ssq[m] / (float)K + a.eps);
@@ -380,7 +383,10 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
                     }
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
-                        if (n + i < a.N) a.out[(size_t)m * a.ldo + n + i] = to_half_bits(v[i]);
+                        if (n + i < a.N) {
+                            if (a.residual) v[i] += half_bits_to_float(a.residual[(size_t)m * a.ldo + n + i]);
+                            a.out[(size_t)m * a.ldo + n + i] = to_half_bits(v[i]);
+                        }
                 }
             }
         }
@@ -403,6 +409,7 @@ hipError_t launch_mt(const SkinnyArgs& a, int epilogue, int grid, hipStream_t st
     case EPI_PLAIN: hipLaunchKernelGGL((skinny_streamk<MT, EPI_PLAIN>), g, b, 0, stream, a); break;
     case EPI_RMSNORM: hipLaunchKernelGGL((skinny_streamk<MT, EPI_RMSNORM>), g, b, 0, stream, a); break;
     case EPI_RMSNORM_ROPE: hipLaunchKernelGGL((skinny_streamk<MT, EPI_RMSNORM_ROPE>), g, b, 0, stream, a); break;
+    case EPI_RMSNORM_SWIGLU: hipLaunchKernelGGL((skinny_streamk<MT, EPI_RMSNORM_SWIGLU>), g, b, 0, stream, a); break;
     default: hipLaunchKernelGGL((skinny_streamk<MT, EPI_SWIGLU>), g, b, 0, stream, a); break;
     }
     return hipGetLastError();

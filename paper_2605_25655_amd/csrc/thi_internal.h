@@ -13,8 +13,12 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 
-enum Epilogue { EPI_PLAIN = 0, EPI_RMSNORM = 1, EPI_SWIGLU = 2, EPI_RMSNORM_ROPE = 3 };
-constexpr bool is_rms(int epi) { return epi == EPI_RMSNORM || epi == EPI_RMSNORM_ROPE; }
+// What is fused around the linear operator.  RMSNORM*: x*gamma in front, the 1/rms scale behind.
+// *SWIGLU: gate and up rows interleaved, silu(g)*u behind.  The plain and RMSNorm kinds add a residual
+// behind the product when the argument block carries one.
+enum Epilogue { EPI_PLAIN = 0, EPI_RMSNORM = 1, EPI_SWIGLU = 2, EPI_RMSNORM_ROPE = 3, EPI_RMSNORM_SWIGLU = 4 };
+constexpr bool is_rms(int epi) { return epi == EPI_RMSNORM || epi == EPI_RMSNORM_ROPE || epi == EPI_RMSNORM_SWIGLU; }
+constexpr bool is_swiglu(int epi) { return epi == EPI_SWIGLU || epi == EPI_RMSNORM_SWIGLU; }
 
 // Rotary embedding applied in the epilogue (EPI_RMSNORM_ROPE): interleaved pairs (2i, 2i+1) of every
 // head in columns [0, n_rot); angle = pos[m] * theta[i].
@@ -53,6 +57,7 @@ struct SkinnyArgs {
     const uint16_t* w0;      // weights [N,K]  (gate weights for SwiGLU)
     const uint16_t* w1;      // up weights [I,K] for SwiGLU, else nullptr
     uint16_t* out;           // [M,ldo]
+    const uint16_t* residual; // [M,ldo] added behind the product (plain / RMSNorm kinds), or nullptr
     unsigned* handover;      // [grid][SK_SLOT_WORDS] hand-over slots
     unsigned* counters;      // [grid] hand-over flags, zero between calls; last word: time-out marker
     int M, N, K, ldo;        // N = physical rows of w0 (I for SwiGLU); ldo = out row length
@@ -75,6 +80,7 @@ struct GemmArgs {
     const uint16_t* w0;      // [N,K]
     const uint16_t* w1;      // up weights for SwiGLU
     uint16_t* out;           // [M,ldo]
+    const uint16_t* residual; // [M,ldo] added behind the product (plain / RMSNorm kinds), or nullptr
     float* partials;         // [grid][2][tile] fp32 partial tiles (stream-K)
     float* ssq;              // [grid][2][256]
     unsigned* counters;      // [tiles]
@@ -112,6 +118,9 @@ __device__ __forceinline__ uintx4 ld_cached(const uint16_t* p) {
 }
 __device__ __forceinline__ float silu_mul(float g, float u) {
     return g / (1.0f + __expf(-g)) * u;
+}
+__device__ __forceinline__ float half_bits_to_float(uint16_t b) {
+    return (float)__builtin_bit_cast(_Float16, b);
 }
 __device__ __forceinline__ uint16_t to_half_bits(float v) {
     _Float16 h = (_Float16)v;   // round-to-nearest-even

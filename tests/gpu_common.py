@@ -61,6 +61,16 @@ class Runner:
         self.thi.thi_swiglu_gate_up(x, wg, wu, out, self.ws)
         return out
 
+    def linear_residual(self, x, w, res, in_place=False):
+        out = res.clone() if in_place else new_out(x.shape[0], w.shape[0])
+        self.thi.thi_linear_residual(x, w, out if in_place else res, out, self.ws)
+        return out
+
+    def rmsnorm_swiglu_mlp(self, x, gamma, eps, wg, wu, wd, res=None, in_place=False):
+        out = res.clone() if (in_place and res is not None) else new_out(x.shape[0], wd.shape[0])
+        self.thi.thi_rmsnorm_swiglu_mlp(x, gamma, eps, wg, wu, wd, (out if in_place else res), out, self.ws)
+        return out
+
     def rmsnorm_qkv_rope(self, x, gamma, eps, w, pos, theta, n_rot, head_dim):
         out = new_out(x.shape[0], w.shape[0])
         self.thi.thi_rmsnorm_qkv_rope(x, gamma, eps, w, pos, theta, n_rot, head_dim, out, self.ws)

@@ -335,6 +335,56 @@ def test_rope_on_layer_configs(thi, oracle_mod, cfg_id, ms):
         assert np.isfinite(got.astype(np.float32)).all()
 
 
+# ------------------------------------- residual epilogues, RMSNorm in front of the MLP
+LAYER_CLOSING = [
+    (1, 272, 1376, 328, 0), (5, 136, 264, 200, 0), (16, 4096, 4096, 1376, 0), (32, 640, 2056, 1032, 1),
+    (8, 4096, 1024, 2048, 3), (17, 100, 1160, 512, 3), (40, 272, 520, 328, 0), (160, 272, 520, 328, 0),
+    (300, 520, 328, 264, 2), (256, 256, 256, 512, 2),
+]
+
+
+@pytest.mark.parametrize("M,N,K,I,family", LAYER_CLOSING)
+def test_residual_and_normalised_mlp(thi, oracle_mod, M, N, K, I, family):
+    """out = res + x W^T (any projection that closes a residual block) and the MLP with the
+    post-attention RMSNorm fused in front and the residual added behind; also in place."""
+    say(f"[case] layer-closing operators M={M} N={N} K={K} I={I} family={family}")
+    x, w, g = synth.random_problem(6100 + M + N + K, M, N, K)
+    rng = np.random.Generator(np.random.Philox(key=6200 + M + N + K + I))
+    res = f16(rng.standard_normal((M, N)))
+    wg, wu = f16(rng.standard_normal((I, K)) * 0.05), f16(rng.standard_normal((I, K)) * 0.05)
+    wd = f16(rng.standard_normal((K, I)) * 0.05)
+    res2 = f16(rng.standard_normal((M, K)))
+    r = Runner(M, K, I, max(N, K))
+    prev = thi.thi_set_kernel_family(family)
+    try:
+        a = to_host(r.linear_residual(to_dev(x), to_dev(w), to_dev(res)))
+        a_in = to_host(r.linear_residual(to_dev(x), to_dev(w), to_dev(res), in_place=True))
+        b = to_host(r.rmsnorm_swiglu_mlp(to_dev(x), to_dev(g), 1e-6, to_dev(wg), to_dev(wu), to_dev(wd), to_dev(res2)))
+        b_in = to_host(r.rmsnorm_swiglu_mlp(to_dev(x), to_dev(g), 1e-6, to_dev(wg), to_dev(wu), to_dev(wd), to_dev(res2),
+                                            in_place=True))
+        c = to_host(r.rmsnorm_swiglu_mlp(to_dev(x), to_dev(g), 1e-6, to_dev(wg), to_dev(wu), to_dev(wd)))
+    finally:
+        thi.thi_set_kernel_family(prev)
+    y, s = oracle_mod.linear_residual(x, w, res)
+    check(a, y, s, "linear_residual", argmax=False)
+    assert np.array_equal(a.view(np.uint16), a_in.view(np.uint16)), "in-place residual differs"
+    y, s = oracle_mod.rmsnorm_swiglu_mlp(x, g, 1e-6, wg, wu, wd, res=res2)
+    check(b, y, s, "rmsnorm_swiglu_mlp + residual", argmax=False)
+    assert np.array_equal(b.view(np.uint16), b_in.view(np.uint16)), "in-place MLP residual differs"
+    y, s = oracle_mod.rmsnorm_swiglu_mlp(x, g, 1e-6, wg, wu, wd)
+    check(c, y, s, "rmsnorm_swiglu_mlp", argmax=False)
+
+
+def test_layer_closing_argument_errors(thi):
+    import torch
+    M, N, K, I = 2, 64, 64, 64
+    r = Runner(M, K, I, N)
+    z = lambda *sh: torch.zeros(sh, dtype=torch.float16, device="cuda")
+    assert thi.thi_linear_residual(z(M, K), z(N, K), None, z(M, N), r.ws, check=False) == 1
+    assert thi.thi_rmsnorm_swiglu_mlp(z(M, K), None, 1e-6, z(I, K), z(I, K), z(K, I), None, z(M, K), r.ws, check=False) == 1
+    assert thi.thi_rmsnorm_swiglu_mlp(z(M, K), z(K), 1e-6, z(I, K), z(I, K), z(K, I), None, z(M, K), r.ws, check=False) == 0
+
+
 # ------------------------------------------------- the five layer configs
 def _layer_case(thi, oracle_mod, cfg_id, rows_limit=32):
     cfg = synth.CONFIGS[cfg_id]
