@@ -121,6 +121,11 @@ class LayerBench:
             t.thi_linear(self.h, w["w_down"], self.y, self.ws)
         elif name == "swiglu_mlp":
             t.thi_swiglu_mlp(self.x_mlp, w["w_gate"], w["w_up"], w["w_down"], self.y, self.ws)
+        elif name == "o_proj_residual":
+            t.thi_linear_residual(self.a_o, w["w_o"], self.x_mlp, self.o, self.ws)
+        elif name == "rmsnorm_swiglu_mlp_residual":
+            t.thi_rmsnorm_swiglu_mlp(self.x_mlp, self.gamma, 1e-6, w["w_gate"], w["w_up"], w["w_down"], self.a_o,
+                                     self.y, self.ws)
         else:
             raise KeyError(name)
 
@@ -146,13 +151,13 @@ def op_bytes_flops(cfg, M, name):
     H, I, Nq = cfg.hidden, cfg.inter, cfg.n_qkv
     if name in ("rmsnorm_qkv", "rmsnorm_qkv_rope"):
         return rf.linear_bytes(M, Nq, H, True), rf.linear_flops(M, Nq, H)
-    if name == "o_proj":
+    if name in ("o_proj", "o_proj_residual"):
         return rf.linear_bytes(M, H, H), rf.linear_flops(M, H, H)
     if name == "gate_up":
         return 2.0 * (2 * I * H + M * H + M * I), 2 * rf.linear_flops(M, I, H)
     if name == "down":
         return rf.linear_bytes(M, H, I), rf.linear_flops(M, H, I)
-    if name == "swiglu_mlp":
+    if name in ("swiglu_mlp", "rmsnorm_swiglu_mlp_residual"):
         return 2.0 * (3 * I * H + 2 * M * H), 3 * rf.linear_flops(M, I, H)
     raise KeyError(name)
 
@@ -237,7 +242,8 @@ def main():
     layer_flops = rf.layer_flops(M, cfg.hidden, cfg.n_qkv, cfg.inter)
 
     ops = {}
-    for name in ("rmsnorm_qkv", "rmsnorm_qkv_rope", "o_proj", "gate_up", "down", "swiglu_mlp"):
+    for name in ("rmsnorm_qkv", "rmsnorm_qkv_rope", "o_proj", "gate_up", "down", "swiglu_mlp", "o_proj_residual",
+                 "rmsnorm_swiglu_mlp_residual"):
         ms, _ = lb.time_loop(lambda i, n=name: lb.op(n, i), max(20, args.steps // 2), max(5, args.warmup // 2))
         b, f = op_bytes_flops(cfg, M, name)
         ops[name] = {"us": round(ms * 1e3, 2), "GBps": round(b / (ms * 1e-3) / 1e9, 1),
@@ -247,7 +253,9 @@ def main():
     gu_ms = ops["gate_up"]["us"] * 1e-3
     gu_bytes, gu_flops = op_bytes_flops(cfg, M, "gate_up")
     if decode:
-        roof = {"bound": "hbm", "kernel": "gate_up (skinny_streamk, SwiGLU epilogue)",
+        fam = thi.thi_query_kernel_family(M, cfg.inter, cfg.hidden, 2)
+        roof = {"bound": "hbm",
+                "kernel": f"gate_up ({'skinny_rowslab' if fam == 3 else 'skinny_streamk'}, SwiGLU epilogue)",
                 "achieved": round(gu_bytes / (gu_ms * 1e-3) / 1e9, 1), "peak": rf.MI355X_HBM_GBS, "unit": "GB/s",
                 "traffic": None}
     else:

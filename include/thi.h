@@ -185,6 +185,15 @@ int thi_version(void);
 int thi_set_kernel_family(int family);
 
 /*
+ * Diagnostic: the kernel family (numbered as above, never 0 for valid arguments)
+ * that a call with these extents would run under the current setting.
+ * fused: 0 = plain linear operator, 1 = RMSNorm in front, 2 = gate/up with the
+ * SwiGLU epilogue (N = I rows per matrix).  Returns 0 for invalid arguments.
+ * Reads the current device's compute-unit count; launches nothing.
+ */
+int thi_query_kernel_family(int M, int N, int K, int fused);
+
+/*
  * Measurement probes for the benchmark (they compute nothing useful): what the GPU sustains for the
  * two resources the kernels are bound by, to be reported next to the nominal peaks.
  *

@@ -20,7 +20,7 @@ _lib = None
 EXPORTED_SYMBOLS = (
     "thi_rmsnorm_qkv", "thi_rmsnorm_qkv_rope", "thi_linear", "thi_swiglu_mlp", "thi_swiglu_gate_up",
     "thi_linear_residual", "thi_rmsnorm_swiglu_mlp", "thi_workspace_bytes",
-    "thi_workspace_init", "thi_status_string", "thi_version", "thi_set_kernel_family",
+    "thi_workspace_init", "thi_status_string", "thi_version", "thi_set_kernel_family", "thi_query_kernel_family",
     "thi_probe_stream_read", "thi_probe_mfma_f16",
 )
 
@@ -71,6 +71,8 @@ def load_library():
     lib.thi_status_string.restype = ctypes.c_char_p
     lib.thi_version.argtypes = []
     lib.thi_version.restype = ci
+    lib.thi_query_kernel_family.argtypes = [ci, ci, ci, ci]
+    lib.thi_query_kernel_family.restype = ci
     lib.thi_set_kernel_family.argtypes = [ci]
     lib.thi_set_kernel_family.restype = ci
     lib.thi_probe_stream_read.argtypes = [vp, sz, vp, vp]
@@ -91,6 +93,11 @@ def thi_version() -> int:
 
 def thi_workspace_bytes(op: int, M: int, N_or_H: int, K_or_I: int) -> int:
     return int(load_library().thi_workspace_bytes(int(op), int(M), int(N_or_H), int(K_or_I)))
+
+
+def thi_query_kernel_family(M: int, N: int, K: int, fused: int = 0) -> int:
+    """1 = stream-K decode kernel, 2 = MFMA GEMM, 3 = row-slab decode kernel (what a call would run)."""
+    return int(load_library().thi_query_kernel_family(int(M), int(N), int(K), int(fused)))
 
 
 def thi_set_kernel_family(family: int) -> int:

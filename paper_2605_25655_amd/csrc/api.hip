@@ -311,6 +311,14 @@ const char* thi_status_string(int status)
 
 int thi_version(void) { return THI_VERSION; }
 
+int thi_query_kernel_family(int M, int N, int K, int fused)
+{
+    if (M < 1 || N < 1 || K < 1 || fused < 0 || fused > 2) return 0;
+    if (!use_skinny(M)) return 2;
+    const int epilogue = fused == 1 ? EPI_RMSNORM : fused == 2 ? EPI_SWIGLU : EPI_PLAIN;
+    return use_rowslab(M < SKINNY_GROUP ? M : SKINNY_GROUP, N, K, epilogue, device_cu_count()) ? 3 : 1;
+}
+
 int thi_set_kernel_family(int family)
 {
     if (family < 0 || family > 3) family = 0;
