@@ -54,6 +54,7 @@ def _load():
                                                       f64p, L, L, L]
         i32p = ctypes.POINTER(ctypes.c_int32)
         f32p = ctypes.POINTER(ctypes.c_float)
+        lib.thi_oracle_decode_attention.argtypes = [u16p, u16p, u16p, i32p, ctypes.c_float, f64p, f64p, L, L, L, L, L]
         lib.thi_oracle_rope_inplace.argtypes = [f64p, f64p, i32p, f32p, L, L, L, L]
         lib.thi_oracle_rmsnorm_qkv_rope.argtypes = [u16p, u16p, ctypes.c_float, u16p, i32p, f32p, f64p, f64p,
                                                     L, L, L, L, L]
@@ -187,4 +188,25 @@ def rmsnorm_qkv_rope(x, gamma, eps, w, pos, theta, n_rot: int, head_dim: int):
     """rmsnorm_qkv followed by the rotation of the Q and K columns, in fp64."""
     y, s = rmsnorm_qkv(x, gamma, eps, w)
     rope_inplace(y, s, pos, theta, n_rot, head_dim)
+    return y, s
+
+
+def decode_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, seq_lens: np.ndarray, scale: float):
+    """y[B,Hq,D] = softmax(scale q k^T) v per head over each request's first seq_lens[b] cached positions
+    (q [B,Hq,D]; k, v [B,Hkv,S_max,D]; grouped-query mapping h -> h // (Hq/Hkv)) and S = sum_j p_j |v_j|."""
+    B, Hq, D = q.shape
+    _, Hkv, S_max, _ = k.shape
+    qb, kb, vb = _bits(q, (B, Hq, D)), _bits(k, (B, Hkv, S_max, D)), _bits(v, (B, Hkv, S_max, D))
+    lens = np.ascontiguousarray(seq_lens, dtype=np.int32)
+    if lens.shape != (B,):
+        raise ValueError("seq_lens must be [B]")
+    y = np.empty((B, Hq, D), np.float64)
+    s = np.empty((B, Hq, D), np.float64)
+    rc = _load().thi_oracle_decode_attention(
+        _p16(qb), _p16(kb), _p16(vb), lens.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), ctypes.c_float(scale),
+        _p64(y), _p64(s), B, Hq, Hkv, D, S_max)
+    if rc == -2:
+        raise ValueError("thi_oracle_decode_attention: bad arguments")
+    if rc:
+        raise MemoryError("thi_oracle_decode_attention failed")
     return y, s

@@ -302,3 +302,58 @@ int thi_oracle_rmsnorm_qkv_rope(const uint16_t *x, const uint16_t *gamma, float 
     if (rc) return rc;
     return thi_oracle_rope_inplace(y, s, pos, theta, M, N, n_rot, head_dim);
 }
+
+/*
+ * Decode attention, one new token per request against that request's own key/value cache
+ * (Eq. 6: softmax(Q K^T / sqrt(d)) V per head; Sec. III-D.1: attention is run per request because
+ * every request has its own cache).  Layout taken: q[B,Hq,D]; k, v[B,Hkv,S_max,D] (the positions of
+ * one head are contiguous, as the per-head scheduling of Sec. III-C.2 streams them); request b uses
+ * positions [0, len[b]).  Query head h reads key/value head h / (Hq/Hkv) (grouped-query attention).
+ *   t_j   = scale * sum_d q[b,h,d] * k[b,g,j,d]
+ *   p_j   = exp(t_j - max_j t) / sum_j exp(t_j - max_j t)      (the shift cancels: plain softmax)
+ *   y[b,h,d] = sum_j p_j * v[b,g,j,d],    s[b,h,d] = sum_j p_j * |v[b,g,j,d]|
+ * len[b] = 0 gives y = s = 0.  scale is the fp32 value the GPU entry point receives.
+ */
+int thi_oracle_decode_attention(const uint16_t *q, const uint16_t *k, const uint16_t *v, const int32_t *len,
+                                float scale, double *y, double *s, long B, long Hq, long Hkv, long D, long S_max)
+{
+    if (B < 1 || Hq < 1 || Hkv < 1 || D < 1 || S_max < 1 || Hq % Hkv) return -2;
+    const long group = Hq / Hkv;
+    for (long b = 0; b < B; ++b)
+        if (len[b] < 0 || len[b] > S_max) return -2;
+    int failed = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (long b = 0; b < B; ++b) {
+        for (long h = 0; h < Hq; ++h) {
+            const long L = len[b], g = h / group;
+            double *yo = y + (b * Hq + h) * D;
+            double *so = s ? s + (b * Hq + h) * D : NULL;
+            for (long d = 0; d < D; ++d) { yo[d] = 0.0; if (so) so[d] = 0.0; }
+            if (L == 0) continue;
+            double *t = (double *)malloc((size_t)L * sizeof(double));
+            if (!t) { failed = 1; continue; }
+            const uint16_t *qh = q + (b * Hq + h) * D;
+            const uint16_t *kh = k + ((b * Hkv + g) * S_max) * D;
+            const uint16_t *vh = v + ((b * Hkv + g) * S_max) * D;
+            double tmax = -INFINITY;
+            for (long j = 0; j < L; ++j) {
+                double acc = 0.0;
+                for (long d = 0; d < D; ++d) acc += half_bits_to_double(qh[d]) * half_bits_to_double(kh[j * D + d]);
+                t[j] = (double)scale * acc;
+                if (t[j] > tmax) tmax = t[j];
+            }
+            double denom = 0.0;
+            for (long j = 0; j < L; ++j) { t[j] = exp(t[j] - tmax); denom += t[j]; }
+            for (long j = 0; j < L; ++j) {
+                const double p = t[j] / denom;
+                for (long d = 0; d < D; ++d) {
+                    const double val = half_bits_to_double(vh[j * D + d]);
+                    yo[d] += p * val;
+                    if (so) so[d] += p * fabs(val);
+                }
+            }
+            free(t);
+        }
+    }
+    return failed ? -1 : 0;
+}
