@@ -152,6 +152,30 @@ int thi_rmsnorm_swiglu_mlp(const void* x, const void* gamma, float eps, const vo
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Decode attention for a batch of requests that each add one token to their own
+ * key/value cache (Eq. 6: softmax(Q K^T / sqrt(d)) V per head; Sec. III-D.1: the
+ * attention part of a batch is run request by request because the caches differ;
+ * Sec. III-C.2: Q and O stay on chip, K and V stream by once).
+ *
+ *   out[b,h,:] = sum_j p_j * v[b,g,j,:],  p = softmax_j(scale * q[b,h,:] . k[b,g,j,:]),
+ *   j over [0, seq_lens[b]),  g = h / (Hq/Hkv)   (grouped-query attention; Hkv = Hq is plain
+ *   multi-head attention)
+ *
+ * q [B,Hq,D], out [B,Hq,D], k_cache and v_cache [B,Hkv,S_max,D] (the positions of one head
+ * are contiguous), all fp16 device memory, 16-byte aligned; seq_lens [B] int32 DEVICE memory,
+ * 0 <= seq_lens[b] <= S_max (not checked on the host; a request with 0 positions gets a zero
+ * row; cache contents at positions >= seq_lens[b] are never used).  The cache must already hold
+ * the current token's key and value.  D is 64 or 128, Hq a multiple of Hkv (THI_ERR_SHAPE
+ * otherwise).  scale is usually 1/sqrt(D).  Scores, weights and sums are fp32; one fp16 rounding
+ * at the end.  Workspace: thi_attention_workspace_bytes(), 256-byte aligned, no preparation
+ * needed, may be the workspace of the other calls if large enough.  Reproducible bit for bit.
+ */
+size_t thi_attention_workspace_bytes(int B, int Hq, int Hkv, int D, int S_max);
+int thi_decode_attention(const void* q, const void* k_cache, const void* v_cache, const int* seq_lens, float scale,
+                         void* out, int B, int Hq, int Hkv, int D, int S_max,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Bytes of workspace the given operator needs for the given shape
  * (op = thi_op; (M, N, K) for the first two operators, (M, H, I) for the MLP).
  * Pure host arithmetic: touches no device.  Returns 0 for invalid arguments.

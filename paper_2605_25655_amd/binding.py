@@ -19,7 +19,8 @@ _lib = None
 
 EXPORTED_SYMBOLS = (
     "thi_rmsnorm_qkv", "thi_rmsnorm_qkv_rope", "thi_linear", "thi_swiglu_mlp", "thi_swiglu_gate_up",
-    "thi_linear_residual", "thi_rmsnorm_swiglu_mlp", "thi_workspace_bytes",
+    "thi_linear_residual", "thi_rmsnorm_swiglu_mlp", "thi_decode_attention", "thi_attention_workspace_bytes",
+    "thi_workspace_bytes",
     "thi_workspace_init", "thi_status_string", "thi_version", "thi_set_kernel_family", "thi_query_kernel_family",
     "thi_probe_stream_read", "thi_probe_mfma_f16",
 )
@@ -63,6 +64,10 @@ def load_library():
     lib.thi_linear_residual.restype = ci
     lib.thi_rmsnorm_swiglu_mlp.argtypes = [vp, vp, cf, vp, vp, vp, vp, vp, ci, ci, ci, vp, sz, vp]
     lib.thi_rmsnorm_swiglu_mlp.restype = ci
+    lib.thi_decode_attention.argtypes = [vp, vp, vp, vp, cf, vp, ci, ci, ci, ci, ci, vp, sz, vp]
+    lib.thi_decode_attention.restype = ci
+    lib.thi_attention_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+    lib.thi_attention_workspace_bytes.restype = sz
     lib.thi_workspace_bytes.argtypes = [ci, ci, ci, ci]
     lib.thi_workspace_bytes.restype = sz
     lib.thi_workspace_init.argtypes = [vp, sz, vp]
@@ -120,13 +125,15 @@ def _stream(stream):
 class Workspace:
     """A caller-owned workspace: a torch byte tensor plus the one-time init call."""
 
-    def __init__(self, nbytes: int, device="cuda", stream=None):
+    def __init__(self, nbytes: int, device="cuda", stream=None, init: bool = True):
+        """init=False: for thi_decode_attention alone, whose workspace needs no preparation."""
         import torch
         self.nbytes = int(nbytes)
         self.buffer = torch.empty(self.nbytes + 256, dtype=torch.uint8, device=device)
         off = (-self.buffer.data_ptr()) % 256
         self.ptr = self.buffer.data_ptr() + off
-        thi_workspace_init(self.ptr, self.nbytes, stream)
+        if init:
+            thi_workspace_init(self.ptr, self.nbytes, stream)
 
     @classmethod
     def for_ops(cls, shapes, device="cuda", stream=None):
@@ -206,6 +213,24 @@ def thi_rmsnorm_swiglu_mlp(x, gamma, eps, w_gate, w_up, w_down, residual, out, w
                                                _stream(stream))
     if check and rc != THI_OK:
         raise ThiError(rc, "thi_rmsnorm_swiglu_mlp")
+    return rc
+
+
+def thi_attention_workspace_bytes(B: int, Hq: int, Hkv: int, D: int, S_max: int) -> int:
+    return int(load_library().thi_attention_workspace_bytes(int(B), int(Hq), int(Hkv), int(D), int(S_max)))
+
+
+def thi_decode_attention(q, k_cache, v_cache, seq_lens, scale, out, workspace, stream=None, check: bool = True) -> int:
+    """out[B,Hq,D] = softmax(scale q k^T) v per head over each request's first seq_lens[b] cached positions.
+
+    q, out [B,Hq,D]; k_cache, v_cache [B,Hkv,S_max,D] fp16 device tensors; seq_lens [B] int32 device tensor."""
+    B, Hq, D = q.shape
+    _, Hkv, S_max, _ = k_cache.shape
+    wp, wb = _ws(workspace)
+    rc = load_library().thi_decode_attention(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_lens), ctypes.c_float(scale),
+                                             _ptr(out), B, Hq, Hkv, D, S_max, wp, wb, _stream(stream))
+    if check and rc != THI_OK:
+        raise ThiError(rc, "thi_decode_attention")
     return rc
 
 

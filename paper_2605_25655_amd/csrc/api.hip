@@ -279,6 +279,49 @@ int thi_rmsnorm_swiglu_mlp(const void* x, const void* gamma, float eps, const vo
                           EPI_PLAIN, ws, stream, RopeArgs{nullptr, nullptr, 0, 2}, (const uint16_t*)residual);
 }
 
+size_t thi_attention_workspace_bytes(int B, int Hq, int Hkv, int D, int S_max)
+{
+    if (B < 1 || Hq < 1 || Hkv < 1 || S_max < 1 || (D != 64 && D != 128) || Hq % Hkv) return 0;
+    return round_up((size_t)B * Hq * AT_MAX_SPLIT * (D + 2) * sizeof(float), 256);
+}
+
+int thi_decode_attention(const void* q, const void* k_cache, const void* v_cache, const int* seq_lens, float scale,
+                         void* out, int B, int Hq, int Hkv, int D, int S_max,
+                         void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!q || !k_cache || !v_cache || !seq_lens || !out || !workspace) return THI_ERR_NULL;
+    if (B < 1 || Hq < 1 || Hkv < 1 || S_max < 1 || (D != 64 && D != 128) || Hq % Hkv) return THI_ERR_SHAPE;
+    if ((long)B * Hkv > 65535L * 8 || B > 65535) return THI_ERR_SHAPE;
+    if (misaligned(q, 16) || misaligned(k_cache, 16) || misaligned(v_cache, 16) || misaligned(out, 16) ||
+        misaligned(seq_lens, 4) || misaligned(workspace, 256))
+        return THI_ERR_ALIGN;
+    if (workspace_bytes < thi_attention_workspace_bytes(B, Hq, Hkv, D, S_max)) return THI_ERR_WORKSPACE;
+    (void)hipGetLastError();      // an error another user of the runtime left behind is not ours to report
+    AttnArgs a;
+    a.q = (const uint16_t*)q;
+    a.k = (const uint16_t*)k_cache;
+    a.v = (const uint16_t*)v_cache;
+    a.seq_lens = seq_lens;
+    a.out = (uint16_t*)out;
+    a.part = (float*)workspace;
+    a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.D = D; a.S_max = S_max;
+    a.group = Hq / Hkv;
+    // enough workgroups to fill the chip about four times over, cut along the positions if need be
+    const int gt = attention_heads_per_workgroup(a.group);
+    const int passes = (a.group + gt - 1) / gt;
+    const int quantum = attention_chunk_quantum(D, gt);
+    const long base = (long)B * Hkv * passes;
+    long want = (4L * device_cu_count() + base - 1) / base;
+    if (want < 1) want = 1;
+    if (want > AT_MAX_SPLIT) want = AT_MAX_SPLIT;
+    int chunk = (int)((S_max + want - 1) / want);
+    chunk = (chunk + quantum - 1) / quantum * quantum;
+    a.chunk = chunk;
+    a.nsplit = (S_max + chunk - 1) / chunk;
+    a.scale2 = scale * 1.44269504088896340736f;
+    return launch_attention(a, (hipStream_t)hip_stream) == hipSuccess ? THI_OK : THI_ERR_HIP;
+}
+
 size_t thi_workspace_bytes(int op, int M, int N_or_H, int K_or_I)
 {
     if (op < THI_OP_RMSNORM_QKV || op > THI_OP_SWIGLU_MLP) return 0;

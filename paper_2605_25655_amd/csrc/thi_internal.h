@@ -93,6 +93,24 @@ constexpr int GEMM_MAX_GRID = 2048;   // in units of 128x128 partial tiles (a 25
 size_t gemm_partial_bytes();
 hipError_t launch_gemm(const GemmArgs& a, int epilogue, int num_cus, hipStream_t stream);
 
+// ---- decode attention ---------------------------------------------------------
+struct AttnArgs {
+    const uint16_t* q;       // [B,Hq,D]
+    const uint16_t* k;       // [B,Hkv,S_max,D]
+    const uint16_t* v;       // [B,Hkv,S_max,D]
+    const int* seq_lens;     // [B] live positions per request (device memory)
+    uint16_t* out;           // [B,Hq,D]
+    float* part;             // [B*Hq][nsplit][D + 2]: a chunk's unnormalised output, running maximum, running sum
+    int B, Hq, Hkv, D, S_max;
+    int group;               // Hq / Hkv query heads per cache head
+    int chunk, nsplit;       // positions per chunk (a multiple of the kernel's quantum), chunks per request
+    float scale2;            // softmax scale times log2(e)
+};
+constexpr int AT_MAX_SPLIT = 32;
+int attention_heads_per_workgroup(int group);
+int attention_chunk_quantum(int D, int gt);
+hipError_t launch_attention(const AttnArgs& a, hipStream_t stream);
+
 // Rotate one interleaved pair (a, b) = (y[c], y[c+1]), c even: Algorithm 1's  y*cos + mix*sin  with
 // mix = (-b, a).  fp32 angle and full-range sinf/cosf (positions reach thousands of radians).
 __device__ __forceinline__ void rope_pair(const RopeArgs& r, int m_pos, int c, float& a, float& b)
