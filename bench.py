@@ -38,6 +38,8 @@ def parse_args():
     ap.add_argument("--m", type=int, default=32, help="tokens per step (decode batch or prefill length)")
     ap.add_argument("--rotate-bytes", type=float, default=1.5e9, help="bytes of distinct weight copies to rotate through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--context", type=int, default=2048,
+                    help="cached positions per request for the decode-attention timing (extra, decode only; 0 = skip)")
     ap.add_argument("--sweep", action="store_true", help="also time the other configs/M (extra, not the headline)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="run one plain 1 GiB device copy before the timed region (scales rocprofv3 FETCH_SIZE/WRITE_SIZE)")
@@ -291,6 +293,27 @@ def main():
         "ops": ops,
         "roofline": roof,
     }
+
+    # Extra (not part of the step): decode attention for the same batch, every request with `--context`
+    # cached positions, heads as in the Llama model of this shape.  Algorithmic bytes: K and V read once.
+    if decode and args.context > 0:
+        Hq, Hkv, D = {1: (8, 8, 64), 2: (32, 32, 128), 3: (40, 40, 128), 4: (52, 52, 128), 5: (64, 8, 128)}[args.config]
+        S = args.context
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(4242)
+        qa = torch.randn((M, Hq, D), generator=gen, device="cuda", dtype=torch.float32).half()
+        ka = torch.randn((M, Hkv, S, D), generator=gen, device="cuda", dtype=torch.float32).half()
+        va = torch.randn((M, Hkv, S, D), generator=gen, device="cuda", dtype=torch.float32).half()
+        la = torch.full((M,), S, dtype=torch.int32, device="cuda")
+        oa = torch.empty((M, Hq, D), dtype=torch.float16, device="cuda")
+        wa = thi.Workspace(thi.thi_attention_workspace_bytes(M, Hq, Hkv, D, S), init=False)
+        ms, _ = lb.time_loop(lambda i: thi.thi_decode_attention(qa, ka, va, la, D ** -0.5, oa, wa),
+                             max(20, args.steps // 2), max(5, args.warmup // 2))
+        kv_bytes = 2.0 * M * Hkv * S * D * 2
+        out["decode_attention"] = {"context": S, "q_heads": Hq, "kv_heads": Hkv, "head_dim": D, "us": round(ms * 1e3, 2),
+                                   "GBps": round(kv_bytes / (ms * 1e-3) / 1e9, 1),
+                                   "hbm_frac": round(kv_bytes / (ms * 1e-3) / 1e9 / rf.MI355X_HBM_GBS, 4)}
+        del qa, ka, va, oa, wa
 
     if args.sweep:
         extra = {}
