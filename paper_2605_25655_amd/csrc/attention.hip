@@ -219,6 +219,170 @@ __global__ __launch_bounds__(AT_THREADS) void attn_decode(AttnArgs a)
     }
 }
 
+// Grouped-query variant (D = 128, 4 or 8 query heads per cache head and pass): with several heads per
+// key row the lane-shuffle dot products of attn_decode make the vector ALU the bottleneck, so the scores
+// of 16 positions x up to 16 heads come from four v_mfma_f32_16x16x32_f16 (keys loaded straight into the
+// A-operand layout: lane = (position, 8-element k group); queries resident as the B operand).  A lane
+// then owns the scores of one head at four positions; the running maximum is shared by the four lanes of
+// a head after every block, so all accumulators of a wave refer to the same maximum and merge by plain
+// addition.  The weights reach the lanes that accumulate V (lane = (row group, 16-byte piece), position
+// 4 * row group + u at step u) through one lane permutation per head and step; V stays on the vector ALU.
+template <int GT>
+__global__ __launch_bounds__(AT_THREADS) void attn_decode_gqa(AttnArgs a)
+{
+    constexpr int D = 128;
+    constexpr int WPOS = 16, GPOS = AT_WAVES * WPOS;
+    __shared__ float s_o[AT_WAVES][GT][D];
+    __shared__ float s_m[AT_WAVES][GT], s_l[AT_WAVES][GT];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int split = blockIdx.x, b = blockIdx.z;
+    const int passes = (a.group + GT - 1) / GT;
+    const int g = blockIdx.y / passes, pass = blockIdx.y % passes;
+    const int L = a.seq_lens[b];
+    const int c0 = split * a.chunk;
+    const int c1 = (c0 + a.chunk < L) ? c0 + a.chunk : L;
+    const int h0 = g * a.group + pass * GT;
+    const int heads = (a.group - pass * GT < GT) ? a.group - pass * GT : GT;
+    if (c0 >= c1) {
+        if (L == 0 && split == 0)
+            for (int idx = tid; idx < heads * D; idx += AT_THREADS)
+                a.out[((size_t)b * a.Hq + h0 + idx / D) * D + idx % D] = 0;
+        return;
+    }
+    const int lo = lane & 15, hi = lane >> 4;      // scores: (head column, position quad); V: (piece, row group)
+
+    half8 qb[4];                                    // B operand: head lo, k group hi, per 32-wide k step
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+        uintx4 raw = {0u, 0u, 0u, 0u};
+        if (lo < heads) raw = *reinterpret_cast<const uintx4*>(a.q + ((size_t)(b * a.Hq + h0 + lo)) * D + s4 * 32 + hi * 8);
+        qb[s4] = __builtin_bit_cast(half8, raw);
+    }
+    const uint16_t* kbase = a.k + ((size_t)(b * a.Hkv + g) * a.S_max) * D;
+    const uint16_t* vbase = a.v + ((size_t)(b * a.Hkv + g) * a.S_max) * D + lo * 8;
+
+    float m = -__builtin_inff(), l = 0.f;           // of head lo (l: this lane's four positions only)
+    float o[GT][8];
+#pragma unroll
+    for (int j = 0; j < GT; ++j)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[j][e] = 0.f;
+
+    auto issue = [&](int it, uintx4 (&kr)[4], uintx4 (&vr)[4]) {
+        const int base = c0 + (it * AT_WAVES + wv) * WPOS;
+        int kp = base + lo;                          // A operand: row lo of the block
+        kp = kp < c1 ? kp : c1 - 1;
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) kr[s4] = ld_stream(kbase + (size_t)kp * D + s4 * 32 + hi * 8);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            int vp = base + 4 * hi + u;
+            vp = vp < c1 ? vp : c1 - 1;
+            vr[u] = ld_stream(vbase + (size_t)vp * D);
+        }
+    };
+
+    const int n_it = (c1 - c0 + GPOS - 1) / GPOS;
+    uintx4 kn[4], vn[4];
+    issue(0, kn, vn);
+    for (int it = 0; it < n_it; ++it) {
+        uintx4 kc[4], vc[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { kc[u] = kn[u]; vc[u] = vn[u]; }
+        issue(it + 1, kn, vn);
+        const int base = c0 + (it * AT_WAVES + wv) * WPOS;
+
+        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, kc[s4]), qb[s4], acc, 0, 0, 0);
+        float t[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) t[i] = (base + 4 * hi + i < c1) ? acc[i] * a.scale2 : -__builtin_inff();
+        float mb = __builtin_fmaxf(__builtin_fmaxf(t[0], t[1]), __builtin_fmaxf(t[2], t[3]));
+        mb = __builtin_fmaxf(mb, __shfl_xor(mb, 16));
+        mb = __builtin_fmaxf(mb, __shfl_xor(mb, 32));
+        const float mn = __builtin_fmaxf(m, mb);
+        const float ms = (mn == -__builtin_inff()) ? 0.f : mn;
+        const float corr = exp2_fast(m - ms);
+        float p[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) p[i] = exp2_fast(t[i] - ms);
+        l = l * corr + ((p[0] + p[1]) + (p[2] + p[3]));
+        m = mn;
+        // the accumulators are rescaled only when some head's maximum moved (rare after the first blocks)
+        if (__builtin_amdgcn_ballot_w64(corr != 1.0f) != 0ull) {
+#pragma unroll
+            for (int j = 0; j < GT; ++j) {
+                const float cj = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, corr), j));
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[j][e] *= cj;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const bool live = base + 4 * hi + u < c1;
+            float vf[8];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const unsigned w = live ? vc[u][e] : 0u;
+                const half2_t hv = __builtin_bit_cast(half2_t, w);
+                vf[2 * e] = (float)hv[0];
+                vf[2 * e + 1] = (float)hv[1];
+            }
+#pragma unroll
+            for (int j = 0; j < GT; ++j) {
+                const float pj = __shfl(p[u], j + 16 * hi);      // head j's weight of position 4*hi + u
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[j][e] = __builtin_fmaf(pj, vf[e], o[j][e]);
+            }
+        }
+    }
+
+    // the wave's four row groups: same maximum, so sums simply add
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+#pragma unroll
+    for (int j = 0; j < GT; ++j)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            o[j][e] += __shfl_xor(o[j][e], 16);
+            o[j][e] += __shfl_xor(o[j][e], 32);
+        }
+    if (hi == 0) {
+#pragma unroll
+        for (int j = 0; j < GT; ++j)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s_o[wv][j][lo * 8 + e] = o[j][e];
+        if (lo < GT) { s_m[wv][lo] = m; s_l[wv][lo] = l; }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < heads * D; idx += AT_THREADS) {
+        const int j = idx / D, d = idx % D;
+        float mn = s_m[0][j];
+#pragma unroll
+        for (int w = 1; w < AT_WAVES; ++w) mn = __builtin_fmaxf(mn, s_m[w][j]);
+        const float ms = (mn == -__builtin_inff()) ? 0.f : mn;
+        float lf = 0.f, of = 0.f;
+#pragma unroll
+        for (int w = 0; w < AT_WAVES; ++w) {        // fixed order: waves 0..3
+            const float cw = exp2_fast(s_m[w][j] - ms);
+            lf += s_l[w][j] * cw;
+            of += s_o[w][j][d] * cw;
+        }
+        const size_t bh = (size_t)b * a.Hq + h0 + j;
+        if (a.nsplit == 1) {
+            a.out[bh * D + d] = to_half_bits(of / lf);
+        } else {
+            float* po = a.part + (bh * a.nsplit + split) * (D + 2);
+            po[d] = of;
+            if (d == 0) { po[D] = mn; po[D + 1] = lf; }
+        }
+    }
+}
+
 // Second pass when the positions were cut into chunks: one workgroup per (request, query head) merges
 // the chunks' triples in chunk order and normalises.
 template <int D>
@@ -255,8 +419,14 @@ hipError_t launch_d(const AttnArgs& a, int gt, hipStream_t stream)
     switch (gt) {
     case 1: launch_decode<D, 1>(a, grid, stream); break;
     case 2: launch_decode<D, 2>(a, grid, stream); break;
-    case 4: launch_decode<D, 4>(a, grid, stream); break;
-    default: launch_decode<D, 8>(a, grid, stream); break;
+    case 4:
+        if (D == 128) hipLaunchKernelGGL((attn_decode_gqa<4>), grid, dim3(AT_THREADS), 0, stream, a);
+        else launch_decode<D, 4>(a, grid, stream);
+        break;
+    default:
+        if (D == 128) hipLaunchKernelGGL((attn_decode_gqa<8>), grid, dim3(AT_THREADS), 0, stream, a);
+        else launch_decode<D, 8>(a, grid, stream);
+        break;
     }
     if (a.nsplit > 1)
         hipLaunchKernelGGL((attn_combine<D>), dim3((unsigned)(a.B * a.Hq)), dim3(D), 0, stream, a);
@@ -267,11 +437,11 @@ hipError_t launch_d(const AttnArgs& a, int gt, hipStream_t stream)
 
 int attention_heads_per_workgroup(int group) { return group >= 8 ? 8 : group >= 4 ? 4 : group >= 2 ? 2 : 1; }
 
-// positions per workgroup iteration: chunks are whole multiples of it
+// chunks are whole multiples of this (a multiple of every kernel's positions per workgroup iteration)
 int attention_chunk_quantum(int D, int gt)
 {
-    const int u = gt >= 4 ? 2 : 4;
-    return AT_WAVES * (64 / (D / 8)) * u;
+    (void)D; (void)gt;
+    return 128;
 }
 
 hipError_t launch_attention(const AttnArgs& a, hipStream_t stream)

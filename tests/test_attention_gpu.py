@@ -65,6 +65,9 @@ CASES = [
     (40, 32, 32, 128, 200, None),                     # many workgroups: one pass per request
     (1, 8, 1, 128, 4096, [4096]),                     # one request, long: cut into chunks
     (2, 64, 8, 128, 2050, [2050, 999]),               # 70B-like heads
+    (2, 8, 2, 128, 333, [333, 200]),                  # group of 4, head size 128
+    (1, 24, 2, 128, 450, [450]),                      # group of 12: a pass of 8 heads and a pass of 4
+    (3, 32, 8, 128, 150, [150, 17, 16]),              # Llama-3-8B-like heads, short
 ]
 
 
