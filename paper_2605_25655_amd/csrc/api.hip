@@ -38,21 +38,28 @@ struct Workspace {
     float* ssq;
     unsigned* handover;
     float* partials;
-    uint16_t* h;
+    uint16_t* h;     // MLP: silu(gate)*up [M,I]
+    uint16_t* xn;    // prefill: normalised activations [M,K] of the RMSNorm-fronted operators
 };
 
 // Both kernel families keep their own regions (either may be forced for any M).
 size_t fixed_bytes() { return WS_COUNTER_BYTES + WS_SSQ_BYTES + round_up(skinny_handover_bytes(), 256); }
 
-size_t workspace_need(int op, int M, int a, int b)
+// (op, M, a, b) = (RMSNORM_QKV or LINEAR, M, N, K) or (SWIGLU_MLP, M, H, I)
+size_t h_bytes(int op, int M, int b) { return op == THI_OP_SWIGLU_MLP ? round_up((size_t)M * (size_t)b * 2, 256) : 0; }
+size_t xn_bytes(int op, int M, int a, int b)
 {
-    size_t need = fixed_bytes() + gemm_partial_bytes();
-    if (op == THI_OP_SWIGLU_MLP) need += round_up((size_t)M * (size_t)b * 2, 256);
-    (void)a;
-    return need;
+    if (op == THI_OP_RMSNORM_QKV) return round_up((size_t)M * (size_t)b * 2, 256);     // [M,K]
+    if (op == THI_OP_SWIGLU_MLP) return round_up((size_t)M * (size_t)a * 2, 256);      // [M,H]
+    return 0;
 }
 
-Workspace carve(void* base)
+size_t workspace_need(int op, int M, int a, int b)
+{
+    return fixed_bytes() + gemm_partial_bytes() + h_bytes(op, M, b) + xn_bytes(op, M, a, b);
+}
+
+Workspace carve(void* base, size_t h_size = 0)
 {
     char* p = static_cast<char*>(base);
     Workspace w;
@@ -61,6 +68,7 @@ Workspace carve(void* base)
     w.handover = reinterpret_cast<unsigned*>(p + WS_COUNTER_BYTES + WS_SSQ_BYTES);
     w.partials = reinterpret_cast<float*>(p + fixed_bytes());
     w.h = reinterpret_cast<uint16_t*>(p + fixed_bytes() + gemm_partial_bytes());
+    w.xn = reinterpret_cast<uint16_t*>(p + fixed_bytes() + gemm_partial_bytes() + h_size);
     return w;
 }
 
@@ -139,6 +147,15 @@ int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const ui
     {
         const long tn = (N + 63) / 64, tm = (M + 127) / 128;     // upper bound on tiles of any configuration
         if (tn * tm > WS_MAX_COUNTERS) return THI_ERR_SHAPE;
+    }
+    // Prefill: RMSNorm runs as a pass of its own (a few percent of the GEMM's time) so that the GEMM can
+    // take both operands straight from memory into LDS in its fastest configuration; the decode kernels
+    // keep it fused, where a second pass over x would cost a launch.
+    if (is_rms(epilogue)) {
+        if (launch_rmsnorm_rows(x, gamma, eps, ws.xn, M, K, stream) != hipSuccess) return THI_ERR_HIP;
+        x = ws.xn;
+        gamma = nullptr;
+        epilogue = epilogue == EPI_RMSNORM ? EPI_PLAIN : epilogue == EPI_RMSNORM_ROPE ? EPI_ROPE : EPI_SWIGLU;
     }
     GemmArgs g;
     g.x = x;
@@ -224,7 +241,7 @@ int thi_swiglu_mlp(const void* x, const void* w_gate, const void* w_up, const vo
     if (misaligned(x, 16) || misaligned(w_gate, 16) || misaligned(w_up, 16) || misaligned(w_down, 16) ||
         misaligned(out, 16))
         return THI_ERR_ALIGN;
-    Workspace ws = carve(workspace);
+    Workspace ws = carve(workspace, h_bytes(THI_OP_SWIGLU_MLP, M, I));
     hipStream_t stream = (hipStream_t)hip_stream;
     rc = run_projection((const uint16_t*)x, nullptr, 0.f, (const uint16_t*)w_gate, (const uint16_t*)w_up, ws.h,
                         M, I, H, I, EPI_SWIGLU, ws, stream);
@@ -270,7 +287,7 @@ int thi_rmsnorm_swiglu_mlp(const void* x, const void* gamma, float eps, const vo
     if (misaligned(x, 16) || misaligned(gamma, 16) || misaligned(w_gate, 16) || misaligned(w_up, 16) ||
         misaligned(w_down, 16) || misaligned(out, 16) || (residual && misaligned(residual, 16)))
         return THI_ERR_ALIGN;
-    Workspace ws = carve(workspace);
+    Workspace ws = carve(workspace, h_bytes(THI_OP_SWIGLU_MLP, M, I));
     hipStream_t stream = (hipStream_t)hip_stream;
     rc = run_projection((const uint16_t*)x, (const uint16_t*)gamma, eps, (const uint16_t*)w_gate,
                         (const uint16_t*)w_up, ws.h, M, I, H, I, EPI_RMSNORM_SWIGLU, ws, stream);

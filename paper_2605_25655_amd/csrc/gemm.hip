@@ -122,7 +122,7 @@ __device__ __forceinline__ void store_fragment(const GemmArgs& a, int tile_n, in
             float v[4];
 #pragma unroll
             for (int c = 0; c < 4; ++c) v[c] = f[4 * aa + c] * scale;
-            if (EPI == EPI_RMSNORM_ROPE) {               // the quad holds two complete pairs of one token
+            if (has_rope(EPI)) {                         // the quad holds two complete pairs of one token
                 const int mp = a.rope.pos[m];
                 rope_pair(a.rope, mp, n, v[0], v[1]);
                 rope_pair(a.rope, mp, n + 2, v[2], v[3]);
@@ -561,15 +561,14 @@ hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream
     } while (0)
     switch (epilogue) {
     case EPI_PLAIN: THI_LAUNCH(EPI_PLAIN); break;
-    case EPI_RMSNORM:
-        if constexpr (ALL) THI_LAUNCH(EPI_RMSNORM);
+    case EPI_ROPE:               // 128x128 configuration only: in the 256x256 one the rotary epilogue spills registers
+        if constexpr (ALL) THI_LAUNCH(EPI_ROPE);
+        else return hipErrorInvalidValue;
         break;
-    case EPI_RMSNORM_ROPE:
-        if constexpr (ALL) THI_LAUNCH(EPI_RMSNORM_ROPE);
-        break;
+    case EPI_RMSNORM:            // RMSNorm runs as a pass of its own in front of the GEMM (see the dispatcher);
+    case EPI_RMSNORM_ROPE:       // the fused variants of this kernel are kept in the source but not built
     case EPI_RMSNORM_SWIGLU:
-        if constexpr (ALL) THI_LAUNCH(EPI_RMSNORM_SWIGLU);
-        break;
+        return hipErrorInvalidValue;
     default: THI_LAUNCH(EPI_SWIGLU); break;
     }
 #undef THI_LAUNCH
@@ -588,6 +587,45 @@ double config_cost(const GemmArgs& a, int epilogue, int B, int grid)
 
 }  // namespace
 
+namespace {
+
+// One workgroup per token row: sum of squares in fp32, then the normalised row in fp16 (one rounding of
+// x * r * gamma).  A memory-bound pass over M*K elements, a few percent of the GEMM it feeds.
+__global__ __launch_bounds__(256) void rmsnorm_rows(const uint16_t* x, const uint16_t* gamma, float eps, uint16_t* xn, int K)
+{
+    __shared__ float s_part[4];
+    const uint16_t* row = x + (size_t)blockIdx.x * K;
+    uint16_t* dst = xn + (size_t)blockIdx.x * K;
+    float ss = 0.f;
+    for (int k = threadIdx.x * 8; k < K; k += 256 * 8) {
+        const half8 v = __builtin_bit_cast(half8, *reinterpret_cast<const uintx4*>(row + k));
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { const float f = (float)v[e]; ss = __builtin_fmaf(f, f, ss); }
+    }
+#pragma unroll
+    for (int sh = 32; sh >= 1; sh >>= 1) ss += __shfl_xor(ss, sh);
+    if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float r = 1.0f / __builtin_sqrtf(((s_part[0] + s_part[1]) + (s_part[2] + s_part[3])) / (float)K + eps);
+    for (int k = threadIdx.x * 8; k < K; k += 256 * 8) {
+        const half8 v = __builtin_bit_cast(half8, *reinterpret_cast<const uintx4*>(row + k));
+        const half8 g = __builtin_bit_cast(half8, *reinterpret_cast<const uintx4*>(gamma + k));
+        half8 o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = (_Float16)((float)v[e] * r * (float)g[e]);
+        *reinterpret_cast<uintx4*>(dst + k) = __builtin_bit_cast(uintx4, o);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_rmsnorm_rows(const uint16_t* x, const uint16_t* gamma, float eps, uint16_t* xn, int M, int K,
+                               hipStream_t stream)
+{
+    hipLaunchKernelGGL(rmsnorm_rows, dim3((unsigned)M), dim3(256), 0, stream, x, gamma, eps, xn, K);
+    return hipGetLastError();
+}
+
 size_t gemm_partial_bytes() { return (size_t)GEMM_MAX_GRID * 2 * 128 * 128 * sizeof(float); }
 
 hipError_t launch_gemm(const GemmArgs& a, int epilogue, int num_cus, hipStream_t stream)
@@ -595,7 +633,7 @@ hipError_t launch_gemm(const GemmArgs& a, int epilogue, int num_cus, hipStream_t
     int g_big = num_cus, g_small = 2 * num_cus;        // workgroups that fit: one resp. two per CU
     if (g_big * 4 > GEMM_MAX_GRID) g_big = GEMM_MAX_GRID / 4;
     if (g_small > GEMM_MAX_GRID) g_small = GEMM_MAX_GRID;
-    bool big = !is_rms(epilogue) && (a.K % 64 == 0);
+    bool big = !is_rms(epilogue) && !has_rope(epilogue) && (a.K % 64 == 0);
     if (big) {
         big = config_cost(a, epilogue, 256, g_big) <= config_cost(a, epilogue, 128, g_small);
     }

@@ -16,9 +16,11 @@ typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 // What is fused around the linear operator.  RMSNORM*: x*gamma in front, the 1/rms scale behind.
 // *SWIGLU: gate and up rows interleaved, silu(g)*u behind.  The plain and RMSNorm kinds add a residual
 // behind the product when the argument block carries one.
-enum Epilogue { EPI_PLAIN = 0, EPI_RMSNORM = 1, EPI_SWIGLU = 2, EPI_RMSNORM_ROPE = 3, EPI_RMSNORM_SWIGLU = 4 };
+// EPI_ROPE (GEMM only): the rotary epilogue on activations that were normalised by a pass of their own.
+enum Epilogue { EPI_PLAIN = 0, EPI_RMSNORM = 1, EPI_SWIGLU = 2, EPI_RMSNORM_ROPE = 3, EPI_RMSNORM_SWIGLU = 4, EPI_ROPE = 5 };
 constexpr bool is_rms(int epi) { return epi == EPI_RMSNORM || epi == EPI_RMSNORM_ROPE || epi == EPI_RMSNORM_SWIGLU; }
 constexpr bool is_swiglu(int epi) { return epi == EPI_SWIGLU || epi == EPI_RMSNORM_SWIGLU; }
+constexpr bool has_rope(int epi) { return epi == EPI_RMSNORM_ROPE || epi == EPI_ROPE; }
 
 // Rotary embedding applied in the epilogue (EPI_RMSNORM_ROPE): interleaved pairs (2i, 2i+1) of every
 // head in columns [0, n_rot); angle = pos[m] * theta[i].
@@ -92,6 +94,9 @@ struct GemmArgs {
 constexpr int GEMM_MAX_GRID = 2048;   // in units of 128x128 partial tiles (a 256x256 tile takes four)
 size_t gemm_partial_bytes();
 hipError_t launch_gemm(const GemmArgs& a, int epilogue, int num_cus, hipStream_t stream);
+// xn[m,k] = fp16(x[m,k] * gamma[k] / sqrt(mean_k x[m,:]^2 + eps)): the prefill path's RMSNorm pass
+hipError_t launch_rmsnorm_rows(const uint16_t* x, const uint16_t* gamma, float eps, uint16_t* xn, int M, int K,
+                               hipStream_t stream);
 
 // ---- decode attention ---------------------------------------------------------
 struct AttnArgs {
