@@ -225,8 +225,9 @@ __global__ __launch_bounds__(AT_THREADS) void attn_decode(AttnArgs a)
 // A-operand layout: lane = (position, 8-element k group); queries resident as the B operand).  A lane
 // then owns the scores of one head at four positions; the running maximum is shared by the four lanes of
 // a head after every block, so all accumulators of a wave refer to the same maximum and merge by plain
-// addition.  The weights reach the lanes that accumulate V (lane = (row group, 16-byte piece), position
-// 4 * row group + u at step u) through one lane permutation per head and step; V stays on the vector ALU.
+// addition.  The weights reach the lanes that accumulate V (lane = (row group, 16-byte piece), positions
+// 4 * row group + u) as fp16 pairs through one lane permutation per head and pair of positions; V stays on
+// the vector ALU (packed fp16 dot products into fp32), two positions per instruction.
 template <int GT>
 __global__ __launch_bounds__(AT_THREADS) void attn_decode_gqa(AttnArgs a)
 {
@@ -234,6 +235,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_decode_gqa(AttnArgs a)
     constexpr int WPOS = 16, GPOS = AT_WAVES * WPOS;
     __shared__ float s_o[AT_WAVES][GT][D];
     __shared__ float s_m[AT_WAVES][GT], s_l[AT_WAVES][GT];
+    __shared__ uintx4 s_q[4][64];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -253,13 +255,16 @@ __global__ __launch_bounds__(AT_THREADS) void attn_decode_gqa(AttnArgs a)
     }
     const int lo = lane & 15, hi = lane >> 4;      // scores: (head column, position quad); V: (piece, row group)
 
-    half8 qb[4];                                    // B operand: head lo, k group hi, per 32-wide k step
+    // B operand (head lo, k group hi, per 32-wide k step), kept in LDS: every wave reads the same
+    if (wv == 0) {
 #pragma unroll
-    for (int s4 = 0; s4 < 4; ++s4) {
-        uintx4 raw = {0u, 0u, 0u, 0u};
-        if (lo < heads) raw = *reinterpret_cast<const uintx4*>(a.q + ((size_t)(b * a.Hq + h0 + lo)) * D + s4 * 32 + hi * 8);
-        qb[s4] = __builtin_bit_cast(half8, raw);
+        for (int s4 = 0; s4 < 4; ++s4) {
+            uintx4 raw = {0u, 0u, 0u, 0u};
+            if (lo < heads) raw = *reinterpret_cast<const uintx4*>(a.q + ((size_t)(b * a.Hq + h0 + lo)) * D + s4 * 32 + hi * 8);
+            s_q[s4][lane] = raw;
+        }
     }
+    __syncthreads();
     const uint16_t* kbase = a.k + ((size_t)(b * a.Hkv + g) * a.S_max) * D;
     const uint16_t* vbase = a.v + ((size_t)(b * a.Hkv + g) * a.S_max) * D + lo * 8;
 
@@ -270,12 +275,15 @@ __global__ __launch_bounds__(AT_THREADS) void attn_decode_gqa(AttnArgs a)
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[j][e] = 0.f;
 
-    auto issue = [&](int it, uintx4 (&kr)[4], uintx4 (&vr)[4]) {
+    auto issue_k = [&](int it, uintx4 (&kr)[4]) {
         const int base = c0 + (it * AT_WAVES + wv) * WPOS;
         int kp = base + lo;                          // A operand: row lo of the block
         kp = kp < c1 ? kp : c1 - 1;
 #pragma unroll
         for (int s4 = 0; s4 < 4; ++s4) kr[s4] = ld_stream(kbase + (size_t)kp * D + s4 * 32 + hi * 8);
+    };
+    auto issue_v = [&](int it, uintx4 (&vr)[4]) {
+        const int base = c0 + (it * AT_WAVES + wv) * WPOS;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             int vp = base + 4 * hi + u;
@@ -285,19 +293,25 @@ __global__ __launch_bounds__(AT_THREADS) void attn_decode_gqa(AttnArgs a)
     };
 
     const int n_it = (c1 - c0 + GPOS - 1) / GPOS;
-    uintx4 kn[4], vn[4];
-    issue(0, kn, vn);
+    // Register budget (three waves per SIMD need <= 168): the keys of the next block are requested only
+    // after this block's score MFMAs have consumed the current ones (same registers), the values are
+    // one block ahead, and the queries are re-read from LDS as the B operand.
+    uintx4 kreg[4], vn[4];
+    issue_k(0, kreg);
+    issue_v(0, vn);
     for (int it = 0; it < n_it; ++it) {
-        uintx4 kc[4], vc[4];
+        uintx4 vc[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) { kc[u] = kn[u]; vc[u] = vn[u]; }
-        issue(it + 1, kn, vn);
+        for (int u = 0; u < 4; ++u) vc[u] = vn[u];
+        issue_v(it + 1, vn);
         const int base = c0 + (it * AT_WAVES + wv) * WPOS;
 
         floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s4 = 0; s4 < 4; ++s4)
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, kc[s4]), qb[s4], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, kreg[s4]),
+                                                         __builtin_bit_cast(half8, s_q[s4][lane]), acc, 0, 0, 0);
+        issue_k(it + 1, kreg);
         float t[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) t[i] = (base + 4 * hi + i < c1) ? acc[i] * a.scale2 : -__builtin_inff();
@@ -321,22 +335,28 @@ __global__ __launch_bounds__(AT_THREADS) void attn_decode_gqa(AttnArgs a)
                 for (int e = 0; e < 8; ++e) o[j][e] *= cj;
             }
         }
+        // weights times V, two positions per instruction: v_dot2_f32_f16 on (V[u][d], V[u+1][d]) and the
+        // fp16 pair of their weights (weights are in [0,1]: 2^-11 relative rounding), fp32 accumulation
+        half2_t ppair[2];
+        ppair[0] = half2_t{(_Float16)p[0], (_Float16)p[1]};
+        ppair[1] = half2_t{(_Float16)p[2], (_Float16)p[3]};
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const bool live = base + 4 * hi + u < c1;
-            float vf[8];
+        for (int up = 0; up < 2; ++up) {
+            const bool live0 = base + 4 * hi + 2 * up < c1, live1 = base + 4 * hi + 2 * up + 1 < c1;
+            half2_t vpk[8];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const unsigned w = live ? vc[u][e] : 0u;
-                const half2_t hv = __builtin_bit_cast(half2_t, w);
-                vf[2 * e] = (float)hv[0];
-                vf[2 * e + 1] = (float)hv[1];
+                const unsigned w0 = live0 ? vc[2 * up][e] : 0u, w1 = live1 ? vc[2 * up + 1][e] : 0u;
+                vpk[2 * e] = __builtin_bit_cast(half2_t, __builtin_amdgcn_perm(w1, w0, 0x05040100u));
+                vpk[2 * e + 1] = __builtin_bit_cast(half2_t, __builtin_amdgcn_perm(w1, w0, 0x07060302u));
             }
 #pragma unroll
             for (int j = 0; j < GT; ++j) {
-                const float pj = __shfl(p[u], j + 16 * hi);      // head j's weight of position 4*hi + u
+                // head j's weights of positions 4*hi + 2*up and + 1 (held by lane j of this row group)
+                const int bits = __shfl(__builtin_bit_cast(int, ppair[up]), j + 16 * hi);
+                const half2_t pj = __builtin_bit_cast(half2_t, bits);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) o[j][e] = __builtin_fmaf(pj, vf[e], o[j][e]);
+                for (int e = 0; e < 8; ++e) o[j][e] = __builtin_amdgcn_fdot2(vpk[e], pj, o[j][e], false);
             }
         }
     }
