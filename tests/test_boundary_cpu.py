@@ -74,6 +74,19 @@ def test_argument_errors_return_codes_without_launching(lib):
     assert lib.thi_linear(p, p, p, 1, 8, 8, p, 1024, null) == 4
     assert lib.thi_workspace_init(null, 1 << 20, null) == 1
     assert lib.thi_workspace_init(p, 16, null) == 4
+    # the fused variants and decode attention validate the same way
+    assert lib.thi_linear_residual(p, p, null, p, 1, 8, 8, p, big, null) == 1
+    assert lib.thi_linear_residual(p, p, odd, p, 1, 8, 8, p, big, null) == 3
+    assert lib.thi_rmsnorm_swiglu_mlp(p, null, 1e-6, p, p, p, null, p, 1, 8, 8, p, big, null) == 1
+    assert lib.thi_rmsnorm_swiglu_mlp(p, p, 1e-6, p, p, p, null, p, 1, 8, 12, p, big, null) == 2
+    assert lib.thi_decode_attention(p, p, p, null, 1.0, p, 1, 2, 2, 128, 8, p, big, null) == 1
+    assert lib.thi_decode_attention(p, p, p, p, 1.0, p, 1, 3, 2, 128, 8, p, big, null) == 2       # Hq % Hkv
+    assert lib.thi_decode_attention(p, p, p, p, 1.0, p, 1, 2, 2, 96, 8, p, big, null) == 2        # head size
+    assert lib.thi_decode_attention(odd, p, p, p, 1.0, p, 1, 2, 2, 128, 8, p, big, null) == 3
+    assert lib.thi_decode_attention(p, p, p, p, 1.0, p, 1, 2, 2, 128, 8, p, 16, null) == 4
+    assert lib.thi_attention_workspace_bytes(2, 8, 2, 128, 1000) >= 2 * 8 * 130 * 4
+    assert lib.thi_attention_workspace_bytes(2, 8, 3, 128, 1000) == 0
+    assert lib.thi_query_kernel_family(0, 8, 8, 0) == 0 and lib.thi_query_kernel_family(4096, 4096, 4096, 0) == 2
 
 
 def test_kernel_family_switch_roundtrip(lib):
