@@ -257,7 +257,7 @@ def main():
     if decode:
         fam = thi.thi_query_kernel_family(M, cfg.inter, cfg.hidden, 2)
         roof = {"bound": "hbm",
-                "kernel": f"gate_up ({'skinny_rowslab' if fam == 3 else 'skinny_streamk'}, SwiGLU epilogue)",
+                "kernel": f"gate_up ({ {3: 'skinny_rowslab', 4: 'skinny_rowblock'}.get(fam, 'skinny_streamk') }, SwiGLU epilogue)",
                 "achieved": round(gu_bytes / (gu_ms * 1e-3) / 1e9, 1), "peak": rf.MI355X_HBM_GBS, "unit": "GB/s",
                 "traffic": None}
     else:

@@ -203,7 +203,9 @@ int thi_version(void);
  * family for subsequent calls from this process.  family: 0 = automatic
  * (default), 1 = weight-streaming decode kernel with stream-K units,
  * 2 = MFMA GEMM kernels, 3 = weight-streaming decode kernel with row slabs
- * (falls back to 1 where K < 1024).
+ * (16 rows over the whole of K per workgroup at a time), 4 = weight-streaming
+ * decode kernel with row blocks (N / #CUs rows per workgroup, several 16-row
+ * tiles in flight); 3 and 4 fall back to 1 where K < 1024 or K > 32768.
  * Returns the previous setting.  Not needed for normal use.
  */
 int thi_set_kernel_family(int family);

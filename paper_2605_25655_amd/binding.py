@@ -101,7 +101,8 @@ def thi_workspace_bytes(op: int, M: int, N_or_H: int, K_or_I: int) -> int:
 
 
 def thi_query_kernel_family(M: int, N: int, K: int, fused: int = 0) -> int:
-    """1 = stream-K decode kernel, 2 = MFMA GEMM, 3 = row-slab decode kernel (what a call would run)."""
+    """1 = stream-K decode kernel, 2 = MFMA GEMM, 3 = row-slab decode kernel, 4 = row-block decode kernel
+    (what a call would run)."""
     return int(load_library().thi_query_kernel_family(int(M), int(N), int(K), int(fused)))
 
 

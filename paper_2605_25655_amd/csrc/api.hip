@@ -75,36 +75,62 @@ Workspace carve(void* base, size_t h_size = 0)
 bool use_skinny(int M)
 {
     const int fam = g_family.load(std::memory_order_relaxed);
-    if (fam == 1 || fam == 3) return true;
+    if (fam == 1 || fam == 3 || fam == 4) return true;
     if (fam == 2) return false;
     return M <= SKINNY_MAX_M;
 }
 
-// Decode: row slabs (no hand-over between workgroups, but every workgroup reads all of x and the
-// slabs must divide well among the compute units) or stream-K units (perfect balance, a hand-over at
-// the end)?  Decided by a time model in microseconds whose constants were measured on MI355X:
-//   both stream the weights at ~7.0 TB/s;
-//   row slabs : ~2.5 us fixed; slowed by the slots a ragged last round leaves empty, by a last unit
-//               of a wave that is only partly full, by the activation traffic (x1.02 at M<=4, x1.07
-//               at M<=8, x1.28 at M<=16, x2.0 above) and by ~5 % for the RMSNorm prologue;
-//   stream-K  : ~5.5 us fixed plus the hand-over, 0.5 + 0.05 M us up to M = 16 and ~5 us above.
-bool use_rowslab(int M, int N, int K, int epilogue, int cus)
+// Decode: which of the three weight-streaming kernels?
+//   stream-K   : work units of 128 rows x 256 k in equal contiguous shares: perfect balance whatever the
+//                shape, a hand-over between workgroups at the end;
+//   row slabs  : slabs of 16 rows over the whole of K, dealt round-robin: no hand-over, but the slabs
+//                must divide well among the compute units and every wave reads its slice of x per slab;
+//   row blocks : N / #CUs rows per workgroup in one contiguous block, several 16-row tiles in flight
+//                sharing the wave's slice of x: no hand-over, balanced whenever N >> #CUs.
+// Decided by a time model in microseconds whose constants were measured on MI355X.  All three stream the
+// weights at ~7.0 TB/s (t_w); a wave's last unit of 256 k may be partly empty (ragged, slabs and blocks).
+//   stream-K   : ~5.5 us fixed plus the hand-over, 0.5 + 0.05 M us up to M = 16 and ~5 us above;
+//   row slabs  : ~2.5 us fixed; slowed by the slots a ragged last round leaves empty, by the activation
+//                traffic (x1.02 at M<=4, x1.09 at M<=8, x1.15 at M<=16, x1.45 above) and by ~10 % for
+//                the RMSNorm prologue;
+//   row blocks : ~3.8 us fixed (all tiles of a pass finish together: their reduction is not hidden),
+//                1.5 us per further pass over K, 2.5 us more with one or two tiles per workgroup and a
+//                short K (a short pipeline); the activation traffic is shared by the tiles of a pass
+//                (+5 % / +15 % / +40 % at M <= 8 / 16 / 32, divided by the tiles per pass); a ragged
+//                last unit costs about a third of what it costs the slabs; slowed by the rows the
+//                last workgroup lacks.
+enum DecodeKernel { DK_STREAMK = 1, DK_ROWSLAB = 3, DK_ROWBLOCK = 4 };
+int pick_decode_kernel(int M, int N, int K, int epilogue, int cus)
 {
-    if (K < 1024 || K > ROWSLAB_MAX_K) return false;
+    if (K < 1024 || K > ROWSLAB_MAX_K) return DK_STREAMK;
     const int fam = g_family.load(std::memory_order_relaxed);
-    if (fam == 3) return true;
-    if (fam == 1) return false;
+    if (fam == 1) return DK_STREAMK;
+    if (fam == 3) return DK_ROWSLAB;
+    if (fam == 4) return DK_ROWBLOCK;
     const bool swiglu = is_swiglu(epilogue);
+    const int out_per_tile = swiglu ? 8 : 16;
     const double t_w = (swiglu ? 2.0 : 1.0) * (double)N * (double)K * 2.0 / 7.0e6;
-    const long slabs = ((long)N + (swiglu ? 7 : 15)) / (swiglu ? 8 : 16);
+    const int groups = (K + 127) / 128, groups_max = (groups + 7) / 8, units_max = (groups_max + 1) / 2;
+    double ragged = (double)units_max * SK_KC * SK_WAVES / (double)K;
+    if (ragged < 1.0) ragged = 1.0;
+
+    const double t_sk = 5.5 + t_w + (M <= 16 ? 0.5 + 0.05 * M : 5.0);
+
+    const long slabs = ((long)N + out_per_tile - 1) / out_per_tile;
     const long rounds = (slabs + cus - 1) / cus;
     const double fill = (double)slabs / (double)(rounds * cus);
-    const int groups = (K + 127) / 128, groups_max = (groups + 7) / 8, units_max = (groups_max + 1) / 2;
-    const double ragged = (double)units_max * SK_KC * SK_WAVES / (double)K;
-    const double x_cost = M <= 1 ? 1.0 : M <= 4 ? 1.02 : M <= 8 ? 1.07 : M <= 16 ? 1.28 : 2.0;
-    const double t_slab = 2.5 + t_w * x_cost * (ragged > 1.0 ? ragged : 1.0) / fill * (is_rms(epilogue) ? 1.05 : 1.0);
-    const double t_sk = 5.5 + t_w + (M <= 16 ? 0.5 + 0.05 * M : 5.0);
-    return t_slab < t_sk;
+    const double x_slab = M <= 1 ? 1.0 : M <= 4 ? 1.02 : M <= 8 ? 1.09 : M <= 16 ? 1.15 : 1.45;
+    const double t_slab = 2.5 + t_w * x_slab * ragged / fill * (is_rms(epilogue) ? 1.10 : 1.0);
+
+    const RowBlockPlan bp = plan_rowblock(N, epilogue, cus);
+    const double per_pass = (double)bp.per_wg / out_per_tile / bp.passes;      // tiles sharing one load of x
+    const double x_extra = (M <= 4 ? 0.0 : M <= 8 ? 0.05 : M <= 16 ? 0.15 : 0.40) / per_pass;
+    const double lacking = (double)bp.per_wg * cus / (double)N;
+    const double t_block = 3.8 + 1.5 * (bp.passes - 1) + ((bp.tiles <= 2 && K < 16384) ? 2.5 : 0.0) +
+                           t_w * (1.0 + x_extra) * (1.0 + 0.3 * (ragged - 1.0)) * lacking;
+
+    if (t_block < t_slab && t_block < t_sk) return DK_ROWBLOCK;
+    return t_slab < t_sk ? DK_ROWSLAB : DK_STREAMK;
 }
 
 // One fused projection: out[M, ldo] = epilogue( prologue(x)[M,K] * w^T ), any M.
@@ -116,7 +142,8 @@ int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const ui
     const int cus = device_cu_count();
     (void)hipGetLastError();      // an error another user of the runtime left behind is not ours to report
     if (use_skinny(M)) {
-        const bool slab = use_rowslab(M < SKINNY_GROUP ? M : SKINNY_GROUP, N, K, epilogue, cus);
+        const int kernel = pick_decode_kernel(M < SKINNY_GROUP ? M : SKINNY_GROUP, N, K, epilogue, cus);
+        const bool slab = kernel != DK_STREAMK, block = kernel == DK_ROWBLOCK;
         const int rows_per_tile = slab ? (is_swiglu(epilogue) ? 8 : 16) : (is_swiglu(epilogue) ? SK_ROWS / 2 : SK_ROWS);
         const int tiles = (N + rows_per_tile - 1) / rows_per_tile;
         if ((long)tiles * ((K + SK_KC - 1) / SK_KC) > (1L << 30)) return THI_ERR_SHAPE;
@@ -139,8 +166,11 @@ int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const ui
             a.eps = eps;
             a.rope = rope;
             if (rope.pos) a.rope.pos = rope.pos + m0;
-            if ((slab ? launch_rowslab(a, epilogue, cus, stream) : launch_skinny(a, epilogue, cus, stream)) != hipSuccess)
-                return THI_ERR_HIP;
+            hipError_t e;
+            if (!slab) e = launch_skinny(a, epilogue, cus, stream);
+            else if (block) e = launch_rowblock(a, epilogue, cus, stream);
+            else e = launch_rowslab(a, epilogue, cus, stream);
+            if (e != hipSuccess) return THI_ERR_HIP;
         }
         return THI_OK;
     }
@@ -376,12 +406,12 @@ int thi_query_kernel_family(int M, int N, int K, int fused)
     if (M < 1 || N < 1 || K < 1 || fused < 0 || fused > 2) return 0;
     if (!use_skinny(M)) return 2;
     const int epilogue = fused == 1 ? EPI_RMSNORM : fused == 2 ? EPI_SWIGLU : EPI_PLAIN;
-    return use_rowslab(M < SKINNY_GROUP ? M : SKINNY_GROUP, N, K, epilogue, device_cu_count()) ? 3 : 1;
+    return pick_decode_kernel(M < SKINNY_GROUP ? M : SKINNY_GROUP, N, K, epilogue, device_cu_count());
 }
 
 int thi_set_kernel_family(int family)
 {
-    if (family < 0 || family > 3) family = 0;
+    if (family < 0 || family > 4) family = 0;
     return g_family.exchange(family);
 }
 

@@ -44,6 +44,7 @@ namespace {
 template <int P>
 __device__ __forceinline__ int swz_f(int row)
 {
+    if (P == 16) return row & 15;     // 256-byte rows: 16 consecutive rows, 16 different pieces
     if (P == 8) return ((row >> 1) & 7) ^ ((row & 1) << 2);
     return (((row >> 1) ^ (row >> 3)) & 1) | (((row >> 2) & 1) << 1);
 }
@@ -91,7 +92,8 @@ struct Deal {
 // half of the rows) holds, per register quad aa, four consecutive n of one token.
 template <int BN, int BM, int WN, int WM, int EPI>
 __device__ __forceinline__ void store_fragment(const GemmArgs& a, int tile_n, int tile_m, int wn, int wm, int tn,
-                                               int tm, int lr, int lg, const floatx16& f, float scale)
+                                               int tm, int lr, int lg, const floatx16& f, float scale,
+                                               int aa_begin = 0, int aa_end = 4)
 {
     constexpr int JPT = is_swiglu(EPI) ? BN / 2 : BN;
     const int m = tile_m * BM + wm * (BM / WM) + tm * 32 + lr;
@@ -99,6 +101,7 @@ __device__ __forceinline__ void store_fragment(const GemmArgs& a, int tile_n, in
     if (is_swiglu(EPI)) {      // scale: the 1/rms factor when RMSNorm sits in front (else 1)
 #pragma unroll
         for (int aa = 0; aa < 4; aa += 2) {
+            if (aa < aa_begin || aa >= aa_end) continue;
             const int v = wn * (BN / WN) + tn * 32 + 8 * aa;
             const int j = tile_n * JPT + (v >> 4) * 8 + 4 * lg;
             half4 hv;
@@ -118,6 +121,7 @@ __device__ __forceinline__ void store_fragment(const GemmArgs& a, int tile_n, in
     } else {
 #pragma unroll
         for (int aa = 0; aa < 4; ++aa) {
+            if (aa < aa_begin || aa >= aa_end) continue;
             const int n = tile_n * BN + wn * (BN / WN) + tn * 32 + 8 * aa + 4 * lg;
             float v[4];
 #pragma unroll
@@ -149,9 +153,10 @@ __device__ __forceinline__ void store_fragment(const GemmArgs& a, int tile_n, in
     }
 }
 
-// Second pass of the stream-K schedule: one workgroup per (shared tile, accumulator fragment) adds the
-// partial fragments of the tile's contributors in workgroup order and applies the epilogue.  The
-// thread <-> element mapping is the main kernel's, so the partials are read back as they were written.
+// Second pass of the stream-K schedule: one workgroup per (shared tile, accumulator fragment, half of the
+// fragment's register quads) adds the partial fragments of the tile's contributors in workgroup order
+// and applies the epilogue.  The thread <-> element mapping is the main kernel's, so the partials are
+// read back as they were written.  (Halves, not quads: SwiGLU pairs quad 2i with quad 2i+1.)
 template <int BN, int BM, int WN, int WM, int EPI>
 __global__ __launch_bounds__(64 * WN * WM) void gemm_fixup(GemmArgs a, int tiles_m, int ktiles, int sk_tiles, int G)
 {
@@ -159,30 +164,54 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_fixup(GemmArgs a, int tiles
     constexpr int TN = BN / WN / 32, TM = BM / WM / 32;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid / 64;
     const int wn = wv % WN, wm = wv / WN, lr = lane & 31, lg = lane >> 5;
-    const int t = blockIdx.x / (TN * TM), frag = blockIdx.x % (TN * TM);
+    const int half = blockIdx.x & 1, tf = blockIdx.x >> 1;
+    const int t = tf / (TN * TM), frag = tf % (TN * TM);
     const int tn = frag / TM, tm = frag % TM;
     const int U = sk_tiles * ktiles;
     const Deal deal{U / G, U % G};
     const int w_first = deal.owner(t * ktiles), w_last = deal.owner(t * ktiles + ktiles - 1);
-    floatx16 f;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) f[e] = 0.f;
+    floatx4 g0 = {0.f, 0.f, 0.f, 0.f}, g1 = {0.f, 0.f, 0.f, 0.f};      // this half's two register quads
     float sq = 0.f;
     const int ml = wm * (BM / WM) + tm * 32 + lr;
-    for (int wc = w_first; wc <= w_last; ++wc) {
+    // a contributor's partial of this tile: slot 0 if the tile is the first of its share, else slot 1
+    auto part = [&](int wc) -> const floatx4* {
         const int cslot = (deal.begin(wc) / ktiles == t) ? 0 : 1;
-        const floatx4* cs = reinterpret_cast<const floatx4*>(a.partials + ((size_t)wc * 2 + cslot) * (BN * BM));
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const floatx4 v = cs[(frag * 4 + q) * THREADS + tid];
-#pragma unroll
-            for (int c = 0; c < 4; ++c) f[4 * q + c] += v[c];
+        return reinterpret_cast<const floatx4*>(a.partials + ((size_t)wc * 2 + cslot) * (BN * BM)) +
+               (frag * 4 + 2 * half) * THREADS + tid;
+    };
+    auto add = [&](const floatx4& v0, const floatx4& v1) { g0 += v0; g1 += v1; };
+    int wc = w_first;
+    for (; wc + 3 <= w_last; wc += 4) {      // four contributors' loads in flight, added in order
+        const floatx4 *p0 = part(wc), *p1 = part(wc + 1), *p2 = part(wc + 2), *p3 = part(wc + 3);
+        const floatx4 a0 = p0[0], a1 = p0[THREADS], b0 = p1[0], b1 = p1[THREADS];
+        const floatx4 c0 = p2[0], c1 = p2[THREADS], d0 = p3[0], d1 = p3[THREADS];
+        add(a0, a1); add(b0, b1); add(c0, c1); add(d0, d1);
+    }
+    for (; wc <= w_last; ++wc) {
+        const floatx4* p = part(wc);
+        const floatx4 v0 = p[0], v1 = p[THREADS];
+        add(v0, v1);
+    }
+    if (is_rms(EPI)) {
+        for (int w2 = w_first; w2 <= w_last; ++w2) {
+            const int cslot = (deal.begin(w2) / ktiles == t) ? 0 : 1;
+            sq += a.ssq[((size_t)w2 * 2 + cslot) * BM + ml];
         }
-        if (is_rms(EPI)) sq += a.ssq[((size_t)wc * 2 + cslot) * BM + ml];
     }
     float scale = 1.0f;
     if (is_rms(EPI)) scale = 1.0f / __builtin_sqrtf(sq / (float)a.K + a.eps);
-    store_fragment<BN, BM, WN, WM, EPI>(a, t / tiles_m, t % tiles_m, wn, wm, tn, tm, lr, lg, f, scale);
+    floatx16 f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) f[e] = 0.f;
+    if (half == 0) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) { f[c] = g0[c]; f[4 + c] = g1[c]; }
+    } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) { f[8 + c] = g0[c]; f[12 + c] = g1[c]; }
+    }
+    store_fragment<BN, BM, WN, WM, EPI>(a, t / tiles_m, t % tiles_m, wn, wm, tn, tm, lr, lg, f, scale, 2 * half,
+                                        2 * half + 2);
 }
 
 // BN x BM output tile, WN x WM waves; wave tile (BN/WN) x (BM/WM) built from 32x32 MFMA tiles.
@@ -204,8 +233,10 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
     constexpr bool W_DMA = !KTAIL;                           // weight tile: global -> LDS directly
     constexpr bool X_DMA = !KTAIL && !is_rms(EPI);     // activation tile: same unless it is transformed
     constexpr int STAGE = (BN + BM) * GPIECES;   // 16-byte units per stage: weight tile, then activation tile
-    static_assert(NS >= 2 && NS <= 4 && (KSTEPS % 2) == 0, "pipeline shape");
-    static_assert(!is_swiglu(EPI) || KTAIL || ROWS_PER_DMA == 8, "gate/up interleave assumes 8-row direct loads");
+    // A direct weight load takes a wave-uniform base; with SwiGLU and 16 tile rows per load (GK = 32) one
+    // load spans a gate block and an up block, so that variant keeps per-lane 64-bit addresses.
+    constexpr bool W_SBASE = !(is_swiglu(EPI) && ROWS_PER_DMA != 8);
+    static_assert(NS >= 2 && NS <= 8 && (KSTEPS % 2) == 0, "pipeline shape");
     static_assert(WPASS >= 1 && XPASS >= 1, "tile too small for the thread count");
 
     extern __shared__ uintx4 smem[];
@@ -272,7 +303,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
                 const int j0 = tile_n * JPT;                         // first row of the tile: always valid
                 int j = j0 + (v >> 4) * 8 + (v & 7);
                 j = j < a.N ? j : a.N - 1;
-                if (W_DMA) {
+                if (W_DMA && W_SBASE) {
                     // ROWS_PER_DMA = 8: a wave instruction covers 8 gate rows or the 8 matching up rows
                     wsrc[i] = ((blk & 1) ? a.w1 : a.w0) + (size_t)j0 * K;
                     woff[i] = (unsigned)((j - j0) * K + piece * 8) * 2u;
@@ -319,8 +350,10 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
         auto load_w = [&](int kt, int buf) {      // DMA: lands in stage buf; else: into wreg
 #pragma unroll
             for (int i = 0; i < WPASS; ++i) {
-                if (W_DMA) {
+                if (W_DMA && W_SBASE) {
                     dma16_sbase(wsrc[i] + kt * GK, woff[i], smem + buf * STAGE + (wv * WPASS + i) * 64);
+                } else if (W_DMA) {
+                    dma16(wsrc[i] + kt * GK, smem + buf * STAGE + (wv * WPASS + i) * 64);
                 } else {
                     const bool kok = kt * GK + vp * 8 < K;
                     uintx4 v = *reinterpret_cast<const uintx4*>(wsrc[i] + (kok ? kt * GK : -vp * 8));
@@ -433,10 +466,16 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
             // behind it (up to NS-2 of them) are still in flight.  The compiler does not carry these
             // loads across the loop edge, hence the explicit wait.
             if (LPT > 0) {
-                const int behind = nk - 2 - it;      // k-tiles after it+1 that have been requested
-                if (NS <= 2 || behind <= 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                else if (NS == 3 || behind == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPT) : "memory");
-                else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPT) : "memory");
+                int behind = nk - 2 - it;            // k-tiles after it+1 that have been requested
+                behind = behind < NS - 2 ? behind : NS - 2;
+                static_assert((NS - 2) * LPT < 64, "wait count out of range");
+                if (behind <= 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                else if (behind == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPT) : "memory");
+                else if (behind == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NS > 3 ? 2 * LPT : 0) : "memory");
+                else if (behind == 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NS > 4 ? 3 * LPT : 0) : "memory");
+                else if (behind == 4) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NS > 5 ? 4 * LPT : 0) : "memory");
+                else if (behind == 5) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NS > 6 ? 5 * LPT : 0) : "memory");
+                else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NS > 7 ? 6 * LPT : 0) : "memory");
             }
             __syncthreads();
             if (it + NS < nk) {
@@ -497,26 +536,32 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
     }
 }
 
-// Time model of the two ways to run `tiles` tiles of edge B on `grid` workgroups (measured speeds:
-// ~1050 TFLOP/s with 256-tiles, ~900 with 128-tiles, for the whole chip):
+// Time model of the two ways to run `tiles` tiles of BN x BM on `grid` workgroups:
 //   whole tiles only : ceil(tiles / grid) rounds;
 //   stream-K remainder: floor(tiles / grid) rounds, the ragged remainder shared equally, plus the second
 //                       pass -- one more launch and the partial tiles' round trip through memory (about
 //                       grid + remainder partial tiles written and read, ~4 TB/s).
+// A tile's time is the larger of its arithmetic (measured whole-chip speeds: ~1050 TFLOP/s with
+// 256x256 tiles, ~900 with 128x128) and, where there is one token tile only (every weight panel is
+// then read exactly once, by one workgroup), its weight traffic at the measured streaming rate.
 struct Schedule {
     int sk_tiles;      // tiles cut into k-steps and dealt stream-K (0: whole tiles only)
     double us;         // modelled time
 };
-Schedule plan_schedule(int tiles, int grid, int B, int K)
+Schedule plan_schedule(int tiles, int tiles_m, int grid, int BN, int BM, int K)
 {
-    const double tflops = (B == 256) ? 1050.0 : 900.0;
-    const double tile_us = 2.0 * B * B * (double)K / (tflops * 1e6 / grid);   // one workgroup's speed = total / grid
+    const double tflops = (BN * BM >= 256 * 256) ? 1050.0 : 900.0;
+    double tile_us = 2.0 * BN * BM * (double)K / (tflops * 1e6 / grid);   // one workgroup's speed = total / grid
+    if (tiles_m == 1) {
+        const double stream_us = (double)BN * K * 2.0 / (6.0e6 / grid);
+        tile_us = tile_us > stream_us ? tile_us : stream_us;
+    }
     const int rem = tiles % grid;
     const double whole = (double)((tiles + grid - 1) / grid) * tile_us;
     if (rem == 0) return Schedule{0, whole};
-    const double fixup_us = 5.0 + (double)(grid + rem) * ((double)B * B * 4.0) * 2.0 / 4.0e6;
-    // short shares suit the 128-tile kernel badly (measured ~1.6x the model): price that in
-    const double shared = (((double)(tiles / grid) + (double)rem / grid) * tile_us + fixup_us) * (B == 256 ? 1.0 : 1.6);
+    const double fixup_us = 5.0 + (double)(grid + rem) * ((double)BN * BM * 4.0) * 2.0 / 4.0e6;
+    // short shares suit the 128x128 kernel badly (measured ~1.6x the model): price that in
+    const double shared = (((double)(tiles / grid) + (double)rem / grid) * tile_us + fixup_us) * (BN == 128 && BM == 128 ? 1.6 : 1.0);
     return shared < whole ? Schedule{rem, shared} : Schedule{0, whole};
 }
 
@@ -533,7 +578,7 @@ hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream
     const long U = (long)a.tiles * ktiles;
     long grid = grid_cap;
     if (grid > U) grid = U;
-    const int sk_tiles = plan_schedule(a.tiles, (int)grid, BN, a.K).sk_tiles;
+    const int sk_tiles = plan_schedule(a.tiles, tiles_m, (int)grid, BN, BM, a.K).sk_tiles;
     const size_t lds = (size_t)NS * (BN + BM) * (GK / 8) * sizeof(uintx4);
     dim3 g((unsigned)grid), b(64 * WN * WM);
 #define THI_LAUNCH_K(E, KT)                                                                                  \
@@ -547,7 +592,7 @@ hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream
         }                                                                                                    \
         hipLaunchKernelGGL(kern, g, b, lds, stream, a, tiles_m, ktiles, sk_tiles);                           \
         if (sk_tiles > 0)                                                                                    \
-            hipLaunchKernelGGL((gemm_fixup<BN, BM, WN, WM, E>), dim3(sk_tiles * (BN / WN / 32) * (BM / WM / 32)), \
+            hipLaunchKernelGGL((gemm_fixup<BN, BM, WN, WM, E>), dim3(2 * sk_tiles * (BN / WN / 32) * (BM / WM / 32)), \
                                b, 0, stream, a, tiles_m, ktiles, sk_tiles, (int)grid);                       \
     } while (0)
 #define THI_LAUNCH(E)                                                                                        \
@@ -576,13 +621,14 @@ hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream
     return hipGetLastError();
 }
 
-double config_cost(const GemmArgs& a, int epilogue, int B, int grid)
+double config_cost(const GemmArgs& a, int epilogue, int BN, int BM, int grid)
 {
-    const int per_tile = is_swiglu(epilogue) ? B / 2 : B;
-    const long tiles = (long)((a.N + per_tile - 1) / per_tile) * ((a.M + B - 1) / B);
+    const int per_tile = is_swiglu(epilogue) ? BN / 2 : BN;
+    const int tiles_m = (a.M + BM - 1) / BM;
+    const long tiles = (long)((a.N + per_tile - 1) / per_tile) * tiles_m;
     const long units = tiles * ((a.K + 63) / 64);
     const int g = (int)(units < grid ? units : grid);
-    return plan_schedule((int)tiles, g, B, a.K).us;
+    return plan_schedule((int)tiles, tiles_m, g, BN, BM, a.K).us;
 }
 
 }  // namespace
@@ -633,10 +679,16 @@ hipError_t launch_gemm(const GemmArgs& a, int epilogue, int num_cus, hipStream_t
     int g_big = num_cus, g_small = 2 * num_cus;        // workgroups that fit: one resp. two per CU
     if (g_big * 4 > GEMM_MAX_GRID) g_big = GEMM_MAX_GRID / 4;
     if (g_small > GEMM_MAX_GRID) g_small = GEMM_MAX_GRID;
-    bool big = !is_rms(epilogue) && !has_rope(epilogue) && (a.K % 64 == 0);
-    if (big) {
-        big = config_cost(a, epilogue, 256, g_big) <= config_cost(a, epilogue, 128, g_small);
+    // the direct-to-LDS configurations: plain / SwiGLU epilogues, K a multiple of the staged k-tile
+    const bool direct = !is_rms(epilogue) && !has_rope(epilogue) && (a.K % 64 == 0);
+    if (direct && a.M <= 128) {
+        // Few tokens: one token tile, the weights are read once and the kernel is bound by how many
+        // bytes a CU keeps in flight.  256 weight rows against 64 or 128 tokens, three stages deep.
+        if (a.M <= 64) return launch_cfg<128, 64, 4, 1, 128, 3, false>(a, epilogue, g_big, stream);
+        return launch_cfg<256, 128, 4, 1, 64, 3, false>(a, epilogue, g_big, stream);
     }
+    bool big = direct;
+    if (big) big = config_cost(a, epilogue, 256, 256, g_big) <= config_cost(a, epilogue, 128, 128, g_small);
     if (big) return launch_cfg<256, 256, 4, 2, 64, 2, false>(a, epilogue, g_big, stream);
     return launch_cfg<128, 128, 2, 2, 64, 2, true>(a, epilogue, g_small, stream);
 }

@@ -1,0 +1,382 @@
+// Row-block decode kernel (M <= 32 tokens per launch) on gfx950: the row-slab kernel's decomposition
+// with several slabs in flight per workgroup.
+//
+// The paper's small-M rule (Sec. III-B.2: broadcast X, split the work along N): the output features
+// are dealt to the workgroups in equal contiguous blocks (one workgroup per compute unit, so every
+// compute unit streams the same number of weight bytes whatever N is), each block over the whole
+// reduction dimension: nothing is handed from workgroup to workgroup.  A block is T tiles of 16 weight rows
+// (rows past the block's end are masked).  Inside the workgroup the k range is cut into eight
+// contiguous pieces, one per wave; per unit of 256 k a wave loads its slice of the activations ONCE, in
+// MFMA operand layout, and uses it for all T tiles, so the activation traffic through the vector
+// cache per weight byte is 1/T of the one-slab kernel's (what limits that kernel from M = 16 up).
+// Weights stream as in the row-slab kernel: coalesced 16-byte loads one tile-step ahead of the
+// arithmetic, a wave-private LDS buffer to reach operand layout.  The eight partial tiles meet in
+// LDS, are added in wave order (reproducible) and finished by the fused epilogue (Sec. III-C.1:
+// RMSNorm scale, rotary embedding, SwiGLU, residual).  Blocks of more than T tiles take several passes
+// over K.
+#include "thi_internal.h"
+
+#include <type_traits>
+
+namespace thi {
+
+namespace {
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+template <int T, int MT, int EPI>
+__global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(SkinnyArgs a, int per_wg)
+{
+    static_assert(T == 2 || T == 4 || T == 6, "tile-steps alternate between two register buffers");
+    constexpr int RT = T / 2;                           // tiles per reduction round (bounds the LDS it takes)
+    constexpr int OUT_PER_TILE = is_swiglu(EPI) ? 8 : 16;
+    __shared__ uintx4 wt[SK_WAVES][WT_UNITS];          // wave-private transposition buffers
+    __shared__ float s_part[SK_WAVES][RT][MT * 4 * 64]; // the waves' partial tiles
+    __shared__ float s_sum[RT][32][17];                // finished sums [tile][token][row]
+    __shared__ float s_red[SK_WAVES][32];
+    __shared__ float s_ssq[32];
+    extern __shared__ uintx4 s_gamma[];                // RMSNorm: each wave's slice of gamma
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int K = a.K;
+
+    // this workgroup's block of outputs (rows of W; gate/up row pairs for SwiGLU)
+    const int r0 = (int)blockIdx.x * per_wg;
+    if (r0 >= a.N) return;
+    const int r1 = r0 + per_wg < a.N ? r0 + per_wg : a.N;
+    const int nT = (r1 - r0 + OUT_PER_TILE - 1) / OUT_PER_TILE;
+    const int P = (nT + T - 1) / T;                    // passes over K
+
+    // this wave's k range: whole groups of 128 k, so that every range starts on a 256-byte boundary of
+    // its rows (K >= 1024: every wave has at least one group)
+    const int S4 = (K + 127) >> 7;
+    const int k_begin = ((wv * S4) >> 3) * 128;
+    const int k_stop = (((wv + 1) * S4) >> 3) * 128;
+    const int k_end = k_stop < K ? k_stop : K;
+    const int nU = (k_end - k_begin + SK_KC - 1) / SK_KC;            // units of 256 k per pass
+    const int total = P * nU * T;                                    // tile-steps of this wave
+
+    const int g_pieces = (((S4 >> 3) + 1) * 128) >> 3;               // 16-byte pieces reserved per wave
+    if (is_rms(EPI)) {
+        for (int p = lane; p * 8 < k_end - k_begin; p += 64)
+            s_gamma[wv * g_pieces + p] = ld_cached(a.gamma + k_begin + p * 8);
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    // weight-load role: load jj of a phase covers MFMA rows 4*jj + lane/16, piece lane%16
+    const int ld_i = lane >> 4, ld_p = lane & 15;
+    // operand role: token column c, k group kg
+    const int c = lane & 15, kg = lane >> 4;
+    const uintx4 zero4 = {0u, 0u, 0u, 0u};
+
+    // Every load is unconditional.  A row past the block's end is read from the block's last row (the
+    // same lines a neighbouring lane asks for); a piece past the wave's k range from the first piece of
+    // the unit; a whole tile past the block (or past the wave's last tile-step: valid = false) from the
+    // first piece of its rows.  What such loads return is zeroed or never stored.
+    auto issue_w = [&](int tile, int uu, bool valid, uintx4 (&w)[8]) {
+        const int k0 = k_begin + uu * SK_KC;
+        const int k_lim = (valid && tile < nT) ? k_end : 0;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int v = 4 * jj + ld_i;                   // virtual row within the tile
+            const uint16_t* base;
+            if (is_swiglu(EPI)) {
+                int j = r0 + tile * 8 + (v & 7);
+                j = j < r1 ? j : r1 - 1;
+                base = ((v >> 3) ? a.w1 : a.w0) + (size_t)j * K;
+            } else {
+                int n = r0 + tile * 16 + v;
+                n = n < r1 ? n : r1 - 1;
+                base = a.w0 + (size_t)n * K;
+            }
+#pragma unroll
+            for (int ph = 0; ph < 2; ++ph) {
+                const int k = k0 + ph * 128 + ld_p * 8;
+                w[ph * 4 + jj] = ld_stream(base + (k < k_lim ? k : k0));
+            }
+        }
+    };
+
+    floatx4 acc[T][MT];
+    floatx4 ssq[MT];                         // RMSNorm: x x^T of this wave's k range, one 16x16 tile per token tile
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[t][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) ssq[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    int pass = 0, uu = 0;                    // the unit being consumed
+    int p_pass = 0, p_uu = 0;                // the unit of the tile-step last requested
+    int requested = 1;
+    uintx4 wb0[8], wb1[8];
+    issue_w(0, 0, true, wb0);
+
+    uintx4 xr[8][MT];                        // the unit's activations, operand layout (x * gamma for RMSNorm)
+
+    // One tile-step = request the next tile-step's weights (the next tile of this unit, or tile 0 of the
+    // next unit), then multiply tile TI of the current pass by the unit's activations.
+    auto request_next = [&](auto ti, uintx4 (&pre)[8]) {
+        constexpr int TI = decltype(ti)::value;
+        if constexpr (TI + 1 == T) {
+            if (++p_uu == nU) { p_uu = 0; ++p_pass; }
+            issue_w(p_pass * T, p_uu, requested < total, pre);
+        } else {
+            issue_w(p_pass * T + TI + 1, p_uu, requested < total, pre);
+        }
+        ++requested;
+    };
+    auto multiply = [&](auto ti, uintx4 (&cur)[8]) {
+        constexpr int TI = decltype(ti)::value;
+        const int k0 = k_begin + uu * SK_KC;
+        // zero what came from a redirected address
+        if (k0 + SK_KC > k_end) {
+#pragma unroll
+            for (int ph = 0; ph < 2; ++ph)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj)
+                    if (k0 + ph * 128 + ld_p * 8 >= k_end) cur[ph * 4 + jj] = zero4;
+        }
+#pragma unroll
+        for (int ph = 0; ph < 2; ++ph) {
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) wt[wv][(4 * jj + ld_i) * WT_STRIDE + ld_p] = cur[ph * 4 + jj];
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) {
+                const int s = ph * 4 + s4;
+                const half8 wa = __builtin_bit_cast(half8, wt[wv][c * WT_STRIDE + 4 * s4 + kg]);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    if constexpr (TI == 0) {
+                        // first use of the unit's activations: mask them, and for RMSNorm multiply by gamma
+                        // (the sum of squares of the first pass is the one used: every pass sees the same x);
+                        // the later tiles of the unit reuse the result
+                        const bool kok = k0 + s * 32 + kg * 8 < k_end;
+                        uintx4 xv = (kok && mt * 16 + c < a.M) ? xr[s][mt] : zero4;
+                        if (is_rms(EPI)) {
+                            const half8 xh = __builtin_bit_cast(half8, xv);
+                            const half8 gh = __builtin_bit_cast(half8, s_gamma[wv * g_pieces + (((kok ? k0 + s * 32 : k_begin) - k_begin) >> 3) + (kok ? kg : 0)]);
+                            // sum of squares on the matrix pipe: x as both operands, the diagonal of x x^T
+                            // (accumulated in every pass, branch-free; only the first pass's sum is used)
+                            ssq[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xh, xh, ssq[mt], 0, 0, 0);
+                            const half8 p = xh * gh;       // one rounding: the fp16 product of two fp16 values
+                            xv = kok ? __builtin_bit_cast(uintx4, p) : zero4;
+                        }
+                        xr[s][mt] = xv;
+                    }
+                    acc[TI][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wa, __builtin_bit_cast(half8, xr[s][mt]),
+                                                                         acc[TI][mt], 0, 0, 0);
+                }
+            }
+        }
+    };
+    auto tile_step = [&](auto ti, uintx4 (&cur)[8], uintx4 (&pre)[8]) {
+        request_next(ti, pre);
+        multiply(ti, cur);
+    };
+
+    // Epilogue of one finished tile: thread -> (token m, row r)
+    auto finish_tile = [&](int tile, int tt) {
+        const float (&sum)[32][17] = s_sum[tt];
+        const int r = tid & 15, m = tid >> 4;
+        if (m >= a.M) return;
+        float scale = 1.0f;
+        if (is_rms(EPI)) scale = 1.0f / __builtin_sqrtf(s_ssq[m] / (float)K + a.eps);
+        if (is_swiglu(EPI)) {
+            const int j = r0 + tile * 8 + r;
+            if (r < 8 && j < r1)
+                a.out[(size_t)m * a.ldo + j] = to_half_bits(silu_mul(sum[m][r] * scale, sum[m][r + 8] * scale));
+        } else {
+            const int n = r0 + tile * 16 + r;
+            if (EPI == EPI_RMSNORM_ROPE) {
+                if ((r & 1) == 0) {       // this thread finishes the pair (n, n + 1); blocks start on even rows
+                    float v0 = sum[m][r] * scale, v1 = sum[m][r + 1] * scale;
+                    rope_pair(a.rope, a.rope.pos[m], n, v0, v1);
+                    if (n < r1) {
+                        if (a.residual) v0 += half_bits_to_float(a.residual[(size_t)m * a.ldo + n]);
+                        a.out[(size_t)m * a.ldo + n] = to_half_bits(v0);
+                    }
+                    if (n + 1 < r1) {
+                        if (a.residual) v1 += half_bits_to_float(a.residual[(size_t)m * a.ldo + n + 1]);
+                        a.out[(size_t)m * a.ldo + n + 1] = to_half_bits(v1);
+                    }
+                }
+            } else if (n < r1) {
+                float v = sum[m][r] * scale;
+                if (a.residual) v += half_bits_to_float(a.residual[(size_t)m * a.ldo + n]);
+                a.out[(size_t)m * a.ldo + n] = to_half_bits(v);
+            }
+        }
+    };
+
+    const int units = P * nU;
+    for (int it = 0; it < units; ++it) {
+        const int k0 = k_begin + uu * SK_KC;
+        const bool first_pass = (pass == 0);
+
+        // Activations of this unit, then the next tile-step's weights: waiting for the activations leaves
+        // those weights in flight.  They are loaded the way the weights are -- 16 lanes cover 256
+        // contiguous bytes of a token row -- and reach operand layout through the wave's LDS buffer:
+        // loading them in operand layout (every lane its own 16 bytes of a different row) costs the
+        // vector cache several times the cycles per byte.
+        uintx4 xl[MT][8];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const int m = mt * 16 + 4 * jj + ld_i;
+                const uint16_t* row = a.x + (size_t)(m < a.M ? m : a.M - 1) * K;
+#pragma unroll
+                for (int ph = 0; ph < 2; ++ph) {
+                    const int k = k0 + ph * 128 + ld_p * 8;
+                    xl[mt][ph * 4 + jj] = ld_cached(row + (k < k_end ? k : k0));
+                }
+            }
+        request_next(std::integral_constant<int, 0>{}, wb1);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int ph = 0; ph < 2; ++ph) {
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) wt[wv][(4 * jj + ld_i) * WT_STRIDE + ld_p] = xl[mt][ph * 4 + jj];
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int s4 = 0; s4 < 4; ++s4) xr[ph * 4 + s4][mt] = wt[wv][c * WT_STRIDE + 4 * s4 + kg];
+            }
+        multiply(std::integral_constant<int, 0>{}, wb0);
+        tile_step(std::integral_constant<int, 1>{}, wb1, wb0);
+        if constexpr (T > 2) {
+            tile_step(std::integral_constant<int, 2>{}, wb0, wb1);
+            tile_step(std::integral_constant<int, 3>{}, wb1, wb0);
+        }
+        if constexpr (T > 4) {
+            tile_step(std::integral_constant<int, 4>{}, wb0, wb1);
+            tile_step(std::integral_constant<int, 5>{}, wb1, wb0);
+        }
+
+        const bool pass_ends = (uu + 1 == nU);
+        const int this_pass = pass;
+        if (++uu == nU) { uu = 0; ++pass; }
+        if (!pass_ends) continue;
+
+        // ---- the eight partial tiles of each of the pass's tiles meet in LDS, RT tiles per round -------
+#pragma unroll
+        for (int rr = 0; rr < T / RT; ++rr) {
+#pragma unroll
+            for (int tt = 0; tt < RT; ++tt)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) s_part[wv][tt][(mt * 4 + i) * 64 + lane] = acc[rr * RT + tt][mt][i];
+                    acc[rr * RT + tt][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+                }
+            if (is_rms(EPI) && first_pass && rr == 0) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    // token c's sum of squares is element (c, c): row c = 4 * (lane / 16) + register index
+                    const int i = c & 3;
+                    const float v = i == 0 ? ssq[mt][0] : i == 1 ? ssq[mt][1] : i == 2 ? ssq[mt][2] : ssq[mt][3];
+                    if (kg == (c >> 2)) s_red[wv][mt * 16 + c] = v;
+                }
+                if (MT == 1 && kg == 0) s_red[wv][16 + c] = 0.f;
+            }
+            __syncthreads();
+            for (int e = tid; e < RT * MT * 256; e += SK_THREADS) {
+                const int tt = e / (MT * 256), q = e % (MT * 256);
+                float v = 0.f;       // fixed order: waves 0..7
+#pragma unroll
+                for (int w = 0; w < SK_WAVES; ++w) v += s_part[w][tt][q];
+                const int l = q & 63, i = (q >> 6) & 3, mt = q >> 8;
+                s_sum[tt][mt * 16 + (l & 15)][4 * (l >> 4) + i] = v;
+            }
+            if (is_rms(EPI) && first_pass && rr == 0 && tid < 32) {      // kept in s_ssq for the later passes
+                float v = 0.f;
+#pragma unroll
+                for (int w = 0; w < SK_WAVES; ++w) v += s_red[w][tid];
+                s_ssq[tid] = v;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int tt = 0; tt < RT; ++tt) {
+                const int tile = this_pass * T + rr * RT + tt;
+                if (tile < nT) finish_tile(tile, tt);
+            }
+            // s_part is rewritten only after every thread has passed the second barrier above, s_sum only
+            // after the next round's first barrier, which every thread reaches after these epilogues
+        }
+    }
+}
+
+// 16-byte pieces of LDS per wave for its slice of gamma (same arithmetic as in the kernel)
+int gamma_pieces(int K) { return ((((K + 127) >> 7) >> 3) + 1) * 128 >> 3; }
+
+template <int T, int MT>
+hipError_t launch_t_mt(const SkinnyArgs& a, int epilogue, int per_wg, int grid, hipStream_t stream)
+{
+    dim3 g(grid), b(SK_THREADS);
+    const size_t gamma_lds = (size_t)SK_WAVES * gamma_pieces(a.K) * sizeof(uintx4);
+    static bool attr_set = false;       // static (+ dynamic) LDS passes 64 KiB: every variant needs the opt-in
+    if (!attr_set) {
+        // largest static part: T = 6, two token tiles (~90 KiB); with this it stays inside the 160 KiB of a CU
+        const int most = (int)((size_t)SK_WAVES * gamma_pieces(ROWSLAB_MAX_K) * sizeof(uintx4));
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_PLAIN>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, most);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_SWIGLU>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, most);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_RMSNORM>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, most);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_RMSNORM_ROPE>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, most);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_RMSNORM_SWIGLU>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, most);
+        attr_set = true;
+    }
+    switch (epilogue) {
+    case EPI_PLAIN: hipLaunchKernelGGL((skinny_rowblock<T, MT, EPI_PLAIN>), g, b, 0, stream, a, per_wg); break;
+    case EPI_RMSNORM: hipLaunchKernelGGL((skinny_rowblock<T, MT, EPI_RMSNORM>), g, b, gamma_lds, stream, a, per_wg); break;
+    case EPI_RMSNORM_ROPE: hipLaunchKernelGGL((skinny_rowblock<T, MT, EPI_RMSNORM_ROPE>), g, b, gamma_lds, stream, a, per_wg); break;
+    case EPI_RMSNORM_SWIGLU: hipLaunchKernelGGL((skinny_rowblock<T, MT, EPI_RMSNORM_SWIGLU>), g, b, gamma_lds, stream, a, per_wg); break;
+    default: hipLaunchKernelGGL((skinny_rowblock<T, MT, EPI_SWIGLU>), g, b, 0, stream, a, per_wg); break;
+    }
+    return hipGetLastError();
+}
+
+template <int T>
+hipError_t launch_t(const SkinnyArgs& a, int epilogue, int per_wg, int grid, hipStream_t stream)
+{
+    if (a.M <= 16) return launch_t_mt<T, 1>(a, epilogue, per_wg, grid, stream);
+    return launch_t_mt<T, 2>(a, epilogue, per_wg, grid, stream);
+}
+
+}  // namespace
+
+RowBlockPlan plan_rowblock(int N, int epilogue, int num_cus)
+{
+    RowBlockPlan p;
+    const int out_per_tile = is_swiglu(epilogue) ? 8 : 16;
+    int per_wg = (N + num_cus - 1) / num_cus;
+    if (!is_swiglu(epilogue)) per_wg = (per_wg + 1) & ~1;      // rotary pairs (n, n + 1) stay in one block
+    p.per_wg = per_wg;
+    p.grid = (N + per_wg - 1) / per_wg;
+    p.tiles = (per_wg + out_per_tile - 1) / out_per_tile;
+    p.passes = (p.tiles + 5) / 6;
+    const int per_pass = (p.tiles + p.passes - 1) / p.passes;
+    p.T = per_pass <= 2 ? 2 : per_pass <= 4 ? 4 : 6;
+    return p;
+}
+
+hipError_t launch_rowblock(const SkinnyArgs& a, int epilogue, int num_cus, hipStream_t stream)
+{
+    if (a.K < 1024 || a.K > ROWSLAB_MAX_K || a.N < 1) return hipErrorInvalidValue;
+    const RowBlockPlan p = plan_rowblock(a.N, epilogue, num_cus);
+    if (p.T == 2) return launch_t<2>(a, epilogue, p.per_wg, p.grid, stream);
+    if (p.T == 4) return launch_t<4>(a, epilogue, p.per_wg, p.grid, stream);
+    return launch_t<6>(a, epilogue, p.per_wg, p.grid, stream);
+}
+
+}  // namespace thi

@@ -23,7 +23,12 @@ namespace {
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
-template <int MT, int EPI>
+// XT: the activations are loaded the way the weights are (16 lanes cover 256 contiguous bytes of a token
+// row) and reach operand layout through the wave's LDS buffer.  From a handful of tokens up this is the
+// cheaper way: loaded in operand layout, every lane asks for its own 16 bytes of a different row, which
+// costs the vector cache several times the cycles per byte.  With very few tokens most lanes of an
+// operand-layout load share an address and the direct load wins.
+template <int MT, int EPI, bool XT>
 __global__ __launch_bounds__(SK_THREADS) void skinny_rowslab(SkinnyArgs a)
 {
     __shared__ uintx4 wt[SK_WAVES][WT_UNITS];          // wave-private transposition buffers
@@ -119,19 +124,48 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowslab(SkinnyArgs a)
         // activations (and gamma) of this unit, in operand layout; issued before the prefetch so that
         // waiting for them leaves the prefetched weights in flight
         uintx4 xr[8][MT];
+        uintx4 xl[XT ? MT : 1][8];
+        if constexpr (XT) {
 #pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            const int kx = k0 + s * 32 + kg * 8;
-            const int kxc = kx < k_end ? kx : k0;
+            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const int m = mt * 16 + c;
-                xr[s][mt] = ld_cached(a.x + (size_t)(m < a.M ? m : a.M - 1) * K + kxc);
+                for (int jj = 0; jj < 4; ++jj) {
+                    const int m = mt * 16 + 4 * jj + ld_i;
+                    const uint16_t* row = a.x + (size_t)(m < a.M ? m : a.M - 1) * K;
+#pragma unroll
+                    for (int ph = 0; ph < 2; ++ph) {
+                        const int k = k0 + ph * 128 + ld_p * 8;
+                        xl[mt][ph * 4 + jj] = ld_cached(row + (k < k_end ? k : k0));
+                    }
+                }
+        } else {
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                const int kx = k0 + s * 32 + kg * 8;
+                const int kxc = kx < k_end ? kx : k0;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const int m = mt * 16 + c;
+                    xr[s][mt] = ld_cached(a.x + (size_t)(m < a.M ? m : a.M - 1) * K + kxc);
+                }
             }
         }
         if (++p_uu == nU) { p_uu = 0; p_slab += G; }
         issue_w(p_slab, p_uu, requested < total, pre);
         ++requested;
+        if constexpr (XT) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int ph = 0; ph < 2; ++ph) {
+                    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) wt[wv][(4 * jj + ld_i) * WT_STRIDE + ld_p] = xl[mt][ph * 4 + jj];
+                    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                    for (int s4 = 0; s4 < 4; ++s4) xr[ph * 4 + s4][mt] = wt[wv][c * WT_STRIDE + 4 * s4 + kg];
+                }
+        }
 
         // zero what came from a redirected address
         if (k0 + SK_KC > k_end) {
@@ -267,7 +301,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowslab(SkinnyArgs a)
 // 16-byte pieces of LDS per wave for its slice of gamma (same arithmetic as in the kernel)
 int rowslab_gamma_pieces(int K) { return ((((K + 127) >> 7) >> 3) + 1) * 128 >> 3; }
 
-template <int MT>
+template <int MT, bool XT>
 hipError_t launch_mt(const SkinnyArgs& a, int epilogue, int grid, hipStream_t stream)
 {
     dim3 g(grid), b(SK_THREADS);
@@ -275,20 +309,20 @@ hipError_t launch_mt(const SkinnyArgs& a, int epilogue, int grid, hipStream_t st
     static bool attr_set = false;       // static + dynamic LDS can pass 64 KiB for large K
     if (!attr_set) {
         const int most = (int)((size_t)SK_WAVES * rowslab_gamma_pieces(ROWSLAB_MAX_K) * sizeof(uintx4));
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowslab<MT, EPI_RMSNORM>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowslab<MT, EPI_RMSNORM, XT>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, most);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowslab<MT, EPI_RMSNORM_ROPE>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowslab<MT, EPI_RMSNORM_ROPE, XT>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, most);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowslab<MT, EPI_RMSNORM_SWIGLU>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowslab<MT, EPI_RMSNORM_SWIGLU, XT>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, most);
         attr_set = true;
     }
     switch (epilogue) {
-    case EPI_PLAIN: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_PLAIN>), g, b, 0, stream, a); break;
-    case EPI_RMSNORM: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_RMSNORM>), g, b, gamma_lds, stream, a); break;
-    case EPI_RMSNORM_ROPE: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_RMSNORM_ROPE>), g, b, gamma_lds, stream, a); break;
-    case EPI_RMSNORM_SWIGLU: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_RMSNORM_SWIGLU>), g, b, gamma_lds, stream, a); break;
-    default: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_SWIGLU>), g, b, 0, stream, a); break;
+    case EPI_PLAIN: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_PLAIN, XT>), g, b, 0, stream, a); break;
+    case EPI_RMSNORM: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_RMSNORM, XT>), g, b, gamma_lds, stream, a); break;
+    case EPI_RMSNORM_ROPE: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_RMSNORM_ROPE, XT>), g, b, gamma_lds, stream, a); break;
+    case EPI_RMSNORM_SWIGLU: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_RMSNORM_SWIGLU, XT>), g, b, gamma_lds, stream, a); break;
+    default: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_SWIGLU, XT>), g, b, 0, stream, a); break;
     }
     return hipGetLastError();
 }
@@ -299,8 +333,9 @@ hipError_t launch_rowslab(const SkinnyArgs& a, int epilogue, int num_cus, hipStr
 {
     if (a.K < 1024 || a.K > ROWSLAB_MAX_K || a.tiles < 1) return hipErrorInvalidValue;
     int grid = num_cus < a.tiles ? num_cus : a.tiles;
-    if (a.M <= 16) return launch_mt<1>(a, epilogue, grid, stream);
-    return launch_mt<2>(a, epilogue, grid, stream);
+    if (a.M <= 4) return launch_mt<1, false>(a, epilogue, grid, stream);
+    if (a.M <= 16) return launch_mt<1, true>(a, epilogue, grid, stream);
+    return launch_mt<2, true>(a, epilogue, grid, stream);
 }
 
 }  // namespace thi

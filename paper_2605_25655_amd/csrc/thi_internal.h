@@ -74,6 +74,17 @@ hipError_t launch_skinny(const SkinnyArgs& a, int epilogue, int num_cus, hipStre
 // wave's slice of gamma must fit its share of LDS); uses no workspace.
 constexpr int ROWSLAB_MAX_K = 32768;
 hipError_t launch_rowslab(const SkinnyArgs& a, int epilogue, int num_cus, hipStream_t stream);
+// Row-block decode kernel: the outputs dealt to the workgroups in equal contiguous blocks, T slabs of a
+// block in flight at a time (same limits on K; a.tiles is not used; uses no workspace).
+struct RowBlockPlan {
+    int per_wg;      // outputs (rows of W, gate/up pairs for SwiGLU) per workgroup
+    int grid;        // workgroups
+    int tiles;       // 16-row tiles per block
+    int passes;      // passes over K
+    int T;           // tiles in flight per pass (2, 4 or 6)
+};
+RowBlockPlan plan_rowblock(int N, int epilogue, int num_cus);
+hipError_t launch_rowblock(const SkinnyArgs& a, int epilogue, int num_cus, hipStream_t stream);
 
 // ---- GEMM (prefill) kernel ---------------------------------------------------
 struct GemmArgs {

@@ -111,7 +111,7 @@ def test_swiglu_odd_shapes(thi, oracle_mod, M, H, I):
     check(got, y, s, f"swiglu {M}x{H}x{I}", argmax=False)
 
 
-@pytest.mark.parametrize("family", [1, 2, 3])
+@pytest.mark.parametrize("family", [1, 2, 3, 4])
 @pytest.mark.parametrize("M", [1, 20, 48, 160])
 def test_both_kernel_families_cover_every_m(thi, oracle_mod, family, M):
     say(f"[case] family={family} M={M}")
@@ -211,6 +211,53 @@ def test_prefill_swiglu_schedules(thi, oracle_mod, M, H, I):
     assert np.isfinite(c1.astype(np.float32)).all()
 
 
+# ------------------------------------------- between decode and prefill (33..128 tokens)
+# One token tile of 64 or 128 against 256 weight rows, three stages deep; every tile is shared among
+# workgroups (far fewer tiles than compute units) and finished by the second pass.
+FEW_TOKENS = [
+    (33, 1000, 1024), (48, 4096 + 200, 2048), (64, 256, 4096), (65, 3000, 1024), (100, 12288, 4096),
+    (128, 520, 11008 + 56),
+]
+
+
+@pytest.mark.parametrize("M,N,K", FEW_TOKENS)
+def test_few_token_gemm(thi, oracle_mod, M, N, K):
+    say(f"[case] few-token gemm M={M} N={N} K={K}")
+    x, w, g = synth.random_problem(9900 + M + N + K, M, N, K)
+    rows = synth.sample_rows(99, M, 12)
+    r = Runner(M, K, K, N)
+    xd, wd, gd = to_dev(x), to_dev(w), to_dev(g)
+    res = to_dev(f16(np.random.default_rng(M).standard_normal((M, N))))
+    a1 = to_host(r.linear(xd, wd))
+    a2 = to_host(r.linear(xd, wd))
+    assert np.array_equal(a1.view(np.uint16), a2.view(np.uint16)), "linear is not reproducible"
+    y, s = oracle_mod.linear(x[rows], w)
+    check(a1[rows], y, s, f"linear {M}x{N}x{K}")
+    b = to_host(r.rmsnorm_qkv(xd, gd, 1e-6, wd))
+    y, s = oracle_mod.rmsnorm_qkv(x[rows], g, 1e-6, w)
+    check(b[rows], y, s, f"rmsnorm_qkv {M}x{N}x{K}")
+    c = to_host(r.linear_residual(xd, wd, res))
+    y, s = oracle_mod.linear_residual(x[rows], w, to_host(res)[rows])
+    check(c[rows], y, s, f"linear_residual {M}x{N}x{K}")
+
+
+@pytest.mark.parametrize("M,H,I", [(40, 1024, 2816), (96, 512, 1376), (128, 2048, 1000)])
+def test_few_token_swiglu(thi, oracle_mod, M, H, I):
+    say(f"[case] few-token swiglu M={M} H={H} I={I}")
+    rng = np.random.Generator(np.random.Philox(key=7100 + M + H + I))
+    x = f16(rng.standard_normal((M, H)))
+    wg, wu = f16(rng.standard_normal((I, H)) * 0.03), f16(rng.standard_normal((I, H)) * 0.03)
+    wd = f16(rng.standard_normal((H, I)) * 0.03)
+    rows = synth.sample_rows(78, M, 12)
+    r = Runner(M, H, I, H)
+    args = (to_dev(x), to_dev(wg), to_dev(wu), to_dev(wd))
+    c1 = to_host(r.swiglu_mlp(*args))
+    c2 = to_host(r.swiglu_mlp(*args))
+    assert np.array_equal(c1.view(np.uint16), c2.view(np.uint16))
+    y, s = oracle_mod.swiglu_mlp(x[rows], wg, wu, wd)
+    check(c1[rows], y, s, f"swiglu {M}x{H}x{I}")
+
+
 # ----------------------------------------------- rotary embedding epilogue
 def _theta(head_dim, base=10000.0):
     i = np.arange(head_dim // 2, dtype=np.float64)
@@ -258,6 +305,68 @@ def test_rowslab_kernel_all_epilogues(thi, oracle_mod, M, N, K):
     # are rounded once to fp16
     _, _, hh = oracle_mod.swiglu_mlp(x, w[:I], wu, np.zeros((K, I), np.float16), return_h=True)
     err = np.abs(h.astype(np.float64) - hh)
+    bound = 2e-3 * np.abs(hh) + 2e-3 * np.sqrt((hh ** 2).mean())
+    assert (err <= bound).all(), f"gate/up worst excess {(err - bound).max()}"
+
+
+# the row-block decode kernel: each workgroup owns N / #CUs outputs = several 16-row tiles (the last one
+# partly masked), 2, 4 or 6 of them in flight; more than six take several passes over K
+ROWBLOCK = [
+    # M, N, K, I (gate/up rows)
+    (1, 4608, 1024, 2304),        # 18 rows per workgroup: two tiles, the second nearly empty
+    (5, 8200, 1160, 4104),        # ragged everything
+    (16, 12288, 1024, 11008),     # 48 rows = 3 whole tiles (4 in flight, one masked); 43 gate/up pairs = 6 tiles
+    (32, 12288, 2056, 11008),
+    (31, 16000, 1032, 5000),      # 63 -> 64 rows = 4 tiles
+    (32, 28000, 1024, 14336),     # 110 rows = 7 tiles: two passes of 4; 56 pairs = 7 tiles
+    (20, 40000, 1096, 28672),     # 157 -> 158 rows = 10 tiles: two passes of 6 (the second with 4); 112 pairs = 14 tiles: 3 passes
+]
+
+
+@pytest.mark.parametrize("M,N,K,I", ROWBLOCK)
+def test_rowblock_kernel_all_epilogues(thi, oracle_mod, M, N, K, I):
+    say(f"[case] row blocks M={M} N={N} K={K} I={I}")
+    x, w, g = synth.random_problem(4700 + M * 5 + N + K, M, N, K)
+    rng = np.random.Generator(np.random.Philox(key=4800 + M + N + K))
+    wu = f16(rng.standard_normal((I, K)) * 0.05)
+    wg = f16(rng.standard_normal((I, K)) * 0.05)
+    res = f16(rng.standard_normal((M, N)))
+    hd = 8
+    n_rot = (N // 2) // hd * hd
+    pos = rng.integers(0, 4096, size=M).astype(np.int32)
+    th = _theta(hd)
+    cols = np.unique(np.concatenate([synth.sample_rows(5, N, 700), np.arange(N - 40, N), np.arange(0, 40)]))
+    cols = np.unique(np.concatenate([cols, cols ^ 1]))          # rotary pairs stay complete
+    cols = cols[cols < N]
+    jc = np.unique(np.concatenate([synth.sample_rows(6, I, 500), np.arange(I - 20, I), np.arange(0, 20)]))
+    r = Runner(M, K, max(I, K), N)
+    xd, wd, gd = to_dev(x), to_dev(w), to_dev(g)
+    prev = thi.thi_set_kernel_family(4)
+    try:
+        a = to_host(r.linear(xd, wd))
+        a2 = to_host(r.linear(xd, wd))
+        ar = to_host(r.linear_residual(xd, wd, to_dev(res)))
+        b = to_host(r.rmsnorm_qkv(xd, gd, 1e-6, wd))
+        c = to_host(r.rmsnorm_qkv_rope(xd, gd, 1e-6, wd, _dev_i32(pos), _dev_f32(th), n_rot, hd))
+        h = to_host(r.swiglu_gate_up(xd, to_dev(wg), to_dev(wu)))
+    finally:
+        thi.thi_set_kernel_family(prev)
+    assert np.array_equal(a.view(np.uint16), a2.view(np.uint16))
+    assert np.isfinite(a.astype(np.float32)).all() and np.isfinite(h.astype(np.float32)).all()
+    ws = np.ascontiguousarray(w[cols])
+    y, s = oracle_mod.linear(x, ws)
+    check(a[:, cols], y, s, "linear", argmax=False)
+    y, s = oracle_mod.linear_residual(x, ws, np.ascontiguousarray(res[:, cols]))
+    check(ar[:, cols], y, s, "linear_residual", argmax=False)
+    y, s = oracle_mod.rmsnorm_qkv(x, g, 1e-6, ws)
+    check(b[:, cols], y, s, "rmsnorm_qkv", argmax=False)
+    # rotary: the oracle on the sampled rows needs their column numbers; pairs are complete in `cols`
+    yf, sf = oracle_mod.rmsnorm_qkv_rope(x, g, 1e-6, w, pos, th, n_rot, hd) if N * K * M <= 2.5e9 else (None, None)
+    if yf is not None:
+        check(c, yf, sf, "rmsnorm_qkv_rope", argmax=False)
+    _, _, hh = oracle_mod.swiglu_mlp(x, np.ascontiguousarray(wg[jc]), np.ascontiguousarray(wu[jc]),
+                                     np.zeros((K, len(jc)), np.float16), return_h=True)
+    err = np.abs(h[:, jc].astype(np.float64) - hh)
     bound = 2e-3 * np.abs(hh) + 2e-3 * np.sqrt((hh ** 2).mean())
     assert (err <= bound).all(), f"gate/up worst excess {(err - bound).max()}"
 
@@ -338,7 +447,7 @@ def test_rope_on_layer_configs(thi, oracle_mod, cfg_id, ms):
 # ------------------------------------- residual epilogues, RMSNorm in front of the MLP
 LAYER_CLOSING = [
     (1, 272, 1376, 328, 0), (5, 136, 264, 200, 0), (16, 4096, 4096, 1376, 0), (32, 640, 2056, 1032, 1),
-    (8, 4096, 1024, 2048, 3), (17, 100, 1160, 512, 3), (40, 272, 520, 328, 0), (160, 272, 520, 328, 0),
+    (8, 4096, 1024, 2048, 3), (17, 100, 1160, 512, 3), (32, 8192, 1024, 6000, 4), (9, 5000, 1096, 11008, 4), (40, 272, 520, 328, 0), (160, 272, 520, 328, 0),
     (300, 520, 328, 264, 2), (256, 256, 256, 512, 2),
 ]
 
