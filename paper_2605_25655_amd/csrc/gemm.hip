@@ -683,8 +683,9 @@ hipError_t launch_gemm(const GemmArgs& a, int epilogue, int num_cus, hipStream_t
     const bool direct = !is_rms(epilogue) && !has_rope(epilogue) && (a.K % 64 == 0);
     if (direct && a.M <= 128) {
         // Few tokens: one token tile, the weights are read once and the kernel is bound by how many
-        // bytes a CU keeps in flight.  256 weight rows against 64 or 128 tokens, three stages deep.
-        if (a.M <= 64) return launch_cfg<128, 64, 4, 1, 128, 3, false>(a, epilogue, g_big, stream);
+        // bytes a CU keeps in flight: three stages of 128 rows x 128 k against 64 tokens (K a multiple of
+        // 128), else of 256 rows x 64 k against 128 tokens.
+        if (a.M <= 64 && a.K % 128 == 0) return launch_cfg<128, 64, 4, 1, 128, 3, false>(a, epilogue, g_big, stream);
         return launch_cfg<256, 128, 4, 1, 64, 3, false>(a, epilogue, g_big, stream);
     }
     bool big = direct;

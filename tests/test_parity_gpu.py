@@ -216,6 +216,7 @@ def test_prefill_swiglu_schedules(thi, oracle_mod, M, H, I):
 # workgroups (far fewer tiles than compute units) and finished by the second pass.
 FEW_TOKENS = [
     (33, 1000, 1024), (48, 4096 + 200, 2048), (64, 256, 4096), (65, 3000, 1024), (100, 12288, 4096),
+    (40, 1000, 4096 + 64),      # K a multiple of 64 but not of 128
     (128, 520, 11008 + 56),
 ]
 
