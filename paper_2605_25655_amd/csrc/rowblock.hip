@@ -59,12 +59,6 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(SkinnyArgs a, int 
     const int total = P * nU * T;                                    // tile-steps of this wave
 
     const int g_pieces = (((S4 >> 3) + 1) * 128) >> 3;               // 16-byte pieces reserved per wave
-    if (is_rms(EPI)) {
-        for (int p = lane; p * 8 < k_end - k_begin; p += 64)
-            s_gamma[wv * g_pieces + p] = ld_cached(a.gamma + k_begin + p * 8);
-        __builtin_amdgcn_wave_barrier();
-    }
-
     // weight-load role: load jj of a phase covers MFMA rows 4*jj + lane/16, piece lane%16
     const int ld_i = lane >> 4, ld_p = lane & 15;
     // operand role: token column c, k group kg
@@ -112,7 +106,18 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(SkinnyArgs a, int 
     int p_pass = 0, p_uu = 0;                // the unit of the tile-step last requested
     int requested = 1;
     uintx4 wb0[8], wb1[8];
+    // RMSNorm: this wave's slice of gamma goes to LDS once (wave-private: no workgroup barrier).  Its first
+    // 64 pieces are requested before the first weights and stored behind them, so that the weights are in
+    // flight while gamma arrives (all of gamma for K <= 4096).
+    uintx4 g_first = zero4;
+    if (is_rms(EPI)) g_first = ld_cached(a.gamma + k_begin + (lane * 8 < k_end - k_begin ? lane * 8 : 0));
     issue_w(0, 0, true, wb0);
+    if (is_rms(EPI)) {
+        if (lane * 8 < k_end - k_begin) s_gamma[wv * g_pieces + lane] = g_first;
+        for (int p = lane + 64; p * 8 < k_end - k_begin; p += 64)
+            s_gamma[wv * g_pieces + p] = ld_cached(a.gamma + k_begin + p * 8);
+        __builtin_amdgcn_wave_barrier();
+    }
 
     uintx4 xr[8][MT];                        // the unit's activations, operand layout (x * gamma for RMSNorm)
 
