@@ -372,6 +372,28 @@ def test_rowblock_kernel_all_epilogues(thi, oracle_mod, M, N, K, I):
     assert (err <= bound).all(), f"gate/up worst excess {(err - bound).max()}"
 
 
+def test_rowblock_largest_lds_footprint(thi, oracle_mod):
+    """K = 32768 with RMSNorm (a wave's slice of gamma: 8 KiB of LDS), six tiles in flight and two token
+    tiles: the largest LDS footprint of the row-block kernel (static + dynamic just under a CU's 160 KiB)."""
+    M, N, K = 17, 20800, 32768
+    say(f"[case] row blocks, largest LDS footprint M={M} N={N} K={K}")
+    rng = np.random.Generator(np.random.Philox(key=31337))
+    base = (rng.standard_normal((2600, K), dtype=np.float32) * 0.02).astype(np.float16)
+    w = np.tile(base, (8, 1))                       # rows repeat with period 2600: cheap to draw
+    x = rng.standard_normal((M, K), dtype=np.float32).astype(np.float16)
+    g = (1.0 + 0.1 * rng.standard_normal(K, dtype=np.float32)).astype(np.float16)
+    cols = np.unique(np.concatenate([synth.sample_rows(8, N, 200), np.arange(N - 20, N), np.arange(0, 20)]))
+    r = Runner(M, K, K, N)
+    prev = thi.thi_set_kernel_family(4)
+    try:
+        b = to_host(r.rmsnorm_qkv(to_dev(x), to_dev(g), 1e-6, to_dev(w)))
+    finally:
+        thi.thi_set_kernel_family(prev)
+    y, s = oracle_mod.rmsnorm_qkv(x, g, 1e-6, np.ascontiguousarray(w[cols]))
+    check(b[:, cols], y, s, "rmsnorm_qkv", argmax=False)
+    assert np.isfinite(b.astype(np.float32)).all()
+
+
 def _dev_i32(a):
     import torch
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
