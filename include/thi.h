@@ -85,7 +85,9 @@ int thi_rmsnorm_qkv(const void* x, const void* gamma, float eps, const void* w_q
  *
  * with y the thi_rmsnorm_qkv result in fp32.  positions [M] int32 and theta [head_dim/2] fp32 are
  * device memory (4-byte aligned); n_rot must be a multiple of head_dim (even) and <= N; columns
- * >= n_rot (V) are not rotated.  Everything else as thi_rmsnorm_qkv.
+ * >= n_rot (V) are not rotated.  Everything else as thi_rmsnorm_qkv.  Above 32 tokens the cosines and
+ * sines come from a table in the workspace that the call fills first, which holds head_dim <= 256
+ * (THI_ERR_SHAPE beyond); the decode kernels take any head_dim.
  */
 int thi_rmsnorm_qkv_rope(const void* x, const void* gamma, float eps, const void* w_qkv,
                          const int* positions, const float* theta, int n_rot, int head_dim,

@@ -40,6 +40,7 @@ struct Workspace {
     float* partials;
     uint16_t* h;     // MLP: silu(gate)*up [M,I]
     uint16_t* xn;    // prefill: normalised activations [M,K] of the RMSNorm-fronted operators
+    float* rope_cs;  // prefill, QKV with the rotary epilogue: (cos, sin) table [M][head_dim/2][2], behind xn
 };
 
 // Both kernel families keep their own regions (either may be forced for any M).
@@ -49,7 +50,8 @@ size_t fixed_bytes() { return WS_COUNTER_BYTES + WS_SSQ_BYTES + round_up(skinny_
 size_t h_bytes(int op, int M, int b) { return op == THI_OP_SWIGLU_MLP ? round_up((size_t)M * (size_t)b * 2, 256) : 0; }
 size_t xn_bytes(int op, int M, int a, int b)
 {
-    if (op == THI_OP_RMSNORM_QKV) return round_up((size_t)M * (size_t)b * 2, 256);     // [M,K]
+    if (op == THI_OP_RMSNORM_QKV)      // [M,K], then the rotary table [M][<= 128][2] fp32
+        return round_up((size_t)M * (size_t)b * 2, 256) + (size_t)M * (ROPE_TABLE_MAX_HEAD_DIM / 2) * 8;
     if (op == THI_OP_SWIGLU_MLP) return round_up((size_t)M * (size_t)a * 2, 256);      // [M,H]
     return 0;
 }
@@ -59,7 +61,7 @@ size_t workspace_need(int op, int M, int a, int b)
     return fixed_bytes() + gemm_partial_bytes() + h_bytes(op, M, b) + xn_bytes(op, M, a, b);
 }
 
-Workspace carve(void* base, size_t h_size = 0)
+Workspace carve(void* base, size_t h_size = 0, size_t xn_size = 0)
 {
     char* p = static_cast<char*>(base);
     Workspace w;
@@ -69,6 +71,7 @@ Workspace carve(void* base, size_t h_size = 0)
     w.partials = reinterpret_cast<float*>(p + fixed_bytes());
     w.h = reinterpret_cast<uint16_t*>(p + fixed_bytes() + gemm_partial_bytes());
     w.xn = reinterpret_cast<uint16_t*>(p + fixed_bytes() + gemm_partial_bytes() + h_size);
+    w.rope_cs = reinterpret_cast<float*>(p + fixed_bytes() + gemm_partial_bytes() + h_size + xn_size);
     return w;
 }
 
@@ -182,7 +185,12 @@ int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const ui
     // take both operands straight from memory into LDS in its fastest configuration; the decode kernels
     // keep it fused, where a second pass over x would cost a launch.
     if (is_rms(epilogue)) {
-        if (launch_rmsnorm_rows(x, gamma, eps, ws.xn, M, K, stream) != hipSuccess) return THI_ERR_HIP;
+        RopeArgs table = rope;
+        if (has_rope(epilogue)) {
+            if (rope.head_dim > ROPE_TABLE_MAX_HEAD_DIM) return THI_ERR_SHAPE;
+            table.cs = rope.cs = ws.rope_cs;
+        }
+        if (launch_rmsnorm_rows(x, gamma, eps, ws.xn, M, K, table, stream) != hipSuccess) return THI_ERR_HIP;
         x = ws.xn;
         gamma = nullptr;
         epilogue = epilogue == EPI_RMSNORM ? EPI_PLAIN : epilogue == EPI_RMSNORM_ROPE ? EPI_ROPE : EPI_SWIGLU;
@@ -243,7 +251,7 @@ int thi_rmsnorm_qkv_rope(const void* x, const void* gamma, float eps, const void
     if (misaligned(x, 16) || misaligned(gamma, 16) || misaligned(w_qkv, 16) || misaligned(out, 16) ||
         misaligned(positions, 4) || misaligned(theta, 4))
         return THI_ERR_ALIGN;
-    Workspace ws = carve(workspace);
+    Workspace ws = carve(workspace, 0, round_up((size_t)M * (size_t)K * 2, 256));
     return run_projection((const uint16_t*)x, (const uint16_t*)gamma, eps, (const uint16_t*)w_qkv, nullptr,
                           (uint16_t*)out, M, N, K, N, EPI_RMSNORM_ROPE, ws, (hipStream_t)hip_stream,
                           RopeArgs{positions, theta, n_rot, head_dim});

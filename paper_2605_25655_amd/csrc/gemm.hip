@@ -127,9 +127,14 @@ __device__ __forceinline__ void store_fragment(const GemmArgs& a, int tile_n, in
 #pragma unroll
             for (int c = 0; c < 4; ++c) v[c] = f[4 * aa + c] * scale;
             if (has_rope(EPI)) {                         // the quad holds two complete pairs of one token
-                const int mp = a.rope.pos[m];
-                rope_pair(a.rope, mp, n, v[0], v[1]);
-                rope_pair(a.rope, mp, n + 2, v[2], v[3]);
+                if (EPI == EPI_ROPE) {                   // cos / sin from the table the RMSNorm pass left
+                    rope_pair_table(a.rope, m, n, v[0], v[1]);
+                    rope_pair_table(a.rope, m, n + 2, v[2], v[3]);
+                } else {
+                    const int mp = a.rope.pos[m];
+                    rope_pair(a.rope, mp, n, v[0], v[1]);
+                    rope_pair(a.rope, mp, n + 2, v[2], v[3]);
+                }
             }
             if (n + 3 < a.N && (a.ldo & 3) == 0) {
                 half4 hv;
@@ -606,10 +611,7 @@ hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream
     } while (0)
     switch (epilogue) {
     case EPI_PLAIN: THI_LAUNCH(EPI_PLAIN); break;
-    case EPI_ROPE:               // 128x128 configuration only: in the 256x256 one the rotary epilogue spills registers
-        if constexpr (ALL) THI_LAUNCH(EPI_ROPE);
-        else return hipErrorInvalidValue;
-        break;
+    case EPI_ROPE: THI_LAUNCH(EPI_ROPE); break;
     case EPI_RMSNORM:            // RMSNorm runs as a pass of its own in front of the GEMM (see the dispatcher);
     case EPI_RMSNORM_ROPE:       // the fused variants of this kernel are kept in the source but not built
     case EPI_RMSNORM_SWIGLU:
@@ -637,8 +639,18 @@ namespace {
 
 // One workgroup per token row: sum of squares in fp32, then the normalised row in fp16 (one rounding of
 // x * r * gamma).  A memory-bound pass over M*K elements, a few percent of the GEMM it feeds.
-__global__ __launch_bounds__(256) void rmsnorm_rows(const uint16_t* x, const uint16_t* gamma, float eps, uint16_t* xn, int K)
+__global__ __launch_bounds__(256) void rmsnorm_rows(const uint16_t* x, const uint16_t* gamma, float eps, uint16_t* xn, int K,
+                                                    RopeArgs rope)
 {
+    // the rotary epilogue's table for this token: fp32 angle, full-range sincosf (positions reach
+    // thousands of radians); done here so that the GEMM's epilogue needs neither
+    if (rope.cs && (int)threadIdx.x < (rope.head_dim >> 1)) {
+        float sn, cs;
+        sincosf((float)rope.pos[blockIdx.x] * rope.theta[threadIdx.x], &sn, &cs);
+        float* e = const_cast<float*>(rope.cs) + ((size_t)blockIdx.x * (rope.head_dim >> 1) + threadIdx.x) * 2;
+        e[0] = cs;
+        e[1] = sn;
+    }
     __shared__ float s_part[4];
     const uint16_t* row = x + (size_t)blockIdx.x * K;
     uint16_t* dst = xn + (size_t)blockIdx.x * K;
@@ -666,9 +678,10 @@ __global__ __launch_bounds__(256) void rmsnorm_rows(const uint16_t* x, const uin
 }  // namespace
 
 hipError_t launch_rmsnorm_rows(const uint16_t* x, const uint16_t* gamma, float eps, uint16_t* xn, int M, int K,
-                               hipStream_t stream)
+                               const RopeArgs& rope, hipStream_t stream)
 {
-    hipLaunchKernelGGL(rmsnorm_rows, dim3((unsigned)M), dim3(256), 0, stream, x, gamma, eps, xn, K);
+    if (rope.cs && rope.head_dim > 2 * 256) return hipErrorInvalidValue;     // one thread per pair of the head
+    hipLaunchKernelGGL(rmsnorm_rows, dim3((unsigned)M), dim3(256), 0, stream, x, gamma, eps, xn, K, rope);
     return hipGetLastError();
 }
 
@@ -680,7 +693,7 @@ hipError_t launch_gemm(const GemmArgs& a, int epilogue, int num_cus, hipStream_t
     if (g_big * 4 > GEMM_MAX_GRID) g_big = GEMM_MAX_GRID / 4;
     if (g_small > GEMM_MAX_GRID) g_small = GEMM_MAX_GRID;
     // the direct-to-LDS configurations: plain / SwiGLU epilogues, K a multiple of the staged k-tile
-    const bool direct = !is_rms(epilogue) && !has_rope(epilogue) && (a.K % 64 == 0);
+    const bool direct = !is_rms(epilogue) && (a.K % 64 == 0);
     if (direct && a.M <= 128) {
         // Few tokens: one token tile, the weights are read once and the kernel is bound by how many
         // bytes a CU keeps in flight: three stages of 128 rows x 128 k against 64 tokens (K a multiple of

@@ -28,7 +28,10 @@ struct RopeArgs {
     const int* pos;          // [M] token positions
     const float* theta;      // [head_dim / 2]
     int n_rot, head_dim;
+    const float* cs;         // GEMM path: [M][head_dim / 2][2] = (cos, sin) of pos[m] * theta[i], made by the
+                             // RMSNorm pass in front of the GEMM; nullptr in the decode kernels
 };
+constexpr int ROPE_TABLE_MAX_HEAD_DIM = 256;     // what the workspace reserves per token for that table
 
 // ---- workspace layout (bytes from the workspace base) ----------------------
 // [0, 64 KiB)             : status words (uint32), zero between calls: the decode kernels' hand-over
@@ -106,8 +109,9 @@ constexpr int GEMM_MAX_GRID = 2048;   // in units of 128x128 partial tiles (a 25
 size_t gemm_partial_bytes();
 hipError_t launch_gemm(const GemmArgs& a, int epilogue, int num_cus, hipStream_t stream);
 // xn[m,k] = fp16(x[m,k] * gamma[k] / sqrt(mean_k x[m,:]^2 + eps)): the prefill path's RMSNorm pass
+// With rope.cs set it also fills that table: cs[m][i] = (cos, sin)(pos[m] * theta[i]), fp32, full-range.
 hipError_t launch_rmsnorm_rows(const uint16_t* x, const uint16_t* gamma, float eps, uint16_t* xn, int M, int K,
-                               hipStream_t stream);
+                               const RopeArgs& rope, hipStream_t stream);
 
 // ---- decode attention ---------------------------------------------------------
 struct AttnArgs {
@@ -135,6 +139,17 @@ __device__ __forceinline__ void rope_pair(const RopeArgs& r, int m_pos, int c, f
     const float ang = (float)m_pos * r.theta[(c % r.head_dim) >> 1];
     float sn, cs;
     sincosf(ang, &sn, &cs);
+    const float na = a * cs - b * sn, nb = b * cs + a * sn;
+    a = na;
+    b = nb;
+}
+
+// The same rotation with cos and sin taken from the table in r.cs (token row m of this launch).
+__device__ __forceinline__ void rope_pair_table(const RopeArgs& r, int m, int c, float& a, float& b)
+{
+    if (c >= r.n_rot) return;
+    const float* e = r.cs + ((size_t)m * (r.head_dim >> 1) + ((c % r.head_dim) >> 1)) * 2;
+    const float cs = e[0], sn = e[1];
     const float na = a * cs - b * sn, nb = b * cs + a * sn;
     a = na;
     b = nb;

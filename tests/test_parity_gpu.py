@@ -405,7 +405,8 @@ def _dev_f32(a):
 
 
 @pytest.mark.parametrize("M,N,K,n_rot,hd", [(1, 96, 64, 64, 32), (7, 200, 136, 128, 64), (32, 384, 520, 256, 128),
-                                            (40, 192, 256, 192, 64), (300, 520, 328, 512, 128), (600, 256, 512, 128, 8)])
+                                            (40, 192, 256, 192, 64), (300, 520, 328, 512, 128), (600, 256, 512, 128, 8),
+                                            (70, 1024, 512, 768, 256), (2100, 1280, 1024, 1024, 128)])
 def test_rope_epilogue_shapes(thi, oracle_mod, M, N, K, n_rot, hd):
     say(f"[case] rope M={M} N={N} K={K} n_rot={n_rot} head_dim={hd}")
     x, w, g = synth.random_problem(3100 + M + N + K, M, N, K)
@@ -444,6 +445,15 @@ def test_rope_argument_errors(thi):
     assert thi.thi_rmsnorm_qkv_rope(x, g, 1e-6, w, pos, th, 128, 16, out, r.ws, check=False) == 2  # n_rot > N
     assert thi.thi_rmsnorm_qkv_rope(x, g, 1e-6, w, pos, th, 32, 15, out, r.ws, check=False) == 2   # odd head_dim
     assert thi.thi_rmsnorm_qkv_rope(x, g, 1e-6, w, None, th, 32, 16, out, r.ws, check=False) == 1
+    # above 32 tokens the cos/sin table in the workspace holds head_dim <= 256
+    M2, N2 = 40, 1024
+    r2 = Runner(M2, K, K, N2)
+    x2 = torch.zeros((M2, K), dtype=torch.float16, device="cuda")
+    w2 = torch.zeros((N2, K), dtype=torch.float16, device="cuda")
+    out2 = torch.zeros((M2, N2), dtype=torch.float16, device="cuda")
+    pos2, th2 = _dev_i32(np.zeros(M2)), _dev_f32(np.ones(256))
+    assert thi.thi_rmsnorm_qkv_rope(x2, g, 1e-6, w2, pos2, th2, 512, 512, out2, r2.ws, check=False) == 2
+    assert thi.thi_rmsnorm_qkv_rope(x2, g, 1e-6, w2, pos2, th2, 512, 256, out2, r2.ws, check=False) == 0
 
 
 @pytest.mark.parametrize("cfg_id,ms", [(1, (1,)), (2, (1, 8, 32)), (5, (32,)), (3, (512,))])
