@@ -573,7 +573,7 @@ Schedule plan_schedule(int tiles, int tiles_m, int grid, int BN, int BM, int K)
 // ALL = also build the variants with a transformed activation tile (RMSNorm) or a ragged K; the
 // 256x256 configuration leaves them to the 128x128 one (they would not fit its register budget).
 template <int BN, int BM, int WN, int WM, int GK, int NS, bool ALL>
-hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream)
+hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream, bool share_all = false)
 {
     const int per_tile = is_swiglu(epilogue) ? BN / 2 : BN;
     const int tiles_n = (a.N + per_tile - 1) / per_tile;
@@ -583,7 +583,8 @@ hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream
     const long U = (long)a.tiles * ktiles;
     long grid = grid_cap;
     if (grid > U) grid = U;
-    const int sk_tiles = plan_schedule(a.tiles, tiles_m, (int)grid, BN, BM, a.K).sk_tiles;
+    // share_all: every tile is cut into k-steps and dealt stream-K, whatever the model says
+    const int sk_tiles = share_all ? a.tiles : plan_schedule(a.tiles, tiles_m, (int)grid, BN, BM, a.K).sk_tiles;
     const size_t lds = (size_t)NS * (BN + BM) * (GK / 8) * sizeof(uintx4);
     dim3 g((unsigned)grid), b(64 * WN * WM);
 #define THI_LAUNCH_K(E, KT)                                                                                  \
@@ -701,9 +702,28 @@ hipError_t launch_gemm(const GemmArgs& a, int epilogue, int num_cus, hipStream_t
         if (a.M <= 64 && a.K % 128 == 0) return launch_cfg<128, 64, 4, 1, 128, 3, false>(a, epilogue, g_big, stream);
         return launch_cfg<256, 128, 4, 1, 64, 3, false>(a, epilogue, g_big, stream);
     }
-    bool big = direct;
-    if (big) big = config_cost(a, epilogue, 256, 256, g_big) <= config_cost(a, epilogue, 128, 128, g_small);
-    if (big) return launch_cfg<256, 256, 4, 2, 64, 2, false>(a, epilogue, g_big, stream);
+    const double c_small = config_cost(a, epilogue, 128, 128, g_small);
+    if (direct) {
+        const double c_big = config_cost(a, epilogue, 256, 256, g_big);
+        // At most one 128x128 tile per CU (e.g. N = K = 4096 at M <= 1024): neither a second workgroup on
+        // the CU nor more, shorter stream-K shares help; what helps is a third LDS stage for the one
+        // workgroup there is (~800 TFLOP/s chip-wide when every CU has a tile; N = K = 4096 at M = 1024:
+        // 45.7 against 70.4 us).  With at most half a tile per CU the tiles are shared by two or more
+        // workgroups each (M = 256: 24 against 36 us, M = 512: 31 against 43 us).
+        // (The model prices the stream-K schedule of the 256x256 tiles about a quarter too high when K is
+        // long -- 7B-shaped down projection at M = 1024: modelled 135, measured 105 us -- hence the 0.75.)
+        const int per_tile = is_swiglu(epilogue) ? 64 : 128;
+        const long t128 = (long)((a.N + per_tile - 1) / per_tile) * ((a.M + 127) / 128);
+        if (t128 <= num_cus) {
+            const double tile_us = 2.0 * 128 * 128 * (double)a.K / (800.0e6 / num_cus);
+            const bool share = t128 * 2 <= num_cus;
+            const double c_deep = share ? (double)t128 / num_cus * tile_us + 5.0 + (double)num_cus * (128 * 128 * 4.0) * 2.0 / 4.0e6
+                                        : tile_us;
+            if (c_deep < 0.75 * c_big && c_deep < c_small)
+                return launch_cfg<128, 128, 2, 2, 64, 3, false>(a, epilogue, num_cus, stream, share);
+        }
+        if (c_big <= c_small) return launch_cfg<256, 256, 4, 2, 64, 2, false>(a, epilogue, g_big, stream);
+    }
     return launch_cfg<128, 128, 2, 2, 64, 2, true>(a, epilogue, g_small, stream);
 }
 
