@@ -24,7 +24,7 @@ if ROOT not in sys.path:
 
 # per-launch HBM KiB (fetch, write) of the gate/up kernel, scaled, from the rocprofv3 --pmc runs in profiles/
 MEASURED_TRAFFIC_KIB = {
-    (2, 32): ((178860.0, 928.0), "profiles/skinny_rowblock_llama7b_decode_m32.txt"),
+    (2, 32): ((178856.0, 928.0), "profiles/skinny_rowblock_llama7b_decode_m32.txt"),
     (5, 2048): ((2766284.0, 115011.0), "profiles/gemm_streamk_llama70b_prefill_m2048.txt"),
 }
 
@@ -99,6 +99,14 @@ class LayerBench:
         need = max(thi.thi_workspace_bytes(0, M, cfg.n_qkv, H), thi.thi_workspace_bytes(1, M, H, H),
                    thi.thi_workspace_bytes(2, M, H, cfg.inter))
         self.ws = thi.Workspace(need)
+        # The O projection alone is small (33.5 MB for the 7B shape): the rotated copies of w_o would fit the
+        # 256 MB last-level cache together.  Its per-operator timing therefore also cycles through the
+        # H-row blocks of the QKV matrices (same shape and layout as w_o, different values).
+        self.o_mats = []
+        for w in self.w:
+            self.o_mats.append(w["w_o"])
+            for b in range(cfg.n_qkv // H):
+                self.o_mats.append(w["w_qkv"][b * H:(b + 1) * H])
 
     def step(self, i):
         w = self.w[i % self.copies]
@@ -116,7 +124,7 @@ class LayerBench:
             t.thi_rmsnorm_qkv_rope(self.x_qkv, self.gamma, 1e-6, w["w_qkv"], self.pos, self.theta, self.n_rot,
                                    self.head_dim, self.qkv, self.ws)
         elif name == "o_proj":
-            t.thi_linear(self.a_o, w["w_o"], self.o, self.ws)
+            t.thi_linear(self.a_o, self.o_mats[i % len(self.o_mats)], self.o, self.ws)
         elif name == "gate_up":
             t.thi_swiglu_gate_up(self.x_mlp, w["w_gate"], w["w_up"], self.h, self.ws)
         elif name == "down":
@@ -124,7 +132,7 @@ class LayerBench:
         elif name == "swiglu_mlp":
             t.thi_swiglu_mlp(self.x_mlp, w["w_gate"], w["w_up"], w["w_down"], self.y, self.ws)
         elif name == "o_proj_residual":
-            t.thi_linear_residual(self.a_o, w["w_o"], self.x_mlp, self.o, self.ws)
+            t.thi_linear_residual(self.a_o, self.o_mats[i % len(self.o_mats)], self.x_mlp, self.o, self.ws)
         elif name == "rmsnorm_swiglu_mlp_residual":
             t.thi_rmsnorm_swiglu_mlp(self.x_mlp, self.gamma, 1e-6, w["w_gate"], w["w_up"], w["w_down"], self.a_o,
                                      self.y, self.ws)
