@@ -139,7 +139,7 @@ int pick_decode_kernel(int M, int N, int K, int epilogue, int cus)
 // One fused projection: out[M, ldo] = epilogue( prologue(x)[M,K] * w^T ), any M.
 int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const uint16_t* w0, const uint16_t* w1,
                    uint16_t* out, int M, int N, int K, int ldo, int epilogue, const Workspace& ws,
-                   hipStream_t stream, RopeArgs rope = RopeArgs{nullptr, nullptr, 0, 2},
+                   hipStream_t stream, RopeArgs rope = RopeArgs{nullptr, nullptr, 0, 2, nullptr},
                    const uint16_t* residual = nullptr)
 {
     const int cus = device_cu_count();
@@ -254,7 +254,7 @@ int thi_rmsnorm_qkv_rope(const void* x, const void* gamma, float eps, const void
     Workspace ws = carve(workspace, 0, round_up((size_t)M * (size_t)K * 2, 256));
     return run_projection((const uint16_t*)x, (const uint16_t*)gamma, eps, (const uint16_t*)w_qkv, nullptr,
                           (uint16_t*)out, M, N, K, N, EPI_RMSNORM_ROPE, ws, (hipStream_t)hip_stream,
-                          RopeArgs{positions, theta, n_rot, head_dim});
+                          RopeArgs{positions, theta, n_rot, head_dim, nullptr});
 }
 
 int thi_linear(const void* x, const void* w, void* out, int M, int N, int K,
@@ -310,7 +310,7 @@ int thi_linear_residual(const void* x, const void* w, const void* residual, void
     if (misaligned(x, 16) || misaligned(w, 16) || misaligned(residual, 16) || misaligned(out, 16)) return THI_ERR_ALIGN;
     Workspace ws = carve(workspace);
     return run_projection((const uint16_t*)x, nullptr, 0.f, (const uint16_t*)w, nullptr, (uint16_t*)out,
-                          M, N, K, N, EPI_PLAIN, ws, (hipStream_t)hip_stream, RopeArgs{nullptr, nullptr, 0, 2},
+                          M, N, K, N, EPI_PLAIN, ws, (hipStream_t)hip_stream, RopeArgs{nullptr, nullptr, 0, 2, nullptr},
                           (const uint16_t*)residual);
 }
 
@@ -331,7 +331,7 @@ int thi_rmsnorm_swiglu_mlp(const void* x, const void* gamma, float eps, const vo
                         (const uint16_t*)w_up, ws.h, M, I, H, I, EPI_RMSNORM_SWIGLU, ws, stream);
     if (rc != THI_OK) return rc;
     return run_projection(ws.h, nullptr, 0.f, (const uint16_t*)w_down, nullptr, (uint16_t*)out, M, H, I, H,
-                          EPI_PLAIN, ws, stream, RopeArgs{nullptr, nullptr, 0, 2}, (const uint16_t*)residual);
+                          EPI_PLAIN, ws, stream, RopeArgs{nullptr, nullptr, 0, 2, nullptr}, (const uint16_t*)residual);
 }
 
 size_t thi_attention_workspace_bytes(int B, int Hq, int Hkv, int D, int S_max)
