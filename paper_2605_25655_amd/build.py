@@ -20,6 +20,9 @@ FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
+    # leading scalar kernel arguments arrive preloaded in registers (the decode kernels pass the operands
+    # of their first loads that way)
+    "-mllvm", "-amdgpu-kernarg-preload-count=12",
 ]
 
 

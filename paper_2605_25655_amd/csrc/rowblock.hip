@@ -25,8 +25,13 @@ namespace {
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
 template <int T, int MT, int EPI>
-__global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(SkinnyArgs a, int per_wg)
+__global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_, const uint16_t* w0_, const uint16_t* w1_,
+                                                              const uint16_t* gamma_, int M_, int N_, int K_, int per_wg,
+                                                              SkinnyArgs a)
 {
+    // The operands the first loads need come as leading scalar arguments: the hardware preloads those
+    // into registers at wave launch, so the first weight request does not wait for an argument fetch.
+    a.x = x_; a.w0 = w0_; a.w1 = w1_; a.gamma = gamma_; a.M = M_; a.N = N_; a.K = K_;
     static_assert(T == 2 || T == 4 || T == 6, "tile-steps alternate between two register buffers");
     constexpr int RT = T / 2;                           // tiles per reduction round (bounds the LDS it takes)
     constexpr int OUT_PER_TILE = is_swiglu(EPI) ? 8 : 16;
@@ -342,11 +347,11 @@ hipError_t launch_t_mt(const SkinnyArgs& a, int epilogue, int per_wg, int grid, 
         attr_set = true;
     }
     switch (epilogue) {
-    case EPI_PLAIN: hipLaunchKernelGGL((skinny_rowblock<T, MT, EPI_PLAIN>), g, b, 0, stream, a, per_wg); break;
-    case EPI_RMSNORM: hipLaunchKernelGGL((skinny_rowblock<T, MT, EPI_RMSNORM>), g, b, gamma_lds, stream, a, per_wg); break;
-    case EPI_RMSNORM_ROPE: hipLaunchKernelGGL((skinny_rowblock<T, MT, EPI_RMSNORM_ROPE>), g, b, gamma_lds, stream, a, per_wg); break;
-    case EPI_RMSNORM_SWIGLU: hipLaunchKernelGGL((skinny_rowblock<T, MT, EPI_RMSNORM_SWIGLU>), g, b, gamma_lds, stream, a, per_wg); break;
-    default: hipLaunchKernelGGL((skinny_rowblock<T, MT, EPI_SWIGLU>), g, b, 0, stream, a, per_wg); break;
+    case EPI_PLAIN: hipLaunchKernelGGL((skinny_rowblock<T, MT, EPI_PLAIN>), g, b, 0, stream, a.x, a.w0, a.w1, a.gamma, a.M, a.N, a.K, per_wg, a); break;
+    case EPI_RMSNORM: hipLaunchKernelGGL((skinny_rowblock<T, MT, EPI_RMSNORM>), g, b, gamma_lds, stream, a.x, a.w0, a.w1, a.gamma, a.M, a.N, a.K, per_wg, a); break;
+    case EPI_RMSNORM_ROPE: hipLaunchKernelGGL((skinny_rowblock<T, MT, EPI_RMSNORM_ROPE>), g, b, gamma_lds, stream, a.x, a.w0, a.w1, a.gamma, a.M, a.N, a.K, per_wg, a); break;
+    case EPI_RMSNORM_SWIGLU: hipLaunchKernelGGL((skinny_rowblock<T, MT, EPI_RMSNORM_SWIGLU>), g, b, gamma_lds, stream, a.x, a.w0, a.w1, a.gamma, a.M, a.N, a.K, per_wg, a); break;
+    default: hipLaunchKernelGGL((skinny_rowblock<T, MT, EPI_SWIGLU>), g, b, 0, stream, a.x, a.w0, a.w1, a.gamma, a.M, a.N, a.K, per_wg, a); break;
     }
     return hipGetLastError();
 }

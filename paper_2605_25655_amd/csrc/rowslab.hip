@@ -29,8 +29,13 @@ typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 // costs the vector cache several times the cycles per byte.  With very few tokens most lanes of an
 // operand-layout load share an address and the direct load wins.
 template <int MT, int EPI, bool XT>
-__global__ __launch_bounds__(SK_THREADS) void skinny_rowslab(SkinnyArgs a)
+__global__ __launch_bounds__(SK_THREADS) void skinny_rowslab(const uint16_t* x_, const uint16_t* w0_, const uint16_t* w1_,
+                                                             const uint16_t* gamma_, int M_, int N_, int K_, int tiles_,
+                                                             SkinnyArgs a)
 {
+    // The operands the first loads need come as leading scalar arguments: the hardware preloads those
+    // into registers at wave launch, so the first weight request does not wait for an argument fetch.
+    a.x = x_; a.w0 = w0_; a.w1 = w1_; a.gamma = gamma_; a.M = M_; a.N = N_; a.K = K_; a.tiles = tiles_;
     __shared__ uintx4 wt[SK_WAVES][WT_UNITS];          // wave-private transposition buffers
     __shared__ float s_part[SK_WAVES][MT * 4 * 64];    // the waves' partial tiles
     __shared__ float s_sum[32][17];                    // finished sums [token][row]
@@ -322,11 +327,11 @@ hipError_t launch_mt(const SkinnyArgs& a, int epilogue, int grid, hipStream_t st
         attr_set = true;
     }
     switch (epilogue) {
-    case EPI_PLAIN: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_PLAIN, XT>), g, b, 0, stream, a); break;
-    case EPI_RMSNORM: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_RMSNORM, XT>), g, b, gamma_lds, stream, a); break;
-    case EPI_RMSNORM_ROPE: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_RMSNORM_ROPE, XT>), g, b, gamma_lds, stream, a); break;
-    case EPI_RMSNORM_SWIGLU: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_RMSNORM_SWIGLU, XT>), g, b, gamma_lds, stream, a); break;
-    default: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_SWIGLU, XT>), g, b, 0, stream, a); break;
+    case EPI_PLAIN: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_PLAIN, XT>), g, b, 0, stream, a.x, a.w0, a.w1, a.gamma, a.M, a.N, a.K, a.tiles, a); break;
+    case EPI_RMSNORM: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_RMSNORM, XT>), g, b, gamma_lds, stream, a.x, a.w0, a.w1, a.gamma, a.M, a.N, a.K, a.tiles, a); break;
+    case EPI_RMSNORM_ROPE: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_RMSNORM_ROPE, XT>), g, b, gamma_lds, stream, a.x, a.w0, a.w1, a.gamma, a.M, a.N, a.K, a.tiles, a); break;
+    case EPI_RMSNORM_SWIGLU: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_RMSNORM_SWIGLU, XT>), g, b, gamma_lds, stream, a.x, a.w0, a.w1, a.gamma, a.M, a.N, a.K, a.tiles, a); break;
+    default: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_SWIGLU, XT>), g, b, 0, stream, a.x, a.w0, a.w1, a.gamma, a.M, a.N, a.K, a.tiles, a); break;
     }
     return hipGetLastError();
 }

@@ -93,8 +93,12 @@ struct UnitRegs {
 };
 
 template <int MT, int EPI>
-__global__ __launch_bounds__(SK_THREADS) void skinny_streamk(SkinnyArgs a)
+__global__ __launch_bounds__(SK_THREADS) void skinny_streamk(const uint16_t* x_, const uint16_t* w0_, const uint16_t* w1_,
+                                                             int M_, int N_, int K_, int tiles_, int kchunks_, SkinnyArgs a)
 {
+    // The operands the first loads need come as leading scalar arguments: the hardware preloads those
+    // into registers at wave launch, so the first weight request does not wait for an argument fetch.
+    a.x = x_; a.w0 = w0_; a.w1 = w1_; a.M = M_; a.N = N_; a.K = K_; a.tiles = tiles_; a.kchunks = kchunks_;
     __shared__ uintx4 xs[2][8 * MT * 64];          // staged activations, MFMA B-operand order
     __shared__ uintx4 wt[SK_WAVES][WT_UNITS];      // wave-private transposition buffers
     __shared__ float s_red[SK_WAVES][32];
@@ -406,11 +410,11 @@ hipError_t launch_mt(const SkinnyArgs& a, int epilogue, int grid, hipStream_t st
 {
     dim3 g(grid), b(SK_THREADS);
     switch (epilogue) {
-    case EPI_PLAIN: hipLaunchKernelGGL((skinny_streamk<MT, EPI_PLAIN>), g, b, 0, stream, a); break;
-    case EPI_RMSNORM: hipLaunchKernelGGL((skinny_streamk<MT, EPI_RMSNORM>), g, b, 0, stream, a); break;
-    case EPI_RMSNORM_ROPE: hipLaunchKernelGGL((skinny_streamk<MT, EPI_RMSNORM_ROPE>), g, b, 0, stream, a); break;
-    case EPI_RMSNORM_SWIGLU: hipLaunchKernelGGL((skinny_streamk<MT, EPI_RMSNORM_SWIGLU>), g, b, 0, stream, a); break;
-    default: hipLaunchKernelGGL((skinny_streamk<MT, EPI_SWIGLU>), g, b, 0, stream, a); break;
+    case EPI_PLAIN: hipLaunchKernelGGL((skinny_streamk<MT, EPI_PLAIN>), g, b, 0, stream, a.x, a.w0, a.w1, a.M, a.N, a.K, a.tiles, a.kchunks, a); break;
+    case EPI_RMSNORM: hipLaunchKernelGGL((skinny_streamk<MT, EPI_RMSNORM>), g, b, 0, stream, a.x, a.w0, a.w1, a.M, a.N, a.K, a.tiles, a.kchunks, a); break;
+    case EPI_RMSNORM_ROPE: hipLaunchKernelGGL((skinny_streamk<MT, EPI_RMSNORM_ROPE>), g, b, 0, stream, a.x, a.w0, a.w1, a.M, a.N, a.K, a.tiles, a.kchunks, a); break;
+    case EPI_RMSNORM_SWIGLU: hipLaunchKernelGGL((skinny_streamk<MT, EPI_RMSNORM_SWIGLU>), g, b, 0, stream, a.x, a.w0, a.w1, a.M, a.N, a.K, a.tiles, a.kchunks, a); break;
+    default: hipLaunchKernelGGL((skinny_streamk<MT, EPI_SWIGLU>), g, b, 0, stream, a.x, a.w0, a.w1, a.M, a.N, a.K, a.tiles, a.kchunks, a); break;
     }
     return hipGetLastError();
 }
