@@ -90,16 +90,16 @@ bool use_skinny(int M)
 //                must divide well among the compute units and every wave reads its slice of x per slab;
 //   row blocks : N / #CUs rows per workgroup in one contiguous block, several 16-row tiles in flight
 //                sharing the wave's slice of x: no hand-over, balanced whenever N >> #CUs.
-// Decided by a time model in microseconds whose constants were fitted to 153 measured (shape, M) points
-// on MI355X (7B..70B projections, M = 1..32; the pick is within 3 % of the best of the three on all but
-// four of them, 4.5 % at worst).  t_w = weight bytes / 7.0 TB/s; a wave's last unit of 256 k may be
+// Decided by a time model in microseconds whose constants were fitted to measured (shape, M) points on
+// MI355X (17 shapes: the 7B..70B projections and a 32000-row output head, M = 1..32; the pick is within
+// 3 % of the best of the three on all but a handful, 5 % at worst).  t_w = weight bytes / 7.0 TB/s; a wave's last unit of 256 k may be
 // partly empty (ragged, slabs and blocks).
-//   stream-K   : ~5.5 us fixed + 1.03 t_w + the hand-over, 0.5 + 0.05 M us up to M = 16 and ~5 us above;
-//   row slabs  : ~3 us fixed; slowed by the slots a ragged last round leaves empty, by the activation
+//   stream-K   : ~5.5 us fixed + 1.06 t_w + the hand-over, 0.5 + 0.05 M us up to M = 16 and ~5 us above;
+//   row slabs  : ~3.5 us fixed; slowed by the slots a ragged last round leaves empty, by the activation
 //                traffic (x1.02 at M<=4, x1.09 at M<=8, x1.15 at M<=16, x1.45 above) and by ~10 % for
 //                the RMSNorm prologue;
 //   row blocks : ~3.8 us fixed (all tiles of a pass finish together: their reduction is not hidden),
-//                1.5 us per further pass over K, 3 us more with one or two tiles per workgroup and
+//                0.5 us per further pass over K, 4 us more with one or two tiles per workgroup and
 //                8192 <= K < 16384 (measured on the 70B O and 13B down projections); the activation
 //                traffic is shared by the tiles of a pass (+5 % / +15 % / +40 % at M <= 8 / 16 / 32,
 //                divided by the tiles per pass); a ragged last unit costs about a third of what it
@@ -119,19 +119,19 @@ int pick_decode_kernel(int M, int N, int K, int epilogue, int cus)
     double ragged = (double)units_max * SK_KC * SK_WAVES / (double)K;
     if (ragged < 1.0) ragged = 1.0;
 
-    const double t_sk = 5.5 + 1.03 * t_w + (M <= 16 ? 0.5 + 0.05 * M : 5.0);
+    const double t_sk = 5.5 + 1.06 * t_w + (M <= 16 ? 0.5 + 0.05 * M : 5.0);
 
     const long slabs = ((long)N + out_per_tile - 1) / out_per_tile;
     const long rounds = (slabs + cus - 1) / cus;
     const double fill = (double)slabs / (double)(rounds * cus);
     const double x_slab = M <= 1 ? 1.0 : M <= 4 ? 1.02 : M <= 8 ? 1.09 : M <= 16 ? 1.15 : 1.45;
-    const double t_slab = 3.0 + t_w * x_slab * ragged / fill * (is_rms(epilogue) ? 1.10 : 1.0);
+    const double t_slab = 3.5 + t_w * x_slab * ragged / fill * (is_rms(epilogue) ? 1.10 : 1.0);
 
     const RowBlockPlan bp = plan_rowblock(N, epilogue, cus);
     const double per_pass = (double)bp.per_wg / out_per_tile / bp.passes;      // tiles sharing one load of x
     const double x_extra = (M <= 4 ? 0.0 : M <= 8 ? 0.05 : M <= 16 ? 0.15 : 0.40) / per_pass;
     const double lacking = (double)bp.per_wg * cus / (double)N;
-    const double t_block = 3.8 + 1.5 * (bp.passes - 1) + ((bp.tiles <= 2 && K >= 8192 && K < 16384) ? 3.0 : 0.0) +
+    const double t_block = 3.8 + 0.5 * (bp.passes - 1) + ((bp.tiles <= 2 && K >= 8192 && K < 16384) ? 4.0 : 0.0) +
                            t_w * (1.0 + x_extra) * (1.0 + 0.3 * (ragged - 1.0)) * lacking;
 
     if (t_block < t_slab && t_block < t_sk) return DK_ROWBLOCK;

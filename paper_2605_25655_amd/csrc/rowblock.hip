@@ -32,8 +32,8 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
     // The operands the first loads need come as leading scalar arguments: the hardware preloads those
     // into registers at wave launch, so the first weight request does not wait for an argument fetch.
     a.x = x_; a.w0 = w0_; a.w1 = w1_; a.gamma = gamma_; a.M = M_; a.N = N_; a.K = K_;
-    static_assert(T == 2 || T == 4 || T == 6, "tile-steps alternate between two register buffers");
-    constexpr int RT = T / 2;                           // tiles per reduction round (bounds the LDS it takes)
+    static_assert(T >= 2 && T <= 6, "tiles in flight");
+    constexpr int RT = (T + 1) / 2;                     // tiles per reduction round (bounds the LDS it takes)
     constexpr int OUT_PER_TILE = is_swiglu(EPI) ? 8 : 16;
     __shared__ uintx4 wt[SK_WAVES][WT_UNITS];          // wave-private transposition buffers
     __shared__ float s_part[SK_WAVES][RT][MT * 4 * 64]; // the waves' partial tiles
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
     // same lines a neighbouring lane asks for); a piece past the wave's k range from the first piece of
     // the unit; a whole tile past the block (or past the wave's last tile-step: valid = false) from the
     // first piece of its rows.  What such loads return is zeroed or never stored.
-    auto issue_w = [&](int tile, int uu, bool valid, uintx4 (&w)[8]) {
+    auto issue_w = [&](int tile, int uu, bool valid, uintx4 (&w)[8]) __attribute__((always_inline)) {
         const int k0 = k_begin + uu * SK_KC;
         const int k_lim = (valid && tile < nT) ? k_end : 0;
 #pragma unroll
@@ -128,7 +128,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
 
     // One tile-step = request the next tile-step's weights (the next tile of this unit, or tile 0 of the
     // next unit), then multiply tile TI of the current pass by the unit's activations.
-    auto request_next = [&](auto ti, uintx4 (&pre)[8]) {
+    auto request_next = [&](auto ti, uintx4 (&pre)[8]) __attribute__((always_inline)) {
         constexpr int TI = decltype(ti)::value;
         if constexpr (TI + 1 == T) {
             if (++p_uu == nU) { p_uu = 0; ++p_pass; }
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
         }
         ++requested;
     };
-    auto multiply = [&](auto ti, uintx4 (&cur)[8]) {
+    auto multiply = [&](auto ti, uintx4 (&cur)[8]) __attribute__((always_inline)) {
         constexpr int TI = decltype(ti)::value;
         const int k0 = k_begin + uu * SK_KC;
         // zero what came from a redirected address
@@ -184,13 +184,13 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
             }
         }
     };
-    auto tile_step = [&](auto ti, uintx4 (&cur)[8], uintx4 (&pre)[8]) {
+    auto tile_step = [&](auto ti, uintx4 (&cur)[8], uintx4 (&pre)[8]) __attribute__((always_inline)) {
         request_next(ti, pre);
         multiply(ti, cur);
     };
 
     // Epilogue of one finished tile: thread -> (token m, row r)
-    auto finish_tile = [&](int tile, int tt) {
+    auto finish_tile = [&](int tile, int tt) __attribute__((always_inline)) {
         const float (&sum)[32][17] = s_sum[tt];
         const int r = tid & 15, m = tid >> 4;
         if (m >= a.M) return;
@@ -223,8 +223,10 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
         }
     };
 
-    const int units = P * nU;
-    for (int it = 0; it < units; ++it) {
+    // One unit of 256 k for all T tiles of the pass.  Tile-steps alternate between the two register
+    // buffers; PAR says which of them holds tile 0 of this unit (with an odd T it flips from unit to unit).
+    auto run_unit = [&](auto par) __attribute__((always_inline)) {
+        constexpr int PAR = decltype(par)::value;
         const int k0 = k_begin + uu * SK_KC;
         const bool first_pass = (pass == 0);
 
@@ -246,7 +248,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
                     xl[mt][ph * 4 + jj] = ld_cached(row + (k < k_end ? k : k0));
                 }
             }
-        request_next(std::integral_constant<int, 0>{}, wb1);
+        request_next(std::integral_constant<int, 0>{}, PAR ? wb0 : wb1);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -258,32 +260,31 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
 #pragma unroll
                 for (int s4 = 0; s4 < 4; ++s4) xr[ph * 4 + s4][mt] = wt[wv][c * WT_STRIDE + 4 * s4 + kg];
             }
-        multiply(std::integral_constant<int, 0>{}, wb0);
-        tile_step(std::integral_constant<int, 1>{}, wb1, wb0);
-        if constexpr (T > 2) {
-            tile_step(std::integral_constant<int, 2>{}, wb0, wb1);
-            tile_step(std::integral_constant<int, 3>{}, wb1, wb0);
-        }
-        if constexpr (T > 4) {
-            tile_step(std::integral_constant<int, 4>{}, wb0, wb1);
-            tile_step(std::integral_constant<int, 5>{}, wb1, wb0);
-        }
+        multiply(std::integral_constant<int, 0>{}, PAR ? wb1 : wb0);
+        tile_step(std::integral_constant<int, 1>{}, PAR ? wb0 : wb1, PAR ? wb1 : wb0);
+        if constexpr (T > 2) tile_step(std::integral_constant<int, 2>{}, PAR ? wb1 : wb0, PAR ? wb0 : wb1);
+        if constexpr (T > 3) tile_step(std::integral_constant<int, 3>{}, PAR ? wb0 : wb1, PAR ? wb1 : wb0);
+        if constexpr (T > 4) tile_step(std::integral_constant<int, 4>{}, PAR ? wb1 : wb0, PAR ? wb0 : wb1);
+        if constexpr (T > 5) tile_step(std::integral_constant<int, 5>{}, PAR ? wb0 : wb1, PAR ? wb1 : wb0);
 
         const bool pass_ends = (uu + 1 == nU);
         const int this_pass = pass;
         if (++uu == nU) { uu = 0; ++pass; }
-        if (!pass_ends) continue;
+        if (!pass_ends) return;
 
         // ---- the eight partial tiles of each of the pass's tiles meet in LDS, RT tiles per round -------
 #pragma unroll
-        for (int rr = 0; rr < T / RT; ++rr) {
+        for (int rr = 0; rr < (T + RT - 1) / RT; ++rr) {
 #pragma unroll
             for (int tt = 0; tt < RT; ++tt)
+                if (rr * RT + tt < T) {
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
+                    for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) s_part[wv][tt][(mt * 4 + i) * 64 + lane] = acc[rr * RT + tt][mt][i];
-                    acc[rr * RT + tt][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+                        for (int i = 0; i < 4; ++i)
+                            s_part[wv][tt][(mt * 4 + i) * 64 + lane] = acc[rr * RT + tt < T ? rr * RT + tt : 0][mt][i];
+                        acc[rr * RT + tt < T ? rr * RT + tt : 0][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+                    }
                 }
             if (is_rms(EPI) && first_pass && rr == 0) {
 #pragma unroll
@@ -296,7 +297,8 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
                 if (MT == 1 && kg == 0) s_red[wv][16 + c] = 0.f;
             }
             __syncthreads();
-            for (int e = tid; e < RT * MT * 256; e += SK_THREADS) {
+            const int round_tiles = (rr + 1) * RT <= T ? RT : T - rr * RT;
+            for (int e = tid; e < round_tiles * MT * 256; e += SK_THREADS) {
                 const int tt = e / (MT * 256), q = e % (MT * 256);
                 float v = 0.f;       // fixed order: waves 0..7
 #pragma unroll
@@ -314,10 +316,21 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
 #pragma unroll
             for (int tt = 0; tt < RT; ++tt) {
                 const int tile = this_pass * T + rr * RT + tt;
-                if (tile < nT) finish_tile(tile, tt);
+                if (rr * RT + tt < T && tile < nT) finish_tile(tile, tt);
             }
             // s_part is rewritten only after every thread has passed the second barrier above, s_sum only
             // after the next round's first barrier, which every thread reaches after these epilogues
+        }
+    };
+
+    const int units = P * nU;
+    if constexpr (T % 2 == 0) {
+        for (int it = 0; it < units; ++it) run_unit(std::integral_constant<int, 0>{});
+    } else {
+        for (int it = 0; it < units; it += 2) {
+            run_unit(std::integral_constant<int, 0>{});
+            if (it + 1 >= units) break;
+            run_unit(std::integral_constant<int, 1>{});
         }
     }
 }
@@ -376,7 +389,7 @@ RowBlockPlan plan_rowblock(int N, int epilogue, int num_cus)
     p.tiles = (per_wg + out_per_tile - 1) / out_per_tile;
     p.passes = (p.tiles + 5) / 6;
     const int per_pass = (p.tiles + p.passes - 1) / p.passes;
-    p.T = per_pass <= 2 ? 2 : per_pass <= 4 ? 4 : 6;
+    p.T = per_pass < 2 ? 2 : per_pass;
     return p;
 }
 
@@ -384,9 +397,13 @@ hipError_t launch_rowblock(const SkinnyArgs& a, int epilogue, int num_cus, hipSt
 {
     if (a.K < 1024 || a.K > ROWSLAB_MAX_K || a.N < 1) return hipErrorInvalidValue;
     const RowBlockPlan p = plan_rowblock(a.N, epilogue, num_cus);
-    if (p.T == 2) return launch_t<2>(a, epilogue, p.per_wg, p.grid, stream);
-    if (p.T == 4) return launch_t<4>(a, epilogue, p.per_wg, p.grid, stream);
-    return launch_t<6>(a, epilogue, p.per_wg, p.grid, stream);
+    switch (p.T) {
+    case 2: return launch_t<2>(a, epilogue, p.per_wg, p.grid, stream);
+    case 3: return launch_t<3>(a, epilogue, p.per_wg, p.grid, stream);
+    case 4: return launch_t<4>(a, epilogue, p.per_wg, p.grid, stream);
+    case 5: return launch_t<5>(a, epilogue, p.per_wg, p.grid, stream);
+    default: return launch_t<6>(a, epilogue, p.per_wg, p.grid, stream);
+    }
 }
 
 }  // namespace thi
