@@ -33,7 +33,9 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
     // into registers at wave launch, so the first weight request does not wait for an argument fetch.
     a.x = x_; a.w0 = w0_; a.w1 = w1_; a.gamma = gamma_; a.M = M_; a.N = N_; a.K = K_;
     static_assert(T >= 2 && T <= 6, "tiles in flight");
-    constexpr int RT = (T + 1) / 2;                     // tiles per reduction round (bounds the LDS it takes)
+    // tiles per reduction round: all of them while the partial tiles and sums fit ~55 KiB of LDS (static
+    // LDS <= 92 KiB leaves room for the largest gamma slice), else half a pass
+    constexpr int RT = (T * MT <= 6 && T <= 5) ? T : (T + 1) / 2;
     constexpr int OUT_PER_TILE = is_swiglu(EPI) ? 8 : 16;
     __shared__ uintx4 wt[SK_WAVES][WT_UNITS];          // wave-private transposition buffers
     __shared__ float s_part[SK_WAVES][RT][MT * 4 * 64]; // the waves' partial tiles
@@ -345,7 +347,7 @@ hipError_t launch_t_mt(const SkinnyArgs& a, int epilogue, int per_wg, int grid, 
     const size_t gamma_lds = (size_t)SK_WAVES * gamma_pieces(a.K) * sizeof(uintx4);
     static bool attr_set = false;       // static (+ dynamic) LDS passes 64 KiB: every variant needs the opt-in
     if (!attr_set) {
-        // largest static part: T = 6, two token tiles (~90 KiB); with this it stays inside the 160 KiB of a CU
+        // largest static part: ~90 KiB (T = 3 or 5 with two token tiles); with this it stays inside the 160 KiB of a CU
         const int most = (int)((size_t)SK_WAVES * gamma_pieces(ROWSLAB_MAX_K) * sizeof(uintx4));
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_PLAIN>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, most);
