@@ -529,6 +529,83 @@ def test_layer_closing_argument_errors(thi):
     assert thi.thi_rmsnorm_swiglu_mlp(z(M, K), z(K), 1e-6, z(I, K), z(I, K), z(K, I), None, z(M, K), r.ws, check=False) == 0
 
 
+# ------------------------------- properties that hold at any size (full 7B shapes)
+@pytest.mark.parametrize("family", [3, 4])
+@pytest.mark.parametrize("M", [1, 32])
+def test_weight_row_permutation_is_exact_at_full_size(thi, family, M):
+    """In the row-slab and row-block kernels an output's sum depends on its weight row and on how K is
+    cut among the eight waves, not on where the row sits: permuting the rows of W must permute the outputs
+    bit for bit (7B QKV and gate/up shapes; no oracle needed at this size)."""
+    import torch
+    H, N, I = 4096, 12288, 11008
+    say(f"[case] row permutation, family {family}, M={M}, 7B shapes")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4242 + M)
+    x = torch.randn((M, H), generator=g, device="cuda", dtype=torch.float32).half()
+    gamma = (1 + 0.1 * torch.randn((H,), generator=g, device="cuda", dtype=torch.float32)).half()
+    w = (0.02 * torch.randn((N, H), generator=g, device="cuda", dtype=torch.float32)).half()
+    wg = (0.02 * torch.randn((I, H), generator=g, device="cuda", dtype=torch.float32)).half()
+    wu = (0.02 * torch.randn((I, H), generator=g, device="cuda", dtype=torch.float32)).half()
+    perm = torch.randperm(N, generator=g, device="cuda")
+    permi = torch.randperm(I, generator=g, device="cuda")
+    r = Runner(M, H, I, N)
+    prev = thi.thi_set_kernel_family(family)
+    try:
+        a = r.rmsnorm_qkv(x, gamma, 1e-6, w)
+        ap = r.rmsnorm_qkv(x, gamma, 1e-6, w[perm].contiguous())
+        h = r.swiglu_gate_up(x, wg, wu)
+        hp = r.swiglu_gate_up(x, wg[permi].contiguous(), wu[permi].contiguous())
+        torch.cuda.synchronize()
+    finally:
+        thi.thi_set_kernel_family(prev)
+    assert torch.equal(a[:, perm].view(torch.int16), ap.view(torch.int16))
+    assert torch.equal(h[:, permi].view(torch.int16), hp.view(torch.int16))
+    assert torch.isfinite(a.float()).all() and torch.isfinite(h.float()).all()
+
+
+@pytest.mark.parametrize("family", [1, 3, 4])
+def test_token_permutation_is_exact_at_full_size(thi, family):
+    """Tokens are independent columns of the accumulator tile: permuting the rows of x must permute the
+    rows of the output bit for bit (7B down-projection shape, M = 32)."""
+    import torch
+    M, N, K = 32, 4096, 11008
+    say(f"[case] token permutation, family {family}")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(777)
+    x = torch.randn((M, K), generator=g, device="cuda", dtype=torch.float32).half()
+    w = (0.02 * torch.randn((N, K), generator=g, device="cuda", dtype=torch.float32)).half()
+    perm = torch.randperm(M, generator=g, device="cuda")
+    r = Runner(M, K, K, N)
+    prev = thi.thi_set_kernel_family(family)
+    try:
+        a = r.linear(x, w)
+        ap = r.linear(x[perm].contiguous(), w)
+        torch.cuda.synchronize()
+    finally:
+        thi.thi_set_kernel_family(prev)
+    assert torch.equal(a[perm].view(torch.int16), ap.view(torch.int16))
+
+
+@pytest.mark.parametrize("M,N,K", [(32, 4096, 11008), (1, 12288, 4096), (100, 4096, 4096), (2048, 8192, 8192), (1000, 10240, 8192)])
+def test_power_of_two_scaling_is_exact_at_full_size(thi, M, N, K):
+    """Scaling the activations by a power of two scales every product and every partial sum exactly, whatever
+    the kernel, its tiling and its reduction order: out(4x) = 4 out(x) bit for bit wherever neither result is
+    subnormal or overflows (decode kernels, few-token and prefill GEMM configurations, full-size shapes)."""
+    import torch
+    say(f"[case] power-of-two scaling M={M} N={N} K={K}")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(99 + M)
+    x = torch.randn((M, K), generator=g, device="cuda", dtype=torch.float32).half()
+    w = (0.02 * torch.randn((N, K), generator=g, device="cuda", dtype=torch.float32)).half()
+    r = Runner(M, K, K, N)
+    a = r.linear(x, w)
+    b = r.linear((x.float() * 4).half(), w)
+    torch.cuda.synchronize()
+    ok = (a.float().abs() >= 2.0 ** -12) & (b.float().abs() < 60000)
+    assert ok.float().mean() > 0.99
+    assert torch.equal((a.float() * 4)[ok], b.float()[ok])
+
+
 # ------------------------------------------------- the five layer configs
 def _layer_case(thi, oracle_mod, cfg_id, rows_limit=32):
     cfg = synth.CONFIGS[cfg_id]
