@@ -108,6 +108,41 @@ def test_sharp_softmax_selects_one_row(thi, oracle_mod):
             assert np.array_equal(got[b, h].view(np.uint16), v[b, h, pick[b][h]].view(np.uint16))
 
 
+@pytest.mark.parametrize("B,Hq,Hkv", [(32, 32, 32), (32, 64, 8), (1, 64, 8)])
+def test_full_size_properties_without_an_oracle(thi, B, Hq, Hkv):
+    """At the benchmark's size (2048 cached positions per request, heads of 128): permuting the requests
+    permutes the outputs bit for bit (requests are independent), and scaling V by a power of two scales the
+    output exactly (the weights do not depend on V)."""
+    import torch
+    D, S = 128, 2048
+    say(f"[case] attention properties B={B} Hq={Hq} Hkv={Hkv} S={S}")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5 + B + Hkv)
+    q = torch.randn((B, Hq, D), generator=g, device="cuda", dtype=torch.float32).half()
+    k = torch.randn((B, Hkv, S, D), generator=g, device="cuda", dtype=torch.float32).half()
+    v = torch.randn((B, Hkv, S, D), generator=g, device="cuda", dtype=torch.float32).half()
+    lens = torch.randint(1, S + 1, (B,), generator=g, device="cuda", dtype=torch.int32)
+    lens[0] = S
+    ws = thi.Workspace(thi.thi_attention_workspace_bytes(B, Hq, Hkv, D, S), init=False)
+    scale = 1.0 / D ** 0.5
+
+    def call(q_, k_, v_, l_):
+        out = torch.full((B, Hq, D), float("nan"), dtype=torch.float16, device="cuda")
+        thi.thi_decode_attention(q_, k_, v_, l_, scale, out, ws)
+        torch.cuda.synchronize()
+        return out
+
+    a = call(q, k, v, lens)
+    assert torch.isfinite(a.float()).all()
+    perm = torch.randperm(B, generator=g, device="cuda")
+    ap = call(q[perm].contiguous(), k[perm].contiguous(), v[perm].contiguous(), lens[perm].contiguous())
+    assert torch.equal(a[perm].view(torch.int16), ap.view(torch.int16))
+    a4 = call(q, k, (v.float() * 4).half(), lens)
+    ok = a.float().abs() >= 2.0 ** -12
+    assert ok.float().mean() > 0.95
+    assert torch.equal((a.float() * 4)[ok], a4.float()[ok])
+
+
 def test_attention_argument_errors(thi):
     import torch
     z = lambda *sh: torch.zeros(sh, dtype=torch.float16, device="cuda")
