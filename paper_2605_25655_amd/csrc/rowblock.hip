@@ -6,14 +6,15 @@
 // compute unit streams the same number of weight bytes whatever N is), each block over the whole
 // reduction dimension: nothing is handed from workgroup to workgroup.  A block is T tiles of 16 weight rows
 // (rows past the block's end are masked).  Inside the workgroup the k range is cut into eight
-// contiguous pieces, one per wave; per unit of 256 k a wave loads its slice of the activations ONCE, in
-// MFMA operand layout, and uses it for all T tiles, so the activation traffic through the vector
-// cache per weight byte is 1/T of the one-slab kernel's (what limits that kernel from M = 16 up).
+// contiguous pieces, one per wave; per unit of 256 k a wave loads its slice of the activations ONCE
+// (coalesced, then through its LDS buffer into MFMA operand layout) and uses it for all T tiles, so the
+// activation traffic through the vector cache per weight byte is 1/T of the one-slab kernel's (what
+// limits that kernel from M = 16 up).
 // Weights stream as in the row-slab kernel: coalesced 16-byte loads one tile-step ahead of the
 // arithmetic, a wave-private LDS buffer to reach operand layout.  The eight partial tiles meet in
 // LDS, are added in wave order (reproducible) and finished by the fused epilogue (Sec. III-C.1:
-// RMSNorm scale, rotary embedding, SwiGLU, residual).  Blocks of more than T tiles take several passes
-// over K.
+// RMSNorm scale, rotary embedding, SwiGLU, residual).  T is the block's tile count when that is at most
+// six; larger blocks take several passes over K with their tiles dealt evenly to the passes.
 #include "thi_internal.h"
 
 #include <type_traits>
