@@ -279,8 +279,10 @@ def main():
     if traffic_kib is None and (args.config, M) in MEASURED_TRAFFIC_KIB:
         traffic_kib, traffic_src = MEASURED_TRAFFIC_KIB[(args.config, M)]
     if traffic_kib is not None:
-        roof["traffic"] = {"fetch_bytes": traffic_kib[0] * 1024, "write_bytes": traffic_kib[1] * 1024,
-                           "algorithmic_bytes": gu_bytes, "source": traffic_src}
+        # HBM bytes per launch (reads + writes); the parts and where they come from next to it
+        roof["traffic"] = (traffic_kib[0] + traffic_kib[1]) * 1024
+        roof["traffic_detail"] = {"fetch_bytes": traffic_kib[0] * 1024, "write_bytes": traffic_kib[1] * 1024,
+                                  "algorithmic_bytes": gu_bytes, "source": traffic_src}
     roof["frac"] = round(roof["achieved"] / roof["peak"], 4)
     roof["launch_us"] = ops["gate_up"]["us"]
 
