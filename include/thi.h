@@ -213,6 +213,16 @@ int thi_version(void);
 int thi_set_kernel_family(int family);
 
 /*
+ * Tuning/diagnostic hook like the one above, for the row-block decode kernel: the
+ * number of workgroups that share one block of rows, each taking 1/split of the
+ * reduction dimension (their sums meet through the workspace).  split: 0 = chosen
+ * by the library per call (default), 1 = never share, 2..6 = share wherever the
+ * shape admits it (plain linear operator, K >= 1024 * split, at most 6 tiles of
+ * 16 rows per block), else as 1.  Returns the previous setting.
+ */
+int thi_set_rowblock_split(int split);
+
+/*
  * Diagnostic: the kernel family (numbered as above, never 0 for valid arguments)
  * that a call with these extents would run under the current setting.
  * fused: 0 = plain linear operator, 1 = RMSNorm in front, 2 = gate/up with the

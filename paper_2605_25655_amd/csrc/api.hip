@@ -15,6 +15,7 @@ constexpr int SKINNY_GROUP = 32;          // tokens per skinny launch
 constexpr int SKINNY_MAX_M = 32;          // automatic dispatch: M <= this -> skinny kernels (measured crossover)
 
 std::atomic<int> g_family{0};
+std::atomic<int> g_rowblock_split{0};      // 0: chosen per call; >= 1: forced where the shape admits it
 
 int device_cu_count()
 {
@@ -103,7 +104,44 @@ bool use_skinny(int M)
 //                8192 <= K < 16384 (measured on the 70B O and 13B down projections); the activation
 //                traffic is shared by the tiles of a pass (+5 % / +15 % / +40 % at M <= 8 / 16 / 32,
 //                divided by the tiles per pass); a ragged last unit costs about a third of what it
-//                costs the slabs; slowed by the rows the last workgroup lacks.
+//                costs the slabs; slowed by the rows the last workgroup lacks.  With S workgroups per
+//                block (plain kind): S x the tiles share a load of x, the eight waves of S workgroups
+//                divide K, and the hand-over at the end costs ~1.8 us.
+// Row blocks, modelled time in microseconds with `split` workgroups per block (constants: see below)
+double rowblock_time(int M, int N, int K, int epilogue, int cus, int split)
+{
+    const bool swiglu = is_swiglu(epilogue);
+    const int out_per_tile = swiglu ? 8 : 16;
+    const double t_w = (swiglu ? 2.0 : 1.0) * (double)N * (double)K * 2.0 / 7.0e6;
+    const int groups = (K + 127) / 128, groups_max = (groups + 8 * split - 1) / (8 * split), units_max = (groups_max + 1) / 2;
+    double ragged = (double)units_max * SK_KC * SK_WAVES * split / (double)K;
+    if (ragged < 1.0) ragged = 1.0;
+    const RowBlockPlan bp = plan_rowblock(N, epilogue, cus, split);
+    const double per_pass = (double)bp.per_wg / out_per_tile / bp.passes;      // tiles sharing one load of x
+    const double x_extra = (M <= 4 ? 0.0 : M <= 8 ? 0.05 : M <= 16 ? 0.15 : 0.40) / per_pass;
+    const double lacking = (double)bp.per_wg * (cus / split) / (double)N;
+    return 3.8 + 0.5 * (bp.passes - 1) + ((split == 1 && bp.tiles <= 2 && K >= 8192 && K < 16384) ? 4.0 : 0.0) +
+           (split > 1 ? 1.8 : 0.0) + t_w * (1.0 + x_extra) * (1.0 + 0.3 * (ragged - 1.0)) * lacking;
+}
+
+// Row blocks: how many workgroups share a block (1 = none)?  The smallest modelled time; sharing must
+// win by half a microsecond.  Not above K = 24576: the 70B down projection (K = 28672) measured 15 %
+// slower with two workgroups on the halves of its 56 KiB rows than the model says.
+int pick_rowblock_split(int M, int N, int K, int epilogue, int cus)
+{
+    const int forced = g_rowblock_split.load(std::memory_order_relaxed);
+    if (forced >= 1) return rowblock_split_ok(N, K, epilogue, cus, forced) ? forced : 1;
+    if (epilogue != EPI_PLAIN || K > 24576) return 1;
+    int best = 1;
+    double t_best = rowblock_time(M, N, K, epilogue, cus, 1) - 0.5;
+    for (int s = 2; s <= 4; ++s) {
+        if (!rowblock_split_ok(N, K, epilogue, cus, s)) continue;
+        const double t = rowblock_time(M, N, K, epilogue, cus, s);
+        if (t < t_best) { t_best = t; best = s; }
+    }
+    return best;
+}
+
 enum DecodeKernel { DK_STREAMK = 1, DK_ROWSLAB = 3, DK_ROWBLOCK = 4 };
 int pick_decode_kernel(int M, int N, int K, int epilogue, int cus)
 {
@@ -127,12 +165,7 @@ int pick_decode_kernel(int M, int N, int K, int epilogue, int cus)
     const double x_slab = M <= 1 ? 1.0 : M <= 4 ? 1.02 : M <= 8 ? 1.09 : M <= 16 ? 1.15 : 1.45;
     const double t_slab = 3.5 + t_w * x_slab * ragged / fill * (is_rms(epilogue) ? 1.10 : 1.0);
 
-    const RowBlockPlan bp = plan_rowblock(N, epilogue, cus);
-    const double per_pass = (double)bp.per_wg / out_per_tile / bp.passes;      // tiles sharing one load of x
-    const double x_extra = (M <= 4 ? 0.0 : M <= 8 ? 0.05 : M <= 16 ? 0.15 : 0.40) / per_pass;
-    const double lacking = (double)bp.per_wg * cus / (double)N;
-    const double t_block = 3.8 + 0.5 * (bp.passes - 1) + ((bp.tiles <= 2 && K >= 8192 && K < 16384) ? 4.0 : 0.0) +
-                           t_w * (1.0 + x_extra) * (1.0 + 0.3 * (ragged - 1.0)) * lacking;
+    const double t_block = rowblock_time(M, N, K, epilogue, cus, pick_rowblock_split(M, N, K, epilogue, cus));
 
     if (t_block < t_slab && t_block < t_sk) return DK_ROWBLOCK;
     return t_slab < t_sk ? DK_ROWSLAB : DK_STREAMK;
@@ -173,7 +206,7 @@ int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const ui
             if (rope.pos) a.rope.pos = rope.pos + m0;
             hipError_t e;
             if (!slab) e = launch_skinny(a, epilogue, cus, stream);
-            else if (block) e = launch_rowblock(a, epilogue, cus, stream);
+            else if (block) e = launch_rowblock(a, epilogue, cus, stream, pick_rowblock_split(a.M, N, K, epilogue, cus));
             else e = launch_rowslab(a, epilogue, cus, stream);
             if (e != hipSuccess) return THI_ERR_HIP;
         }
@@ -417,6 +450,12 @@ int thi_query_kernel_family(int M, int N, int K, int fused)
     if (!use_skinny(M)) return 2;
     const int epilogue = fused == 1 ? EPI_RMSNORM : fused == 2 ? EPI_SWIGLU : EPI_PLAIN;
     return pick_decode_kernel(M < SKINNY_GROUP ? M : SKINNY_GROUP, N, K, epilogue, device_cu_count());
+}
+
+int thi_set_rowblock_split(int split)
+{
+    if (split < 0 || split > ROWBLOCK_MAX_SPLIT) split = 0;
+    return g_rowblock_split.exchange(split);
 }
 
 int thi_set_kernel_family(int family)

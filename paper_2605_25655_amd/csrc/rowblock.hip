@@ -15,6 +15,13 @@
 // LDS, are added in wave order (reproducible) and finished by the fused epilogue (Sec. III-C.1:
 // RMSNorm scale, rotary embedding, SwiGLU, residual).  T is the block's tile count when that is at most
 // six; larger blocks take several passes over K with their tiles dealt evenly to the passes.
+//
+// Where N is so small that a block is a single tile (N = hidden size: the O and down projections), the
+// activations would cost the vector cache twice the weights' bytes at 32 tokens.  The SPLIT variant (plain
+// kind) then lets S workgroups share a block of S x as many rows, each over 1/S of K: a slice of x serves
+// S x as many tiles.  The S sums of a block meet through hand-over slots in the workspace; the workgroup
+// that arrives last (a counter per block, reset by that workgroup) adds them in share order, so the
+// result does not depend on the order of arrival, and nobody waits for anybody.
 #include "thi_internal.h"
 
 #include <type_traits>
@@ -25,7 +32,7 @@ namespace {
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
-template <int T, int MT, int EPI>
+template <int T, int MT, int EPI, bool SPLIT = false>
 __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_, const uint16_t* w0_, const uint16_t* w1_,
                                                               const uint16_t* gamma_, int M_, int N_, int K_, int per_wg,
                                                               SkinnyArgs a)
@@ -43,15 +50,22 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
     __shared__ float s_sum[RT][32][17];                // finished sums [tile][token][row]
     __shared__ float s_red[SK_WAVES][32];
     __shared__ float s_ssq[32];
+    __shared__ unsigned s_last;                        // SPLIT: this workgroup closes its row block
     extern __shared__ uintx4 s_gamma[];                // RMSNorm: each wave's slice of gamma
+    static_assert(!SPLIT || EPI == EPI_PLAIN, "the reduction dimension is only shared for the plain kind");
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int K = a.K;
 
-    // this workgroup's block of outputs (rows of W; gate/up row pairs for SwiGLU)
-    const int r0 = (int)blockIdx.x * per_wg;
+    // this workgroup's block of outputs (rows of W; gate/up row pairs for SwiGLU); SPLIT: S workgroups
+    // share a block, each with 1/S of the reduction dimension (S travels in a.kchunks)
+    const int S = SPLIT ? a.kchunks : 1;
+    const int blocks = SPLIT ? (int)gridDim.x / S : (int)gridDim.x;
+    const int rb = SPLIT ? (int)blockIdx.x % blocks : (int)blockIdx.x;
+    const int ks = SPLIT ? (int)blockIdx.x / blocks : 0;
+    const int r0 = rb * per_wg;
     if (r0 >= a.N) return;
     const int r1 = r0 + per_wg < a.N ? r0 + per_wg : a.N;
     const int nT = (r1 - r0 + OUT_PER_TILE - 1) / OUT_PER_TILE;
@@ -60,8 +74,8 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
     // this wave's k range: whole groups of 128 k, so that every range starts on a 256-byte boundary of
     // its rows (K >= 1024: every wave has at least one group)
     const int S4 = (K + 127) >> 7;
-    const int k_begin = ((wv * S4) >> 3) * 128;
-    const int k_stop = (((wv + 1) * S4) >> 3) * 128;
+    const int k_begin = SPLIT ? ((ks * 8 + wv) * S4 / (8 * S)) * 128 : ((wv * S4) >> 3) * 128;
+    const int k_stop = SPLIT ? ((ks * 8 + wv + 1) * S4 / (8 * S)) * 128 : (((wv + 1) * S4) >> 3) * 128;
     const int k_end = k_stop < K ? k_stop : K;
     const int nU = (k_end - k_begin + SK_KC - 1) / SK_KC;            // units of 256 k per pass
     const int total = P * nU * T;                                    // tile-steps of this wave
@@ -226,6 +240,15 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
         }
     };
 
+    // SPLIT: the block's sums over this workgroup's share of K go to its hand-over slot, [tile][token][row]
+    unsigned* const slot = a.handover + (size_t)blockIdx.x * SK_SLOT_WORDS;
+    auto hand_in = [&](int tile, int tt) __attribute__((always_inline)) {
+        const int r = tid & 15, m = tid >> 4;
+        if (m < a.M)
+            __hip_atomic_store(slot + (tile * 32 + m) * 16 + r, __builtin_bit_cast(unsigned, s_sum[tt][m][r]),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
+
     // One unit of 256 k for all T tiles of the pass.  Tile-steps alternate between the two register
     // buffers; PAR says which of them holds tile 0 of this unit (with an odd T it flips from unit to unit).
     auto run_unit = [&](auto par) __attribute__((always_inline)) {
@@ -319,7 +342,10 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
 #pragma unroll
             for (int tt = 0; tt < RT; ++tt) {
                 const int tile = this_pass * T + rr * RT + tt;
-                if (rr * RT + tt < T && tile < nT) finish_tile(tile, tt);
+                if (rr * RT + tt < T && tile < nT) {
+                    if constexpr (SPLIT) hand_in(tile, tt);
+                    else finish_tile(tile, tt);
+                }
             }
             // s_part is rewritten only after every thread has passed the second barrier above, s_sum only
             // after the next round's first barrier, which every thread reaches after these epilogues
@@ -336,21 +362,73 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
             run_unit(std::integral_constant<int, 1>{});
         }
     }
+
+    if constexpr (SPLIT) {
+        // The block's S workgroups have each handed in their sums (one pass: the host only splits K when
+        // the block's tiles are all in flight).  Whoever arrives last adds the S contributions in share
+        // order -- the same result whichever workgroup that is -- and writes the outputs.  Nobody waits:
+        // the stores are device-scope and acknowledged before the arrival is counted.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0) {
+            const unsigned before = __hip_atomic_fetch_add(a.counters + rb, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const unsigned last = before + 1u == (unsigned)S;
+            if (last) __hip_atomic_store(a.counters + rb, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // zero between calls
+            s_last = last;
+        }
+        __syncthreads();
+        if (s_last == 0u) return;
+        const int r = tid & 15, m = tid >> 4;
+        if (m >= a.M) return;
+        const unsigned* const first = a.handover + (size_t)rb * SK_SLOT_WORDS + m * 16 + r;      // share 0's slot
+        const size_t share_stride = (size_t)blocks * SK_SLOT_WORDS;
+        float v[T];
+#pragma unroll
+        for (int t = 0; t < T; ++t) v[t] = 0.f;
+        for (int s0 = 0; s0 < S; s0 += 4) {
+            // the loads of four shares x T tiles are in flight together; a share or tile that does not
+            // exist is read from one that does and not added
+            unsigned pv[4][T];
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+#pragma unroll
+                for (int t = 0; t < T; ++t)
+                    pv[b][t] = __hip_atomic_load(first + (size_t)(s0 + b < S ? s0 + b : S - 1) * share_stride + (t < nT ? t : 0) * 512,
+                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+#pragma unroll
+                for (int t = 0; t < T; ++t)
+                    if (s0 + b < S) v[t] += __builtin_bit_cast(float, pv[b][t]);
+        }
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const int n = r0 + t * 16 + r;
+            if (t < nT && n < r1) {
+                float o = v[t];
+                if (a.residual) o += half_bits_to_float(a.residual[(size_t)m * a.ldo + n]);
+                a.out[(size_t)m * a.ldo + n] = to_half_bits(o);
+            }
+        }
+    }
 }
 
 // 16-byte pieces of LDS per wave for its slice of gamma (same arithmetic as in the kernel)
 int gamma_pieces(int K) { return ((((K + 127) >> 7) >> 3) + 1) * 128 >> 3; }
 
 template <int T, int MT>
-hipError_t launch_t_mt(const SkinnyArgs& a, int epilogue, int per_wg, int grid, hipStream_t stream)
+hipError_t launch_t_mt(const SkinnyArgs& a, int epilogue, const RowBlockPlan& p, hipStream_t stream)
 {
-    dim3 g(grid), b(SK_THREADS);
+    dim3 g(p.grid), b(SK_THREADS);
+    const int per_wg = p.per_wg;
     const size_t gamma_lds = (size_t)SK_WAVES * gamma_pieces(a.K) * sizeof(uintx4);
     static bool attr_set = false;       // static (+ dynamic) LDS passes 64 KiB: every variant needs the opt-in
     if (!attr_set) {
         // largest static part: ~90 KiB (T = 3 or 5 with two token tiles); with this it stays inside the 160 KiB of a CU
         const int most = (int)((size_t)SK_WAVES * gamma_pieces(ROWSLAB_MAX_K) * sizeof(uintx4));
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_PLAIN>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, most);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_PLAIN, true>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, most);
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_SWIGLU>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, most);
@@ -361,6 +439,12 @@ hipError_t launch_t_mt(const SkinnyArgs& a, int epilogue, int per_wg, int grid, 
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_RMSNORM_SWIGLU>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, most);
         attr_set = true;
+    }
+    if (p.ksplit > 1) {      // plain kind only (checked by the caller); the share count travels in kchunks
+        SkinnyArgs s = a;
+        s.kchunks = p.ksplit;
+        hipLaunchKernelGGL((skinny_rowblock<T, MT, EPI_PLAIN, true>), g, b, 0, stream, s.x, s.w0, s.w1, s.gamma, s.M, s.N, s.K, per_wg, s);
+        return hipGetLastError();
     }
     switch (epilogue) {
     case EPI_PLAIN: hipLaunchKernelGGL((skinny_rowblock<T, MT, EPI_PLAIN>), g, b, 0, stream, a.x, a.w0, a.w1, a.gamma, a.M, a.N, a.K, per_wg, a); break;
@@ -373,22 +457,26 @@ hipError_t launch_t_mt(const SkinnyArgs& a, int epilogue, int per_wg, int grid, 
 }
 
 template <int T>
-hipError_t launch_t(const SkinnyArgs& a, int epilogue, int per_wg, int grid, hipStream_t stream)
+hipError_t launch_t(const SkinnyArgs& a, int epilogue, const RowBlockPlan& p, hipStream_t stream)
 {
-    if (a.M <= 16) return launch_t_mt<T, 1>(a, epilogue, per_wg, grid, stream);
-    return launch_t_mt<T, 2>(a, epilogue, per_wg, grid, stream);
+    if (a.M <= 16) return launch_t_mt<T, 1>(a, epilogue, p, stream);
+    return launch_t_mt<T, 2>(a, epilogue, p, stream);
 }
 
 }  // namespace
 
-RowBlockPlan plan_rowblock(int N, int epilogue, int num_cus)
+RowBlockPlan plan_rowblock(int N, int epilogue, int num_cus, int ksplit)
 {
     RowBlockPlan p;
     const int out_per_tile = is_swiglu(epilogue) ? 8 : 16;
-    int per_wg = (N + num_cus - 1) / num_cus;
+    if (ksplit < 1) ksplit = 1;
+    int groups = num_cus / ksplit;          // row blocks: ksplit workgroups each
+    if (groups < 1) groups = 1;
+    int per_wg = (N + groups - 1) / groups;
     if (!is_swiglu(epilogue)) per_wg = (per_wg + 1) & ~1;      // rotary pairs (n, n + 1) stay in one block
     p.per_wg = per_wg;
-    p.grid = (N + per_wg - 1) / per_wg;
+    p.ksplit = ksplit;
+    p.grid = ((N + per_wg - 1) / per_wg) * ksplit;
     p.tiles = (per_wg + out_per_tile - 1) / out_per_tile;
     p.passes = (p.tiles + 5) / 6;
     const int per_pass = (p.tiles + p.passes - 1) / p.passes;
@@ -396,16 +484,27 @@ RowBlockPlan plan_rowblock(int N, int epilogue, int num_cus)
     return p;
 }
 
-hipError_t launch_rowblock(const SkinnyArgs& a, int epilogue, int num_cus, hipStream_t stream)
+bool rowblock_split_ok(int N, int K, int epilogue, int num_cus, int ksplit)
+{
+    if (ksplit < 2 || ksplit > ROWBLOCK_MAX_SPLIT || epilogue != EPI_PLAIN) return false;
+    if (((K + 127) >> 7) < 8 * ksplit) return false;           // every wave of every share gets k of its own
+    const RowBlockPlan p = plan_rowblock(N, epilogue, num_cus, ksplit);
+    // one pass (the hand-over happens once, at the end), one workgroup per compute unit at most, and a
+    // slot / a counter per workgroup / block within the workspace
+    return p.passes == 1 && p.grid <= num_cus && p.grid <= SK_MAX_GRID && p.T * 512 <= SK_SLOT_WORDS;
+}
+
+hipError_t launch_rowblock(const SkinnyArgs& a, int epilogue, int num_cus, hipStream_t stream, int ksplit)
 {
     if (a.K < 1024 || a.K > ROWSLAB_MAX_K || a.N < 1) return hipErrorInvalidValue;
-    const RowBlockPlan p = plan_rowblock(a.N, epilogue, num_cus);
+    if (ksplit > 1 && !rowblock_split_ok(a.N, a.K, epilogue, num_cus, ksplit)) return hipErrorInvalidValue;
+    const RowBlockPlan p = plan_rowblock(a.N, epilogue, num_cus, ksplit);
     switch (p.T) {
-    case 2: return launch_t<2>(a, epilogue, p.per_wg, p.grid, stream);
-    case 3: return launch_t<3>(a, epilogue, p.per_wg, p.grid, stream);
-    case 4: return launch_t<4>(a, epilogue, p.per_wg, p.grid, stream);
-    case 5: return launch_t<5>(a, epilogue, p.per_wg, p.grid, stream);
-    default: return launch_t<6>(a, epilogue, p.per_wg, p.grid, stream);
+    case 2: return launch_t<2>(a, epilogue, p, stream);
+    case 3: return launch_t<3>(a, epilogue, p, stream);
+    case 4: return launch_t<4>(a, epilogue, p, stream);
+    case 5: return launch_t<5>(a, epilogue, p, stream);
+    default: return launch_t<6>(a, epilogue, p, stream);
     }
 }
 

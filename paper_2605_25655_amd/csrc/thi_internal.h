@@ -78,16 +78,22 @@ hipError_t launch_skinny(const SkinnyArgs& a, int epilogue, int num_cus, hipStre
 constexpr int ROWSLAB_MAX_K = 32768;
 hipError_t launch_rowslab(const SkinnyArgs& a, int epilogue, int num_cus, hipStream_t stream);
 // Row-block decode kernel: the outputs dealt to the workgroups in equal contiguous blocks, T slabs of a
-// block in flight at a time (same limits on K; a.tiles is not used; uses no workspace).
+// block in flight at a time (same limits on K; a.tiles is not used; no workspace unless ksplit > 1).
 struct RowBlockPlan {
     int per_wg;      // outputs (rows of W, gate/up pairs for SwiGLU) per workgroup
     int grid;        // workgroups
     int tiles;       // 16-row tiles per block
     int passes;      // passes over K
-    int T;           // tiles in flight per pass (2, 4 or 6)
+    int T;           // tiles in flight per pass (2..6)
+    int ksplit;      // workgroups that share a block, each with 1/ksplit of K (1: nothing is handed over)
 };
-RowBlockPlan plan_rowblock(int N, int epilogue, int num_cus);
-hipError_t launch_rowblock(const SkinnyArgs& a, int epilogue, int num_cus, hipStream_t stream);
+// ksplit > 1 (plain kind, one pass): blocks of ksplit x as many rows, so that a wave's slice of x serves
+// ksplit x as many tiles; the block's workgroups hand their sums in through the stream-K kernel's
+// hand-over slots (a.handover, a.counters) and the last to arrive adds them in share order.
+constexpr int ROWBLOCK_MAX_SPLIT = 6;
+RowBlockPlan plan_rowblock(int N, int epilogue, int num_cus, int ksplit = 1);
+bool rowblock_split_ok(int N, int K, int epilogue, int num_cus, int ksplit);
+hipError_t launch_rowblock(const SkinnyArgs& a, int epilogue, int num_cus, hipStream_t stream, int ksplit = 1);
 
 // ---- GEMM (prefill) kernel ---------------------------------------------------
 struct GemmArgs {

@@ -372,6 +372,57 @@ def test_rowblock_kernel_all_epilogues(thi, oracle_mod, M, N, K, I):
     assert (err <= bound).all(), f"gate/up worst excess {(err - bound).max()}"
 
 
+# row blocks whose reduction dimension is shared by `split` workgroups: blocks of split x as many rows, the
+# sums handed in through the workspace and added in share order by the workgroup that arrives last
+ROWBLOCK_SPLIT = [
+    # M, N, K, split
+    (32, 4096, 11008, 2),        # the 7B down projection: 86 groups of 128 k over 16 / 24 / 32 waves
+    (32, 4096, 11008, 3),
+    (17, 4096, 11008, 4),
+    (1, 6656, 2048, 2),          # one group of 128 k per wave
+    (5, 5120, 5160, 3),          # ragged K, 20 -> 60 rows per block
+    (16, 1000, 4104, 4),         # few rows: 16 per block even when shared, one tile of two in flight
+    (32, 8190, 8192, 2),         # 64 rows per block, the last block two short
+    (9, 3000, 1024, 2),          # not admissible (K < 1024 * split): runs unshared
+]
+
+
+@pytest.mark.parametrize("M,N,K,split", ROWBLOCK_SPLIT)
+def test_rowblock_shared_reduction(thi, oracle_mod, M, N, K, split):
+    say(f"[case] row blocks, K shared by {split} workgroups M={M} N={N} K={K}")
+    x, w, g = synth.random_problem(5100 + M * 3 + N + K + split, M, N, K)
+    rng = np.random.Generator(np.random.Philox(key=5200 + M + N + K))
+    res = f16(rng.standard_normal((M, N)))
+    cols = np.unique(np.concatenate([synth.sample_rows(9, N, 600), np.arange(N - 70, N), np.arange(0, 70)]))
+    r = Runner(M, K, K, N)
+    xd, wd = to_dev(x), to_dev(w)
+    prev = thi.thi_set_kernel_family(4)
+    prev_split = thi.thi_set_rowblock_split(split)
+    try:
+        a = to_host(r.linear(xd, wd))
+        ar = to_host(r.linear_residual(xd, wd, to_dev(res)))
+        thi.thi_set_kernel_family(1)          # the stream-K kernel uses the same flags and slots: left clean?
+        sk = to_host(r.linear(xd, wd))
+        thi.thi_set_kernel_family(4)
+        a2 = to_host(r.linear(xd, wd))
+        thi.thi_set_rowblock_split(1)
+        a1 = to_host(r.linear(xd, wd))
+    finally:
+        thi.thi_set_rowblock_split(prev_split)
+        thi.thi_set_kernel_family(prev)
+    assert np.array_equal(a.view(np.uint16), a2.view(np.uint16))          # whoever arrives last: same sums
+    ws = np.ascontiguousarray(w[cols])
+    y, s = oracle_mod.linear(x, ws)
+    check(a[:, cols], y, s, "linear", argmax=False)
+    check(sk[:, cols], y, s, "linear (stream-K after)", argmax=False)
+    check(a1[:, cols], y, s, "linear (unshared)", argmax=False)
+    y, s = oracle_mod.linear_residual(x, ws, np.ascontiguousarray(res[:, cols]))
+    check(ar[:, cols], y, s, "linear_residual", argmax=False)
+    # all outputs, not only the sampled ones: shared and unshared differ by summation order only
+    d = np.abs(a.astype(np.float64) - a1.astype(np.float64))
+    assert (d <= 2e-3 * np.abs(a1.astype(np.float64)) + 2e-3 * np.sqrt((a1.astype(np.float64) ** 2).mean())).all()
+
+
 @pytest.mark.parametrize("M,N", [(17, 20800), (17, 17920), (9, 17920), (9, 20800)])
 def test_rowblock_largest_lds_footprint(thi, oracle_mod, M, N):
     """K = 32768 with RMSNorm (a wave's slice of gamma: 8 KiB of LDS), five or six tiles in flight, one or
