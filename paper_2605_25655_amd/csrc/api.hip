@@ -103,10 +103,10 @@ bool use_skinny(int M)
 //                0.5 us per further pass over K, 4 us more with one or two tiles per workgroup and
 //                8192 <= K < 16384 (measured on the 70B O and 13B down projections); the activation
 //                traffic is shared by the tiles of a pass (+5 % / +15 % / +40 % at M <= 8 / 16 / 32,
-//                divided by the tiles per pass); a ragged last unit costs about a third of what it
+//                divided by the tiles per pass); a ragged last unit costs about a fifth of what it
 //                costs the slabs; slowed by the rows the last workgroup lacks.  With S workgroups per
 //                block (plain kind): S x the tiles share a load of x, the eight waves of S workgroups
-//                divide K, and the hand-over at the end costs ~1.8 us.
+//                divide K, and the hand-over at the end costs ~2 us.
 // Row blocks, modelled time in microseconds with `split` workgroups per block (constants: see below)
 double rowblock_time(int M, int N, int K, int epilogue, int cus, int split)
 {
@@ -121,7 +121,7 @@ double rowblock_time(int M, int N, int K, int epilogue, int cus, int split)
     const double x_extra = (M <= 4 ? 0.0 : M <= 8 ? 0.05 : M <= 16 ? 0.15 : 0.40) / per_pass;
     const double lacking = (double)bp.per_wg * (cus / split) / (double)N;
     return 3.8 + 0.5 * (bp.passes - 1) + ((split == 1 && bp.tiles <= 2 && K >= 8192 && K < 16384) ? 4.0 : 0.0) +
-           (split > 1 ? 1.8 : 0.0) + t_w * (1.0 + x_extra) * (1.0 + 0.3 * (ragged - 1.0)) * lacking;
+           (split > 1 ? 2.0 : 0.0) + t_w * (1.0 + x_extra) * (1.0 + 0.2 * (ragged - 1.0)) * lacking;
 }
 
 // Row blocks: how many workgroups share a block (1 = none)?  The smallest modelled time; sharing must

@@ -168,6 +168,8 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
         }
 #pragma unroll
         for (int ph = 0; ph < 2; ++ph) {
+            // the second half of a unit that ends after 128 k holds nothing: skipped (wave-uniform)
+            if (ph == 1 && k0 + 128 >= k_end) break;
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) wt[wv][(4 * jj + ld_i) * WT_STRIDE + ld_p] = cur[ph * 4 + jj];
