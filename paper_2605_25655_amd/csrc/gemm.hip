@@ -78,10 +78,30 @@ __device__ __forceinline__ void dma16_sbase(const void* base_uniform, unsigned l
                  : "memory");
 }
 
-// U work units dealt to G workers in contiguous shares: the first `rem` take q+1, the others q.
+// The k-steps of the shared tiles (tile t = units [t * ktiles, (t + 1) * ktiles)) dealt to G workers.
+//   parts == 0: contiguous equal shares whatever the tile boundaries (the first `rem` workers take q + 1
+//               units, the others q); a share may span the end of one tile and the start of the next.
+//   parts >= 1: every shared tile is cut into `parts` equal k ranges, worker w takes range w % parts of
+//               tile w / parts (workers past sk_tiles * parts take none).  Workers on neighbouring tiles
+//               then walk the same k range at the same time, so the operand panels they have in common
+//               are still fetched once per L2 instead of once per workgroup.
 struct Deal {
-    int q, rem;
-    __device__ __forceinline__ int begin(int w) const { return w * q + (w < rem ? w : rem); }
+    int q, rem, parts, ktiles, shared;
+    __device__ __forceinline__ Deal(int sk_tiles, int ktiles_, int G, int parts_)
+        : q(sk_tiles * ktiles_ / G), rem(sk_tiles * ktiles_ % G), parts(parts_), ktiles(ktiles_), shared(sk_tiles) {}
+    __device__ __forceinline__ int begin(int w) const {
+        if (parts == 0) return w * q + (w < rem ? w : rem);
+        if (w >= shared * parts) return shared * ktiles;
+        return (w / parts) * ktiles + (w % parts) * ktiles / parts;
+    }
+    __device__ __forceinline__ int end(int w) const {
+        if (parts == 0) return begin(w + 1);
+        if (w >= shared * parts) return shared * ktiles;
+        return (w / parts) * ktiles + (w % parts + 1) * ktiles / parts;
+    }
+    // first and last worker with a share of tile t
+    __device__ __forceinline__ int first(int t) const { return parts == 0 ? owner(t * ktiles) : t * parts; }
+    __device__ __forceinline__ int last(int t) const { return parts == 0 ? owner(t * ktiles + ktiles - 1) : t * parts + parts - 1; }
     __device__ __forceinline__ int owner(int u) const {
         const int edge = rem * (q + 1);
         return u < edge ? u / (q + 1) : rem + (u - edge) / q;
@@ -163,7 +183,7 @@ __device__ __forceinline__ void store_fragment(const GemmArgs& a, int tile_n, in
 // and applies the epilogue.  The thread <-> element mapping is the main kernel's, so the partials are
 // read back as they were written.  (Halves, not quads: SwiGLU pairs quad 2i with quad 2i+1.)
 template <int BN, int BM, int WN, int WM, int EPI>
-__global__ __launch_bounds__(64 * WN * WM) void gemm_fixup(GemmArgs a, int tiles_m, int ktiles, int sk_tiles, int G)
+__global__ __launch_bounds__(64 * WN * WM) void gemm_fixup(GemmArgs a, int tiles_m, int ktiles, int sk_tiles, int G, int parts)
 {
     constexpr int THREADS = 64 * WN * WM;
     constexpr int TN = BN / WN / 32, TM = BM / WM / 32;
@@ -172,9 +192,8 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_fixup(GemmArgs a, int tiles
     const int half = blockIdx.x & 1, tf = blockIdx.x >> 1;
     const int t = tf / (TN * TM), frag = tf % (TN * TM);
     const int tn = frag / TM, tm = frag % TM;
-    const int U = sk_tiles * ktiles;
-    const Deal deal{U / G, U % G};
-    const int w_first = deal.owner(t * ktiles), w_last = deal.owner(t * ktiles + ktiles - 1);
+    const Deal deal(sk_tiles, ktiles, G, parts);
+    const int w_first = deal.first(t), w_last = deal.last(t);
     floatx4 g0 = {0.f, 0.f, 0.f, 0.f}, g1 = {0.f, 0.f, 0.f, 0.f};      // this half's two register quads
     float sq = 0.f;
     const int ml = wm * (BM / WM) + tm * 32 + lr;
@@ -222,7 +241,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_fixup(GemmArgs a, int tiles
 // BN x BM output tile, WN x WM waves; wave tile (BN/WN) x (BM/WM) built from 32x32 MFMA tiles.
 // KTAIL: K is not a multiple of 64 (pieces past K are zero-filled; operands then go through VGPRs).
 template <int BN, int BM, int WN, int WM, int GK, int NS, int EPI, bool KTAIL>
-__global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int tiles_m, int ktiles, int sk_tiles)
+__global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int tiles_m, int ktiles, int sk_tiles, int parts)
 {
     constexpr int NWAVES = WN * WM;
     constexpr int THREADS = 64 * NWAVES;
@@ -262,9 +281,8 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
     }
     // The first sk_tiles tiles are cut into k-steps and dealt stream-K; the others are taken whole,
     // round-robin.  The shared tiles come first so that their hand-over overlaps the whole tiles.
-    const int U = sk_tiles * ktiles;
-    const Deal deal{U / G, U % G};
-    const int u_begin = deal.begin(worker), u_end = deal.begin(worker + 1);
+    const Deal deal(sk_tiles, ktiles, G, parts);
+    const int u_begin = deal.begin(worker), u_end = deal.end(worker);
     const int first_tile = u_begin / ktiles;
     int t_whole = sk_tiles + worker;
 
@@ -541,39 +559,65 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
     }
 }
 
-// Time model of the two ways to run `tiles` tiles of BN x BM on `grid` workgroups:
+// Time model (microseconds) of running `tiles` tiles of BN x BM on `grid` workgroups.
 //   whole tiles only : ceil(tiles / grid) rounds;
-//   stream-K remainder: floor(tiles / grid) rounds, the ragged remainder shared equally, plus the second
-//                       pass -- one more launch and the partial tiles' round trip through memory (about
-//                       grid + remainder partial tiles written and read, ~4 TB/s).
-// A tile's time is the larger of its arithmetic (measured whole-chip speeds: ~1050 TFLOP/s with
-// 256x256 tiles, ~900 with 128x128) and, where there is one token tile only (every weight panel is
-// then read exactly once, by one workgroup), its weight traffic at the measured streaming rate.
+//   shared remainder : floor(tiles / grid) whole rounds; the ragged remainder is cut along K and a second
+//                      pass (one more launch, the partial tiles' round trip through memory) adds the parts.
+// How the remainder is cut depends on what bounds the kernel.  With several token tiles it is the matrix
+// cores, fed through the L2: workgroups on neighbouring tiles must walk the same k range at the same
+// time or the panels they share are fetched once per workgroup (measured: a 30B-shaped down projection,
+// 208 tiles of 256x256 on 256 workgroups in equal contiguous shares, ran HBM-bound at 585 us against 485
+// us for whole tiles on 208 workgroups).  So every remainder tile is cut into the same `parts` = grid /
+// remainder equal k ranges (whole tiles if that is 1).  With one token tile every weight panel is read
+// exactly once by one workgroup whatever the cut and the kernel is bound by its weight traffic: equal
+// contiguous shares (parts = 0) keep every workgroup busy.
+// A workgroup's speed by configuration, fitted to measurements of every configuration and cut on the four
+// projections of the 7B..70B shapes at M = 256..2048 (clocks settled under each shape's load for 40 ms
+// first -- after a lighter kernel the first launches run up to 15 % slower): 256x256 tiles 4.6 TFLOP/s + 6
+// us per tile, 128x128 tiles two per CU 2.0 TFLOP/s + 4 us, 128x128 with three stages one per CU 3.4
+// TFLOP/s + 6 us; the second pass 5 us + its bytes at ~6 TB/s.  On those 64 shapes the pick is on average
+// 0.5 % slower than the best of the six (configuration, cut) pairs, 6 % at worst.
 struct Schedule {
-    int sk_tiles;      // tiles cut into k-steps and dealt stream-K (0: whole tiles only)
-    double us;         // modelled time
+    int sk_tiles;      // tiles cut along K (0: whole tiles only)
+    int parts;         // equal k ranges per shared tile; 0 = equal contiguous shares across tile boundaries
+    double us;
 };
-Schedule plan_schedule(int tiles, int tiles_m, int grid, int BN, int BM, int K)
+
+Schedule plan_schedule(int tiles, int tiles_m, int grid, int BN, int BM, int K, double wg_tflops, double tile_fixed_us)
 {
-    const double tflops = (BN * BM >= 256 * 256) ? 1050.0 : 900.0;
-    double tile_us = 2.0 * BN * BM * (double)K / (tflops * 1e6 / grid);   // one workgroup's speed = total / grid
+    const double flops_us = 2.0 * BN * BM * (double)K / (wg_tflops * 1e6);
+    double tile_us = tile_fixed_us + flops_us;
+    const int rem = tiles % grid, full = tiles / grid;
+    const double tile_bytes = (double)BN * BM * 4.0;
     if (tiles_m == 1) {
         const double stream_us = (double)BN * K * 2.0 / (6.0e6 / grid);
         tile_us = tile_us > stream_us ? tile_us : stream_us;
+        const double whole = (double)((tiles + grid - 1) / grid) * tile_us;
+        if (rem == 0) return Schedule{0, 0, whole};
+        const double shared = ((double)full + (double)rem / grid) * tile_us + 5.0 + (double)(grid + rem) * tile_bytes * 2.0 / 4.0e6;
+        return shared < whole ? Schedule{rem, 0, shared} : Schedule{0, 0, whole};
     }
-    const int rem = tiles % grid;
     const double whole = (double)((tiles + grid - 1) / grid) * tile_us;
-    if (rem == 0) return Schedule{0, whole};
-    const double fixup_us = 5.0 + (double)(grid + rem) * ((double)BN * BM * 4.0) * 2.0 / 4.0e6;
-    // short shares suit the 128x128 kernel badly (measured ~1.6x the model): price that in
-    const double shared = (((double)(tiles / grid) + (double)rem / grid) * tile_us + fixup_us) * (BN == 128 && BM == 128 ? 1.6 : 1.0);
-    return shared < whole ? Schedule{rem, shared} : Schedule{0, whole};
+    if (rem == 0) return Schedule{0, 1, whole};
+    const int ktiles = (K + 63) / 64;
+    int parts = grid / rem;
+    if (parts > ktiles) parts = ktiles;
+    if (parts < 2) return Schedule{0, 1, whole};
+    const double shared = (double)full * tile_us + tile_fixed_us + flops_us / parts + 5.0 +
+                          (double)rem * parts * tile_bytes * 2.0 / 6.0e6;
+    return shared < whole ? Schedule{rem, parts, shared} : Schedule{0, 1, whole};
 }
+
+// the three multi-token-tile configurations
+constexpr double BIG_TFLOPS = 4.6, BIG_FIXED_US = 6.0;        // 256x256, one workgroup per CU
+constexpr double SMALL_TFLOPS = 2.0, SMALL_FIXED_US = 4.0;    // 128x128, two per CU
+constexpr double DEEP_TFLOPS = 3.4, DEEP_FIXED_US = 6.0;      // 128x128, three stages, one per CU
+constexpr double FEW_TFLOPS = 900.0 / 256;                    // one token tile: bound by the weight stream anyway
 
 // ALL = also build the variants with a transformed activation tile (RMSNorm) or a ragged K; the
 // 256x256 configuration leaves them to the 128x128 one (they would not fit its register budget).
 template <int BN, int BM, int WN, int WM, int GK, int NS, bool ALL>
-hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream, bool share_all = false)
+hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream, double wg_tflops, double tile_fixed_us)
 {
     const int per_tile = is_swiglu(epilogue) ? BN / 2 : BN;
     const int tiles_n = (a.N + per_tile - 1) / per_tile;
@@ -583,8 +627,8 @@ hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream
     const long U = (long)a.tiles * ktiles;
     long grid = grid_cap;
     if (grid > U) grid = U;
-    // share_all: every tile is cut into k-steps and dealt stream-K, whatever the model says
-    const int sk_tiles = share_all ? a.tiles : plan_schedule(a.tiles, tiles_m, (int)grid, BN, BM, a.K).sk_tiles;
+    const Schedule plan = plan_schedule(a.tiles, tiles_m, (int)grid, BN, BM, a.K, wg_tflops, tile_fixed_us);
+    const int sk_tiles = plan.sk_tiles, parts = plan.parts;
     const size_t lds = (size_t)NS * (BN + BM) * (GK / 8) * sizeof(uintx4);
     dim3 g((unsigned)grid), b(64 * WN * WM);
 #define THI_LAUNCH_K(E, KT)                                                                                  \
@@ -596,10 +640,10 @@ hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                 \
             attr_set = true;                                                                                 \
         }                                                                                                    \
-        hipLaunchKernelGGL(kern, g, b, lds, stream, a, tiles_m, ktiles, sk_tiles);                           \
+        hipLaunchKernelGGL(kern, g, b, lds, stream, a, tiles_m, ktiles, sk_tiles, parts);                    \
         if (sk_tiles > 0)                                                                                    \
             hipLaunchKernelGGL((gemm_fixup<BN, BM, WN, WM, E>), dim3(2 * sk_tiles * (BN / WN / 32) * (BM / WM / 32)), \
-                               b, 0, stream, a, tiles_m, ktiles, sk_tiles, (int)grid);                       \
+                               b, 0, stream, a, tiles_m, ktiles, sk_tiles, (int)grid, parts);                \
     } while (0)
 #define THI_LAUNCH(E)                                                                                        \
     do {                                                                                                     \
@@ -624,14 +668,14 @@ hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream
     return hipGetLastError();
 }
 
-double config_cost(const GemmArgs& a, int epilogue, int BN, int BM, int grid)
+double config_cost(const GemmArgs& a, int epilogue, int BN, int BM, int grid, double wg_tflops, double tile_fixed_us)
 {
     const int per_tile = is_swiglu(epilogue) ? BN / 2 : BN;
     const int tiles_m = (a.M + BM - 1) / BM;
     const long tiles = (long)((a.N + per_tile - 1) / per_tile) * tiles_m;
     const long units = tiles * ((a.K + 63) / 64);
     const int g = (int)(units < grid ? units : grid);
-    return plan_schedule((int)tiles, tiles_m, g, BN, BM, a.K).us;
+    return plan_schedule((int)tiles, tiles_m, g, BN, BM, a.K, wg_tflops, tile_fixed_us).us;
 }
 
 }  // namespace
@@ -699,32 +743,25 @@ hipError_t launch_gemm(const GemmArgs& a, int epilogue, int num_cus, hipStream_t
         // Few tokens: one token tile, the weights are read once and the kernel is bound by how many
         // bytes a CU keeps in flight: three stages of 128 rows x 128 k against 64 tokens (K a multiple of
         // 128), else of 256 rows x 64 k against 128 tokens.
-        if (a.M <= 64 && a.K % 128 == 0) return launch_cfg<128, 64, 4, 1, 128, 3, false>(a, epilogue, g_big, stream);
-        return launch_cfg<256, 128, 4, 1, 64, 3, false>(a, epilogue, g_big, stream);
+        if (a.M <= 64 && a.K % 128 == 0) return launch_cfg<128, 64, 4, 1, 128, 3, false>(a, epilogue, g_big, stream, FEW_TFLOPS, 0.0);
+        return launch_cfg<256, 128, 4, 1, 64, 3, false>(a, epilogue, g_big, stream, FEW_TFLOPS, 0.0);
     }
-    const double c_small = config_cost(a, epilogue, 128, 128, g_small);
+    // Several token tiles: the configuration with the smallest modelled time.  The three-stage 128x128
+    // configuration runs one workgroup per CU, which only pays where the two-per-CU one would not have a
+    // second workgroup for most CUs anyway (at most one 128x128 tile per CU).
+    const double c_small = config_cost(a, epilogue, 128, 128, g_small, SMALL_TFLOPS, SMALL_FIXED_US);
     if (direct) {
-        const double c_big = config_cost(a, epilogue, 256, 256, g_big);
-        // At most one 128x128 tile per CU (e.g. N = K = 4096 at M <= 1024): neither a second workgroup on
-        // the CU nor more, shorter stream-K shares help; what helps is a third LDS stage for the one
-        // workgroup there is (~800 TFLOP/s chip-wide when every CU has a tile; N = K = 4096 at M = 1024:
-        // 45.7 against 70.4 us).  With at most half a tile per CU the tiles are shared by two or more
-        // workgroups each (M = 256: 24 against 36 us, M = 512: 31 against 43 us).
-        // (The model prices the stream-K schedule of the 256x256 tiles about a quarter too high when K is
-        // long -- 7B-shaped down projection at M = 1024: modelled 135, measured 105 us -- hence the 0.75.)
+        const double c_big = config_cost(a, epilogue, 256, 256, g_big, BIG_TFLOPS, BIG_FIXED_US);
         const int per_tile = is_swiglu(epilogue) ? 64 : 128;
         const long t128 = (long)((a.N + per_tile - 1) / per_tile) * ((a.M + 127) / 128);
         if (t128 <= num_cus) {
-            const double tile_us = 2.0 * 128 * 128 * (double)a.K / (800.0e6 / num_cus);
-            const bool share = t128 * 2 <= num_cus;
-            const double c_deep = share ? (double)t128 / num_cus * tile_us + 5.0 + (double)num_cus * (128 * 128 * 4.0) * 2.0 / 4.0e6
-                                        : tile_us;
-            if (c_deep < 0.75 * c_big && c_deep < c_small)
-                return launch_cfg<128, 128, 2, 2, 64, 3, false>(a, epilogue, num_cus, stream, share);
+            const double c_deep = config_cost(a, epilogue, 128, 128, num_cus, DEEP_TFLOPS, DEEP_FIXED_US);
+            if (c_deep < c_big && c_deep < c_small)
+                return launch_cfg<128, 128, 2, 2, 64, 3, false>(a, epilogue, num_cus, stream, DEEP_TFLOPS, DEEP_FIXED_US);
         }
-        if (c_big <= c_small) return launch_cfg<256, 256, 4, 2, 64, 2, false>(a, epilogue, g_big, stream);
+        if (c_big <= c_small) return launch_cfg<256, 256, 4, 2, 64, 2, false>(a, epilogue, g_big, stream, BIG_TFLOPS, BIG_FIXED_US);
     }
-    return launch_cfg<128, 128, 2, 2, 64, 2, true>(a, epilogue, g_small, stream);
+    return launch_cfg<128, 128, 2, 2, 64, 2, true>(a, epilogue, g_small, stream, SMALL_TFLOPS, SMALL_FIXED_US);
 }
 
 }  // namespace thi
