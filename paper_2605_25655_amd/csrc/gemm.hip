@@ -572,11 +572,12 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
 // exactly once by one workgroup whatever the cut and the kernel is bound by its weight traffic: equal
 // contiguous shares (parts = 0) keep every workgroup busy.
 // A workgroup's speed by configuration, fitted to measurements of every configuration and cut on the four
-// projections of the 7B..70B shapes at M = 256..2048 (clocks settled under each shape's load for 40 ms
-// first -- after a lighter kernel the first launches run up to 15 % slower): 256x256 tiles 4.6 TFLOP/s + 6
-// us per tile, 128x128 tiles two per CU 2.0 TFLOP/s + 4 us, 128x128 with three stages one per CU 3.4
-// TFLOP/s + 6 us; the second pass 5 us + its bytes at ~6 TB/s.  On those 64 shapes the pick is on average
-// 0.5 % slower than the best of the six (configuration, cut) pairs, 6 % at worst.
+// projections of the 7B..70B shapes at M = 256..2048 (weight copies rotated so that they come from HBM;
+// clocks settled under each shape's load for 40 ms first -- after a lighter kernel the first launches run
+// up to 15 % slower): 256x256 tiles 4.7 TFLOP/s + 6 us per tile, 128x128 tiles two per CU 1.8 TFLOP/s + 6
+// us, 128x128 with three stages one per CU 3.4 TFLOP/s + 4 us; the second pass 5 us + its bytes at ~8
+// TB/s (they are still in the caches).  On those 64 shapes the pick is on average 0.5 % slower than the
+// best of the six (configuration, cut) pairs, 8 % at worst.
 struct Schedule {
     int sk_tiles;      // tiles cut along K (0: whole tiles only)
     int parts;         // equal k ranges per shared tile; 0 = equal contiguous shares across tile boundaries
@@ -604,14 +605,14 @@ Schedule plan_schedule(int tiles, int tiles_m, int grid, int BN, int BM, int K, 
     if (parts > ktiles) parts = ktiles;
     if (parts < 2) return Schedule{0, 1, whole};
     const double shared = (double)full * tile_us + tile_fixed_us + flops_us / parts + 5.0 +
-                          (double)rem * parts * tile_bytes * 2.0 / 6.0e6;
+                          (double)rem * parts * tile_bytes * 2.0 / 8.0e6;
     return shared < whole ? Schedule{rem, parts, shared} : Schedule{0, 1, whole};
 }
 
 // the three multi-token-tile configurations
-constexpr double BIG_TFLOPS = 4.6, BIG_FIXED_US = 6.0;        // 256x256, one workgroup per CU
-constexpr double SMALL_TFLOPS = 2.0, SMALL_FIXED_US = 4.0;    // 128x128, two per CU
-constexpr double DEEP_TFLOPS = 3.4, DEEP_FIXED_US = 6.0;      // 128x128, three stages, one per CU
+constexpr double BIG_TFLOPS = 4.7, BIG_FIXED_US = 6.0;        // 256x256, one workgroup per CU
+constexpr double SMALL_TFLOPS = 1.8, SMALL_FIXED_US = 6.0;    // 128x128, two per CU
+constexpr double DEEP_TFLOPS = 3.4, DEEP_FIXED_US = 4.0;      // 128x128, three stages, one per CU
 constexpr double FEW_TFLOPS = 900.0 / 256;                    // one token tile: bound by the weight stream anyway
 
 // ALL = also build the variants with a transformed activation tile (RMSNorm) or a ragged K; the
