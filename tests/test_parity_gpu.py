@@ -170,6 +170,10 @@ SCHED = [
     (300, 1000, 1096, "ragged M, N, K"),
     (2048, 2560 + 256, 1024, "256-tile configuration with remainder"),
     (1024, 8192, 512, "256-tile configuration, whole rounds"),
+    # remainder tiles cut into equal k ranges (the cut is chosen by a time model; the shapes below are priced so)
+    (2048, 8192 + 256, 1088, "256-tile: one whole round + 8 tiles in 17 ranges each (as many as k-tiles)"),
+    (2048, 2560, 4160, "256-tile: 80 tiles in 3 ranges each, 65 k-tiles (uneven ranges)"),
+    (1024, 10240, 8256, "128-tile: one whole round + 128 tiles in 4 ranges each, 129 k-tiles"),
 ]
 
 
