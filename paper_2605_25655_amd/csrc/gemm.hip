@@ -17,13 +17,14 @@
 // store -- and, for SwiGLU, with g and u of the same (token, j) in registers of
 // the same lane (a tile interleaves 8 gate rows with the 8 matching up rows).
 //
-// Scheduling is stream-K: the (tile, k-step) units are dealt in equal contiguous
-// shares to a fixed number of workgroups (one or two per CU), so no CU idles on
-// a ragged last round of tiles and small problems still fill the chip.  Tiles
-// whose k range is shared leave fp32 partial tiles in the workspace; a second,
-// chip-wide kernel adds them in workgroup order (bitwise reproducible) and
-// applies the epilogue.  Only the ragged remainder is cut this way; tiles that
-// fill whole rounds of the grid are computed and finished in one piece.
+// Scheduling: a fixed number of workgroups (one or two per CU).  Tiles that fill whole rounds of the
+// grid are computed and finished in one piece; the ragged remainder (everything, when there are fewer
+// tiles than workgroups) may be cut along K so that no CU idles -- into equal k ranges per tile, the
+// same for every tile, when there are several token tiles (workgroups on neighbouring tiles then walk
+// the same k range together and keep sharing operand panels through the L2), into equal contiguous
+// stream-K shares when there is one token tile (every weight panel is read once anyway).  Tiles that
+// were cut leave fp32 partial tiles in the workspace; a second, chip-wide kernel adds them in workgroup
+// order (bitwise reproducible) and applies the epilogue.
 //
 // Workgroups are numbered so that the eight XCDs (one L2 each; hardware deals
 // consecutive workgroup ids round-robin to them) each walk a contiguous range
@@ -178,7 +179,7 @@ __device__ __forceinline__ void store_fragment(const GemmArgs& a, int tile_n, in
     }
 }
 
-// Second pass of the stream-K schedule: one workgroup per (shared tile, accumulator fragment, half of the
+// Second pass for tiles that were cut along K: one workgroup per (shared tile, accumulator fragment, half of the
 // fragment's register quads) adds the partial fragments of the tile's contributors in workgroup order
 // and applies the epilogue.  The thread <-> element mapping is the main kernel's, so the partials are
 // read back as they were written.  (Halves, not quads: SwiGLU pairs quad 2i with quad 2i+1.)
@@ -279,8 +280,8 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
         const int bid = blockIdx.x, per = G / 8, rem = G % 8, xcd = bid % 8, local = bid / 8;
         worker = xcd * per + (xcd < rem ? xcd : rem) + local;
     }
-    // The first sk_tiles tiles are cut into k-steps and dealt stream-K; the others are taken whole,
-    // round-robin.  The shared tiles come first so that their hand-over overlaps the whole tiles.
+    // The first sk_tiles tiles are cut along K and dealt as `Deal` says; the others are taken whole,
+    // round-robin.  The shared tiles come first: their partial tiles are long written when the kernel ends.
     const Deal deal(sk_tiles, ktiles, G, parts);
     const int u_begin = deal.begin(worker), u_end = deal.end(worker);
     const int first_tile = u_begin / ktiles;

@@ -103,7 +103,7 @@ struct GemmArgs {
     const uint16_t* w1;      // up weights for SwiGLU
     uint16_t* out;           // [M,ldo]
     const uint16_t* residual; // [M,ldo] added behind the product (plain / RMSNorm kinds), or nullptr
-    float* partials;         // [grid][2][tile] fp32 partial tiles (stream-K)
+    float* partials;         // [grid][2][tile] fp32 partial tiles of tiles that were cut along K
     float* ssq;              // [grid][2][256]
     unsigned* counters;      // [tiles]
     int M, N, K, ldo;        // N = physical rows of w0
