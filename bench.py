@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 # per-launch HBM KiB (fetch, write) of the gate/up kernel, scaled, from the rocprofv3 --pmc runs in profiles/
 MEASURED_TRAFFIC_KIB = {
     (2, 32): ((178861.0, 928.0), "profiles/skinny_rowblock_llama7b_decode_m32.txt"),
-    (5, 2048): ((2767194.0, 114961.0), "profiles/gemm_streamk_llama70b_prefill_m2048.txt"),
+    (5, 2048): ((2770494.0, 115073.0), "profiles/gemm_streamk_llama70b_prefill_m2048.txt"),
 }
 
 
