@@ -21,7 +21,7 @@
  *     aligned, and prepared ONCE after allocation with thi_workspace_init().
  *     Every call leaves the workspace ready for the next call.  One workspace
  *     must not be used by two calls that may run concurrently.  The decode
- *     kernels (M <= 32) hand partial results from workgroup to workgroup inside
+ *     kernels (M <= 64) hand partial results from workgroup to workgroup inside
  *     one launch of one workgroup per compute unit; the waits are bounded, so a
  *     launch always terminates, but if the GPU is shared so heavily that a wait
  *     runs out, the last 32-bit word of the first 64 KiB of the workspace is set
@@ -203,7 +203,9 @@ int thi_version(void);
 /*
  * Tuning/diagnostic hook used by the benchmark and tests: force a kernel
  * family for subsequent calls from this process.  family: 0 = automatic
- * (default), 1 = weight-streaming decode kernel with stream-K units,
+ * (default: a decode kernel up to 32 tokens, the stream-K decode kernel or the
+ * GEMM kernels for 33..64 tokens, the GEMM kernels above), 1 = weight-streaming
+ * decode kernel with stream-K units (up to 64 tokens per launch),
  * 2 = MFMA GEMM kernels, 3 = weight-streaming decode kernel with row slabs
  * (16 rows over the whole of K per workgroup at a time), 4 = weight-streaming
  * decode kernel with row blocks (N / #CUs rows per workgroup, several 16-row

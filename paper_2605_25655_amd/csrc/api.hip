@@ -76,14 +76,6 @@ Workspace carve(void* base, size_t h_size = 0, size_t xn_size = 0)
     return w;
 }
 
-bool use_skinny(int M)
-{
-    const int fam = g_family.load(std::memory_order_relaxed);
-    if (fam == 1 || fam == 3 || fam == 4) return true;
-    if (fam == 2) return false;
-    return M <= SKINNY_MAX_M;
-}
-
 // Decode: which of the three weight-streaming kernels?
 //   stream-K   : work units of 128 rows x 256 k in equal contiguous shares: perfect balance whatever the
 //                shape, a hand-over between workgroups at the end;
@@ -171,6 +163,37 @@ int pick_decode_kernel(int M, int N, int K, int epilogue, int cus)
     return t_slab < t_sk ? DK_ROWSLAB : DK_STREAMK;
 }
 
+// Which kernel runs a projection of M tokens, and how many tokens a launch takes.
+//   M <= 32       : a decode kernel (pick_decode_kernel), one launch.
+//   33 <= M <= 64 : the stream-K decode kernel takes up to 64 tokens per launch (its activations are
+//                   shared by the workgroup's waves through LDS, so the wider batch costs it least); it
+//                   runs where its modelled time beats the few-token GEMM's (fitted on the 7B..70B
+//                   projections: stream-K 5.5 us + 1.06 t_w + 8 us with three token tiles / 13 us with
+//                   four; GEMM 8 us for its two launches, 5 more for the RMSNorm pass, + 1.5 t_w up to
+//                   t_w = 30 us and 1.25 t_w beyond).  Typically: everything but the smallest matrices up
+//                   to 48 tokens, about a tie above.
+//   M > 64        : the GEMM kernels.
+// A forced family overrides this (forced stream-K: 64 tokens per launch; forced row slabs / blocks: 32).
+struct DecodePlan {
+    int kernel;     // DK_*, or 0 = the GEMM kernels
+    int group;      // tokens per launch
+};
+DecodePlan plan_decode(int M, int N, int K, int epilogue, int cus)
+{
+    const int fam = g_family.load(std::memory_order_relaxed);
+    if (fam == 2) return DecodePlan{0, 0};
+    const int first = M < SKINNY_GROUP ? M : SKINNY_GROUP;
+    if (fam == 1) return DecodePlan{DK_STREAMK, M > SKINNY_GROUP ? 16 * SK_MAX_MT : SKINNY_GROUP};
+    if (fam == 3 || fam == 4) return DecodePlan{pick_decode_kernel(first, N, K, epilogue, cus), SKINNY_GROUP};
+    if (M <= SKINNY_MAX_M) return DecodePlan{pick_decode_kernel(first, N, K, epilogue, cus), SKINNY_GROUP};
+    if (M > 16 * SK_MAX_MT) return DecodePlan{0, 0};
+    const double t_w = (is_swiglu(epilogue) ? 2.0 : 1.0) * (double)N * (double)K * 2.0 / 7.0e6;
+    const double t_sk = 5.5 + 1.06 * t_w + (M <= 48 ? 8.0 : 13.0);
+    const double t_gemm = (is_rms(epilogue) ? 13.0 : 8.0) + 1.5 * (t_w < 30.0 ? t_w : 30.0) + 1.25 * (t_w > 30.0 ? t_w - 30.0 : 0.0);
+    if (t_sk < t_gemm) return DecodePlan{DK_STREAMK, 16 * SK_MAX_MT};
+    return DecodePlan{0, 0};
+}
+
 // One fused projection: out[M, ldo] = epilogue( prologue(x)[M,K] * w^T ), any M.
 int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const uint16_t* w0, const uint16_t* w1,
                    uint16_t* out, int M, int N, int K, int ldo, int epilogue, const Workspace& ws,
@@ -179,13 +202,14 @@ int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const ui
 {
     const int cus = device_cu_count();
     (void)hipGetLastError();      // an error another user of the runtime left behind is not ours to report
-    if (use_skinny(M)) {
-        const int kernel = pick_decode_kernel(M < SKINNY_GROUP ? M : SKINNY_GROUP, N, K, epilogue, cus);
+    const DecodePlan dp = plan_decode(M, N, K, epilogue, cus);
+    if (dp.kernel != 0) {
+        const int kernel = dp.kernel, group = dp.group;
         const bool slab = kernel != DK_STREAMK, block = kernel == DK_ROWBLOCK;
         const int rows_per_tile = slab ? (is_swiglu(epilogue) ? 8 : 16) : (is_swiglu(epilogue) ? SK_ROWS / 2 : SK_ROWS);
         const int tiles = (N + rows_per_tile - 1) / rows_per_tile;
         if ((long)tiles * ((K + SK_KC - 1) / SK_KC) > (1L << 30)) return THI_ERR_SHAPE;
-        for (int m0 = 0; m0 < M; m0 += SKINNY_GROUP) {
+        for (int m0 = 0; m0 < M; m0 += group) {
             SkinnyArgs a;
             a.x = x + (size_t)m0 * K;
             a.gamma = gamma;
@@ -195,7 +219,7 @@ int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const ui
             a.residual = residual ? residual + (size_t)m0 * ldo : nullptr;
             a.handover = ws.handover;
             a.counters = ws.counters;
-            a.M = (M - m0 < SKINNY_GROUP) ? M - m0 : SKINNY_GROUP;
+            a.M = (M - m0 < group) ? M - m0 : group;
             a.N = N;
             a.K = K;
             a.ldo = ldo;
@@ -447,9 +471,9 @@ int thi_version(void) { return THI_VERSION; }
 int thi_query_kernel_family(int M, int N, int K, int fused)
 {
     if (M < 1 || N < 1 || K < 1 || fused < 0 || fused > 2) return 0;
-    if (!use_skinny(M)) return 2;
     const int epilogue = fused == 1 ? EPI_RMSNORM : fused == 2 ? EPI_SWIGLU : EPI_PLAIN;
-    return pick_decode_kernel(M < SKINNY_GROUP ? M : SKINNY_GROUP, N, K, epilogue, device_cu_count());
+    const DecodePlan dp = plan_decode(M, N, K, epilogue, device_cu_count());
+    return dp.kernel != 0 ? dp.kernel : 2;
 }
 
 int thi_set_rowblock_split(int split)

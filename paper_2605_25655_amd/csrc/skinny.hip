@@ -101,9 +101,11 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(const uint16_t* x_,
     a.x = x_; a.w0 = w0_; a.w1 = w1_; a.M = M_; a.N = N_; a.K = K_; a.tiles = tiles_; a.kchunks = kchunks_;
     __shared__ uintx4 xs[2][8 * MT * 64];          // staged activations, MFMA B-operand order
     __shared__ uintx4 wt[SK_WAVES][WT_UNITS];      // wave-private transposition buffers
-    __shared__ float s_red[SK_WAVES][32];
-    __shared__ float s_ssq[32];
+    constexpr int TOK = MT == 1 ? 32 : 16 * MT;    // token slots of the per-token sums (a single tile is padded to 32)
+    __shared__ float s_red[SK_WAVES][TOK];
+    __shared__ float s_ssq[TOK];
     __shared__ unsigned s_flag;
+    static_assert(MT >= 1 && MT <= SK_MAX_MT, "token tiles per launch");
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -250,7 +252,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(const uint16_t* x_,
             }
             if (MT == 1 && st_g == 0) s_red[wv][16 + st_c] = 0.f;
             __syncthreads();
-            if (tid < 32) {
+            if (tid < TOK) {
                 float v = 0.f;
 #pragma unroll
                 for (int i = 0; i < SK_WAVES; ++i) v += s_red[i][tid];
@@ -272,8 +274,8 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(const uint16_t* x_,
         if (!whole) {
             const int w_first = deal.owner(tile_begin);
             const int w_last = deal.owner(tile_begin + kch - 1);
-            const bool lane_ssq = is_rms(EPI) && tid < 32;
-            const int own = (wv * 2 * 64 + lane) * 4;       // this lane's word group (token tile 0) in a slot
+            const bool lane_ssq = is_rms(EPI) && tid < TOK;
+            const int own = (wv * SK_MAX_MT * 64 + lane) * 4;       // this lane's word group (token tile 0) in a slot
             if (wg != w_first) {
                 unsigned* ps = a.handover + (size_t)wg * SK_SLOT_WORDS;
                 // only the lanes that hold a real token (column c = lane % 16 of token tile mt) take part
@@ -333,7 +335,18 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(const uint16_t* x_,
                                 ? __hip_atomic_load(cs[b] + SK_SLOT_SSQ + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
                                 : 0u;      // +0.0f
                         }
-                        load_device_x4_batch<MT>(cs[0] + own, cs[1] + own, cs[2] + own, cs[3] + own, pv);
+                        if constexpr (MT <= 2) {
+                            load_device_x4_batch<MT>(cs[0] + own, cs[1] + own, cs[2] + own, cs[3] + own, pv);
+                        } else {      // token tiles 0, 1, then the others: two batches
+                            uintx4 lo[4][2], hi[4][MT - 2];
+                            load_device_x4_batch<2>(cs[0] + own, cs[1] + own, cs[2] + own, cs[3] + own, lo);
+                            load_device_x4_batch<MT - 2>(cs[0] + own + 512, cs[1] + own + 512, cs[2] + own + 512,
+                                                         cs[3] + own + 512, hi);
+#pragma unroll
+                            for (int b = 0; b < 4; ++b)
+#pragma unroll
+                                for (int mt = 0; mt < MT; ++mt) pv[b][mt] = mt < 2 ? lo[b][mt < 2 ? mt : 0] : hi[b][mt >= 2 ? mt - 2 : 0];
+                        }
 #pragma unroll
                         for (int b = 0; b < 4; ++b) {
                             if (wc0 + b > w_last) continue;
@@ -351,7 +364,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(const uint16_t* x_,
                     }
                     if (is_rms(EPI)) {
                         __syncthreads();
-                        if (tid < 32) s_ssq[tid] = sq;
+                        if (tid < TOK) s_ssq[tid] = sq;
                         __syncthreads();
                     }
                 }
@@ -439,7 +452,10 @@ hipError_t launch_skinny(const SkinnyArgs& a, int epilogue, int num_cus, hipStre
     if (grid > SK_MAX_GRID) grid = SK_MAX_GRID;
     if (grid > U) grid = U;
     if (a.M <= 16) return launch_mt<1>(a, epilogue, (int)grid, stream);
-    return launch_mt<2>(a, epilogue, (int)grid, stream);
+    if (a.M <= 32) return launch_mt<2>(a, epilogue, (int)grid, stream);
+    if (a.M <= 48) return launch_mt<3>(a, epilogue, (int)grid, stream);
+    if (a.M <= 16 * SK_MAX_MT) return launch_mt<4>(a, epilogue, (int)grid, stream);
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_fill_words(void* ptr, size_t bytes, uint32_t value, hipStream_t stream)

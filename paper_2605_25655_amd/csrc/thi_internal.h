@@ -49,12 +49,13 @@ constexpr int SK_THREADS = 512;     // 8 waves
 constexpr int SK_WAVES = 8;
 constexpr int SK_ROWS = 128;        // virtual weight rows per tile (16 per wave)
 constexpr int SK_KC = 256;          // k extent of one work unit
-constexpr int SK_MAX_GRID = 1024;   // upper bound on workgroups (sizes the hand-over slots)
+constexpr int SK_MAX_GRID = 512;    // upper bound on workgroups (sizes the hand-over slots)
+constexpr int SK_MAX_MT = 4;        // token tiles of 16 per launch of the stream-K kernel (64 tokens)
 constexpr unsigned SK_SPIN_LIMIT = 1u << 24;   // polls of a contributor's flag before a workgroup gives up
-// hand-over slot of one workgroup: its partial tile (8 waves x 2 token tiles x 64 lanes x 4 registers,
-// fp32 bit patterns), then 32 partial sums of squares, padded to a multiple of 64 words
-constexpr int SK_SLOT_SSQ = SK_WAVES * 2 * 4 * 64;
-constexpr int SK_SLOT_WORDS = SK_SLOT_SSQ + 64;
+// hand-over slot of one workgroup: its partial tile (8 waves x up to 4 token tiles x 64 lanes x 4
+// registers, fp32 bit patterns), then up to 64 partial sums of squares
+constexpr int SK_SLOT_SSQ = SK_WAVES * SK_MAX_MT * 4 * 64;
+constexpr int SK_SLOT_WORDS = SK_SLOT_SSQ + 16 * SK_MAX_MT;
 
 struct SkinnyArgs {
     const uint16_t* x;       // [M,K] activations

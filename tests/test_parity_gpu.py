@@ -136,6 +136,59 @@ def test_both_kernel_families_cover_every_m(thi, oracle_mod, family, M):
     check(c, y, s, "swiglu", argmax=False)
 
 
+# ------------------------------- 33..64 tokens per launch of the stream-K decode kernel
+# three and four token tiles; the tiles are shared between workgroups (hand-over of the wider partial
+# tiles), every epilogue; family 0 = the dispatcher's own choice for these sizes
+@pytest.mark.parametrize("M,N,K,family", [(33, 4096, 4096, 1), (48, 2000, 11008 + 8, 1), (49, 4096, 4096, 1),
+                                          (64, 1536, 8192, 1), (100, 640, 2056, 1), (48, 12288, 4096, 0),
+                                          (64, 12288, 4096, 0)])
+def test_streamk_wide_batches(thi, oracle_mod, M, N, K, family):
+    say(f"[case] stream-K, up to 64 tokens per launch M={M} N={N} K={K} family={family}")
+    x, w, g = synth.random_problem(8300 + M + N + K, M, N, K)
+    rng = np.random.Generator(np.random.Philox(key=8400 + M + N + K))
+    res = f16(rng.standard_normal((M, N)))
+    I = N // 2
+    hd = 64
+    n_rot = (N // 2) // hd * hd
+    pos = rng.integers(0, 4096, size=M).astype(np.int32)
+    th = _theta(hd)
+    cols = np.unique(np.concatenate([synth.sample_rows(11, N, 300), np.arange(N - 40, N), np.arange(0, 40)]))
+    cols = np.unique(np.concatenate([cols, cols ^ 1]))
+    cols = cols[cols < N]
+    jc = np.unique(np.concatenate([synth.sample_rows(12, I, 200), np.arange(I - 20, I), np.arange(0, 20)]))
+    r = Runner(M, K, max(I, K), N)
+    xd, wd, gd = to_dev(x), to_dev(w), to_dev(g)
+    if family == 0:
+        assert thi.thi_query_kernel_family(M, N, K, 1) == 1      # the RMSNorm-fronted projection goes to stream-K
+    prev = thi.thi_set_kernel_family(family)
+    try:
+        a = to_host(r.linear(xd, wd))
+        a2 = to_host(r.linear(xd, wd))
+        ar = to_host(r.linear_residual(xd, wd, to_dev(res)))
+        b = to_host(r.rmsnorm_qkv(xd, gd, 1e-6, wd))
+        b2 = to_host(r.rmsnorm_qkv(xd, gd, 1e-6, wd))
+        c = to_host(r.rmsnorm_qkv_rope(xd, gd, 1e-6, wd, _dev_i32(pos), _dev_f32(th), n_rot, hd))
+        h = to_host(r.swiglu_gate_up(xd, wd[:I], wd[I:2 * I]))
+    finally:
+        thi.thi_set_kernel_family(prev)
+    assert np.array_equal(a.view(np.uint16), a2.view(np.uint16)) and np.array_equal(b.view(np.uint16), b2.view(np.uint16))
+    ws = np.ascontiguousarray(w[cols])
+    y, s = oracle_mod.linear(x, ws)
+    check(a[:, cols], y, s, "linear", argmax=False)
+    y, s = oracle_mod.linear_residual(x, ws, np.ascontiguousarray(res[:, cols]))
+    check(ar[:, cols], y, s, "linear_residual", argmax=False)
+    y, s = oracle_mod.rmsnorm_qkv(x, g, 1e-6, ws)
+    check(b[:, cols], y, s, "rmsnorm_qkv", argmax=False)
+    rows = synth.sample_rows(13, M, 6)
+    y, s = oracle_mod.rmsnorm_qkv_rope(x[rows], g, 1e-6, w, pos[rows], th, n_rot, hd)
+    check(c[rows], y, s, "rmsnorm_qkv_rope", argmax=False)
+    _, _, hh = oracle_mod.swiglu_mlp(x, np.ascontiguousarray(w[:I][jc]), np.ascontiguousarray(w[I:2 * I][jc]),
+                                     np.zeros((K, len(jc)), np.float16), return_h=True)
+    err = np.abs(h[:, jc].astype(np.float64) - hh)
+    bound = 2e-3 * np.abs(hh) + 2e-3 * np.sqrt((hh ** 2).mean())
+    assert (err <= bound).all(), f"gate/up worst excess {(err - bound).max()}"
+
+
 # ----------------------------------------------- shared-tile hand-over (decode)
 @pytest.mark.parametrize("M,N,K", [(1, 4096, 4096), (32, 4096, 4096), (32, 4096, 11008), (16, 512, 8192)])
 def test_shared_tile_handover_is_reproducible(thi, oracle_mod, M, N, K):
