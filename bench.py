@@ -200,8 +200,11 @@ def cpu_baseline(cfg, M, host_layer, target_seconds=12.0):
                       f"calls, all output columns), {dt:.1f} s of CPU time"}
 
 
-def measure_ceilings():
-    """What this GPU sustains: streaming HBM read and register-only fp16 MFMA (random operands)."""
+def measure_ceilings(same_bytes=None):
+    """What this GPU sustains: streaming HBM read and register-only fp16 MFMA (random operands).
+    same_bytes: also time the streaming read on that many bytes per launch, launched back to back the way
+    the operators are timed (windows of a 2 GiB buffer in rotation): what a kernel that only reads the
+    dominant kernel's bytes, and pays its own launch, gets."""
     import torch
     import paper_2605_25655_amd as thi
     sink = torch.zeros(4, dtype=torch.float32, device="cuda")
@@ -211,8 +214,21 @@ def measure_ceilings():
     for _ in range(4):
         e0.record(); thi.thi_probe_stream_read(buf, sink); e1.record(); torch.cuda.synchronize()
         best = max(best, buf.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9)
-    del buf
     out = {"hbm_stream_read_GBps": round(best, 1)}
+    if same_bytes:
+        nb = int(same_bytes) // 65536 * 65536
+        windows = [buf[i * nb:(i + 1) * nb] for i in range(buf.numel() // nb)]
+        for i in range(10):
+            thi.thi_probe_stream_read(windows[i % len(windows)], sink)
+        torch.cuda.synchronize()
+        n = 100
+        e0.record()
+        for i in range(n):
+            thi.thi_probe_stream_read(windows[i % len(windows)], sink)
+        e1.record(); torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / n
+        out["hbm_stream_read_same_bytes"] = {"bytes": nb, "us": round(us, 2), "GBps": round(nb / us / 1e3, 1)}
+    del buf
     gen = torch.Generator(device="cuda"); gen.manual_seed(5)
     for name, ops in (("mfma_f16_random_operands_TFLOPs", torch.randn(32768, generator=gen, device="cuda").half()),
                       ("mfma_f16_constant_operands_TFLOPs", torch.full((32768,), 0.0625, device="cuda").half())):
@@ -343,10 +359,12 @@ def main():
             print(f"# sweep {c2.name} M={m}: {extra[f'{c2.name}/M={m}']}", file=sys.stderr, flush=True)
         out["sweep"] = extra
 
-    out["ceilings"] = measure_ceilings()
+    out["ceilings"] = measure_ceilings(gu_bytes if decode else None)
     roof["attainable"] = (out["ceilings"]["hbm_stream_read_GBps"] if decode
                           else out["ceilings"]["mfma_f16_random_operands_TFLOPs"])
     roof["frac_of_attainable"] = round(roof["achieved"] / roof["attainable"], 4)
+    if decode:      # against a kernel that only reads the same bytes, launch included
+        roof["frac_of_read_only_kernel"] = round(out["ceilings"]["hbm_stream_read_same_bytes"]["us"] / roof["launch_us"], 4)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, M, host_layer)
     print(json.dumps(out), flush=True)
