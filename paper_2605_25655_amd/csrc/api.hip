@@ -36,7 +36,6 @@ inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Workspace {
     unsigned* counters;
-    float* ssq;
     unsigned* handover;
     float* partials;
     uint16_t* h;     // MLP: silu(gate)*up [M,I]
@@ -45,7 +44,7 @@ struct Workspace {
 };
 
 // Both kernel families keep their own regions (either may be forced for any M).
-size_t fixed_bytes() { return WS_COUNTER_BYTES + WS_SSQ_BYTES + round_up(skinny_handover_bytes(), 256); }
+size_t fixed_bytes() { return WS_COUNTER_BYTES + round_up(skinny_handover_bytes(), 256); }
 
 // (op, M, a, b) = (RMSNORM_QKV or LINEAR, M, N, K) or (SWIGLU_MLP, M, H, I)
 size_t h_bytes(int op, int M, int b) { return op == THI_OP_SWIGLU_MLP ? round_up((size_t)M * (size_t)b * 2, 256) : 0; }
@@ -67,8 +66,7 @@ Workspace carve(void* base, size_t h_size = 0, size_t xn_size = 0)
     char* p = static_cast<char*>(base);
     Workspace w;
     w.counters = reinterpret_cast<unsigned*>(p);
-    w.ssq = reinterpret_cast<float*>(p + WS_COUNTER_BYTES);
-    w.handover = reinterpret_cast<unsigned*>(p + WS_COUNTER_BYTES + WS_SSQ_BYTES);
+    w.handover = reinterpret_cast<unsigned*>(p + WS_COUNTER_BYTES);
     w.partials = reinterpret_cast<float*>(p + fixed_bytes());
     w.h = reinterpret_cast<uint16_t*>(p + fixed_bytes() + gemm_partial_bytes());
     w.xn = reinterpret_cast<uint16_t*>(p + fixed_bytes() + gemm_partial_bytes() + h_size);
@@ -256,20 +254,16 @@ int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const ui
     }
     GemmArgs g;
     g.x = x;
-    g.gamma = gamma;
     g.w0 = w0;
     g.w1 = w1;
     g.out = out;
     g.residual = residual;
     g.partials = ws.partials;
-    g.ssq = ws.ssq;
-    g.counters = ws.counters;
     g.tiles = 0;
     g.M = M;
     g.N = N;
     g.K = K;
     g.ldo = ldo;
-    g.eps = eps;
     g.rope = rope;
     return launch_gemm(g, epilogue, cus, stream) == hipSuccess ? THI_OK : THI_ERR_HIP;
 }

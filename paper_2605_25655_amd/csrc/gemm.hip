@@ -1,10 +1,12 @@
 // LDS-tiled fp16 MFMA GEMM for prefill (large M) on gfx950.
 //
 // Function: the paper's large-M linear operator (Sec. III-B.2) -- out = x W^T
-// with fp16 operands and fp32 accumulation (Sec. III-B.4) -- plus the same fused
-// low-density operators as the decode path (Sec. III-C.1): RMSNorm in front
-// (x*gamma applied while the activation tile is staged, sum x^2 on the side,
-// 1/sqrt(mean+eps) applied to the accumulator) and SiLU(gate)*up behind.
+// with fp16 operands and fp32 accumulation (Sec. III-B.4) -- plus the fused
+// low-density operators behind it (Sec. III-C.1): SiLU(gate)*up, the rotary
+// embedding, the residual.  RMSNorm in front runs as a small pass of its own
+// (rmsnorm_rows below) so that both operand tiles can go from memory straight
+// into LDS; fused into the staging of the activation tile it cost 25 % and
+// three times the HBM reads.
 // The paper's DDR->GSM->AM dataflow is specific to its scratchpad machine; here
 // a workgroup owns a BN x BM output tile (up to 256 x 256), stages BN x 64 and
 // BM x 64 operand tiles in LDS (double buffered, XOR-swizzled 16-byte pieces so
@@ -113,13 +115,13 @@ struct Deal {
 // half of the rows) holds, per register quad aa, four consecutive n of one token.
 template <int BN, int BM, int WN, int WM, int EPI>
 __device__ __forceinline__ void store_fragment(const GemmArgs& a, int tile_n, int tile_m, int wn, int wm, int tn,
-                                               int tm, int lr, int lg, const floatx16& f, float scale,
+                                               int tm, int lr, int lg, const floatx16& f,
                                                int aa_begin = 0, int aa_end = 4)
 {
     constexpr int JPT = is_swiglu(EPI) ? BN / 2 : BN;
     const int m = tile_m * BM + wm * (BM / WM) + tm * 32 + lr;
     if (m >= a.M) return;
-    if (is_swiglu(EPI)) {      // scale: the 1/rms factor when RMSNorm sits in front (else 1)
+    if (is_swiglu(EPI)) {
 #pragma unroll
         for (int aa = 0; aa < 4; aa += 2) {
             if (aa < aa_begin || aa >= aa_end) continue;
@@ -128,7 +130,7 @@ __device__ __forceinline__ void store_fragment(const GemmArgs& a, int tile_n, in
             half4 hv;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                const float g = f[4 * aa + c] * scale, uu = f[4 * (aa + 1) + c] * scale;
+                const float g = f[4 * aa + c], uu = f[4 * (aa + 1) + c];
                 hv[c] = (_Float16)(g / (1.0f + __expf(-g)) * uu);
             }
             if (j + 3 < a.N && (a.ldo & 3) == 0) {
@@ -146,7 +148,7 @@ __device__ __forceinline__ void store_fragment(const GemmArgs& a, int tile_n, in
             const int n = tile_n * BN + wn * (BN / WN) + tn * 32 + 8 * aa + 4 * lg;
             float v[4];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) v[c] = f[4 * aa + c] * scale;
+            for (int c = 0; c < 4; ++c) v[c] = f[4 * aa + c];
             if (has_rope(EPI)) {                         // the quad holds two complete pairs of one token
                 if (EPI == EPI_ROPE) {                   // cos / sin from the table the RMSNorm pass left
                     rope_pair_table(a.rope, m, n, v[0], v[1]);
@@ -196,8 +198,6 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_fixup(GemmArgs a, int tiles
     const Deal deal(sk_tiles, ktiles, G, parts);
     const int w_first = deal.first(t), w_last = deal.last(t);
     floatx4 g0 = {0.f, 0.f, 0.f, 0.f}, g1 = {0.f, 0.f, 0.f, 0.f};      // this half's two register quads
-    float sq = 0.f;
-    const int ml = wm * (BM / WM) + tm * 32 + lr;
     // a contributor's partial of this tile: slot 0 if the tile is the first of its share, else slot 1
     auto part = [&](int wc) -> const floatx4* {
         const int cslot = (deal.begin(wc) / ktiles == t) ? 0 : 1;
@@ -217,14 +217,6 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_fixup(GemmArgs a, int tiles
         const floatx4 v0 = p[0], v1 = p[THREADS];
         add(v0, v1);
     }
-    if (is_rms(EPI)) {
-        for (int w2 = w_first; w2 <= w_last; ++w2) {
-            const int cslot = (deal.begin(w2) / ktiles == t) ? 0 : 1;
-            sq += a.ssq[((size_t)w2 * 2 + cslot) * BM + ml];
-        }
-    }
-    float scale = 1.0f;
-    if (is_rms(EPI)) scale = 1.0f / __builtin_sqrtf(sq / (float)a.K + a.eps);
     floatx16 f;
 #pragma unroll
     for (int e = 0; e < 16; ++e) f[e] = 0.f;
@@ -235,8 +227,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_fixup(GemmArgs a, int tiles
 #pragma unroll
         for (int c = 0; c < 4; ++c) { f[8 + c] = g0[c]; f[12 + c] = g1[c]; }
     }
-    store_fragment<BN, BM, WN, WM, EPI>(a, t / tiles_m, t % tiles_m, wn, wm, tn, tm, lr, lg, f, scale, 2 * half,
-                                        2 * half + 2);
+    store_fragment<BN, BM, WN, WM, EPI>(a, t / tiles_m, t % tiles_m, wn, wm, tn, tm, lr, lg, f, 2 * half, 2 * half + 2);
 }
 
 // BN x BM output tile, WN x WM waves; wave tile (BN/WN) x (BM/WM) built from 32x32 MFMA tiles.
@@ -256,7 +247,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
     constexpr int TM = BM / WM / 32;
     constexpr int JPT = is_swiglu(EPI) ? BN / 2 : BN;   // physical weight rows per tile
     constexpr bool W_DMA = !KTAIL;                           // weight tile: global -> LDS directly
-    constexpr bool X_DMA = !KTAIL && !is_rms(EPI);     // activation tile: same unless it is transformed
+    constexpr bool X_DMA = !KTAIL;                           // activation tile: the same
     constexpr int STAGE = (BN + BM) * GPIECES;   // 16-byte units per stage: weight tile, then activation tile
     // A direct weight load takes a wave-uniform base; with SwiGLU and 16 tile rows per load (GK = 32) one
     // load spans a gate block and an up block, so that variant keeps per-lane 64-bit addresses.
@@ -265,7 +256,6 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
     static_assert(WPASS >= 1 && XPASS >= 1, "tile too small for the thread count");
 
     extern __shared__ uintx4 smem[];
-    __shared__ float s_r[BM];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid / 64);     // wave index, known uniform to the compiler
@@ -289,8 +279,8 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
 
     // DMA staging role.  A wave instruction covers ROWS_PER_DMA tile rows = 64 consecutive LDS units;
     // lane L owns unit L of it: row (ROWS_PER_DMA*block + L/P), physical slot L%P, logical piece
-    // slot ^ f(row).  VGPR staging role (operands that are transformed or zero-padded): logical piece
-    // tid%P of rows tid/P + ROWS_PER_PASS*i, so that one gamma piece serves all rows of a thread.
+    // slot ^ f(row).  VGPR staging role (operands that are zero-padded: ragged K): logical piece
+    // tid%P of rows tid/P + ROWS_PER_PASS*i.
     const int slot = lane % GPIECES;
     const int vp = tid % GPIECES, vr0 = tid / GPIECES;
     const uintx4 zero4 = {0u, 0u, 0u, 0u};
@@ -364,10 +354,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
             }
         }
 
-        uintx4 wreg[W_DMA ? 1 : WPASS], xreg[X_DMA ? 1 : XPASS], greg;
-        float ssq[XPASS];
-#pragma unroll
-        for (int i = 0; i < XPASS; ++i) ssq[i] = 0.f;
+        uintx4 wreg[W_DMA ? 1 : WPASS], xreg[X_DMA ? 1 : XPASS];
 
         // K is a multiple of 8, so a 16-byte piece is entirely inside or outside [0,K); with KTAIL the
         // pieces past K are read from the row start (valid memory) and replaced by zeros.
@@ -396,10 +383,6 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
                     xreg[i] = kok ? v : zero4;
                 }
             }
-            if (!X_DMA && is_rms(EPI)) {
-                const bool kok = !KTAIL || kt * GK + vp * 8 < K;
-                greg = *reinterpret_cast<const uintx4*>(a.gamma + (kok ? kt * GK + vp * 8 : 0));
-            }
         };
         auto store_w = [&](int buf) {             // VGPR path only
             if (!W_DMA) {
@@ -411,16 +394,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
             if (!X_DMA) {
 #pragma unroll
                 for (int i = 0; i < XPASS; ++i) {
-                    uintx4 xv = xreg[i];
-                    if (is_rms(EPI)) {
-                        half8 xh = __builtin_bit_cast(half8, xv);
-                        half8 gh = __builtin_bit_cast(half8, greg);
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) { float f = (float)xh[e]; ssq[i] = __builtin_fmaf(f, f, ssq[i]); }
-                        half8 pr = xh * gh;      // one rounding: the fp16 product of two fp16 values
-                        xv = __builtin_bit_cast(uintx4, pr);
-                    }
-                    smem[buf * STAGE + BN * GPIECES + swz<GPIECES>(vr0 + ROWS_PER_PASS * i, vp)] = xv;
+                    smem[buf * STAGE + BN * GPIECES + swz<GPIECES>(vr0 + ROWS_PER_PASS * i, vp)] = xreg[i];
                 }
             }
         };
@@ -514,19 +488,6 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
             mfmas((KSTEPS - 1) & 1);
         }
 
-        // ---- this run's sum of squares per token row (RMSNorm) -----------------------------------
-        if (is_rms(EPI)) {
-#pragma unroll
-            for (int i = 0; i < XPASS; ++i) {
-                float v = ssq[i];
-                v += __shfl_xor(v, 1);
-                v += __shfl_xor(v, 2);
-                v += __shfl_xor(v, 4);
-                if (vp == 0) s_r[vr0 + ROWS_PER_PASS * i] = v;
-            }
-            __syncthreads();
-        }
-
         // ---- whole tile: finished below; shared tile: leave the fp32 partial for the fix-up kernel ---
         const bool whole = (kb == 0 && ke == ktiles);
         if (!whole) {
@@ -540,22 +501,17 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
                     for (int q = 0; q < 4; ++q)
                         ps[((tn * TM + tm) * 4 + q) * THREADS + tid] =
                             floatx4{acc[tn][tm][4 * q], acc[tn][tm][4 * q + 1], acc[tn][tm][4 * q + 2], acc[tn][tm][4 * q + 3]};
-            if (is_rms(EPI) && tid < BM) a.ssq[((size_t)worker * 2 + pslot) * BM + tid] = s_r[tid];
         }
 
         // ---- epilogue ------------------------------------------------------------------------
         if (whole) {
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm) {
-                float scale = 1.0f;
-                if (is_rms(EPI))
-                    scale = 1.0f / __builtin_sqrtf(s_r[wm * (BM / WM) + tm * 32 + lr] / (float)K + a.eps);
+            for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn)
-                    store_fragment<BN, BM, WN, WM, EPI>(a, tile_n, tile_m, wn, wm, tn, tm, lr, lg, acc[tn][tm], scale);
-            }
+                    store_fragment<BN, BM, WN, WM, EPI>(a, tile_n, tile_m, wn, wm, tn, tm, lr, lg, acc[tn][tm]);
         }
-        // the next run rewrites the LDS stages and s_r only after this barrier
+        // the next run rewrites the LDS stages only after this barrier
         __syncthreads();
     }
 }
@@ -616,8 +572,8 @@ constexpr double SMALL_TFLOPS = 1.8, SMALL_FIXED_US = 6.0;    // 128x128, two pe
 constexpr double DEEP_TFLOPS = 3.4, DEEP_FIXED_US = 4.0;      // 128x128, three stages, one per CU
 constexpr double FEW_TFLOPS = 900.0 / 256;                    // one token tile: bound by the weight stream anyway
 
-// ALL = also build the variants with a transformed activation tile (RMSNorm) or a ragged K; the
-// 256x256 configuration leaves them to the 128x128 one (they would not fit its register budget).
+// ALL = also build the variant for a ragged K (operands staged through VGPRs); the direct-to-LDS
+// configurations leave it to the 128x128 one.
 template <int BN, int BM, int WN, int WM, int GK, int NS, bool ALL>
 hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream, double wg_tflops, double tile_fixed_us)
 {
@@ -659,8 +615,8 @@ hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream
     switch (epilogue) {
     case EPI_PLAIN: THI_LAUNCH(EPI_PLAIN); break;
     case EPI_ROPE: THI_LAUNCH(EPI_ROPE); break;
-    case EPI_RMSNORM:            // RMSNorm runs as a pass of its own in front of the GEMM (see the dispatcher);
-    case EPI_RMSNORM_ROPE:       // the fused variants of this kernel are kept in the source but not built
+    case EPI_RMSNORM:            // RMSNorm runs as a pass of its own in front of the GEMM: the dispatcher
+    case EPI_RMSNORM_ROPE:       // calls this with the plain / rotary / SwiGLU kinds only
     case EPI_RMSNORM_SWIGLU:
         return hipErrorInvalidValue;
     default: THI_LAUNCH(EPI_SWIGLU); break;

@@ -5,9 +5,10 @@
 // a workgroup owns a slab of 16 output features over the WHOLE reduction dimension, so nothing is
 // shared between workgroups.  Inside the workgroup the k range is cut into eight contiguous pieces,
 // one per wave; a wave streams its 16 rows x (K/8) k of weights in units of 256 k with fully
-// coalesced 16-byte loads (one or two units ahead of the arithmetic), passes them through a wave-private
-// LDS buffer to reach the MFMA operand layout, and takes its slice of the activations straight from
-// memory in operand layout (they stay cache resident: every workgroup reads the same M x K block).
+// coalesced 16-byte loads (one unit ahead of the arithmetic), passes them through a wave-private
+// LDS buffer to reach the MFMA operand layout, and takes its slice of the activations from memory
+// itself (they stay cache resident: every workgroup reads the same M x K block) -- in operand layout
+// up to four tokens, like the weights from five tokens up (XT below).
 // The eight partial tiles meet in LDS, are added in wave order (reproducible) and finished by the
 // fused epilogue (Sec. III-C.1: RMSNorm scale, rotary embedding, SwiGLU).
 //
@@ -102,12 +103,12 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowslab(const uint16_t* x_,
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) { acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f}; ssq[mt] = 0.f; }
 
-    // PD units of weights are in flight ahead of the one being consumed (register buffers in rotation)
-    constexpr int PD = 1;
+    // one unit of weights is in flight ahead of the one being consumed (two register buffers in rotation;
+    // a second unit ahead measured no faster)
     int slab = blockIdx.x, uu = 0;           // the unit being consumed
     int p_slab = blockIdx.x, p_uu = 0;       // the unit last requested
     int requested = 1;
-    uintx4 wb0[8], wb1[8], wb2[PD == 2 ? 8 : 1];
+    uintx4 wb0[8], wb1[8];
     // RMSNorm: this wave's slice of gamma goes to LDS once (wave-private: no workgroup barrier).  Its first
     // 64 pieces are requested before the first weights and stored behind them, so that the weights are in
     // flight while gamma arrives (all of gamma for K <= 4096).
@@ -119,11 +120,6 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowslab(const uint16_t* x_,
         for (int p = lane + 64; p * 8 < k_end - k_begin; p += 64)
             s_gamma[wv * g_pieces + p] = ld_cached(a.gamma + k_begin + p * 8);
         __builtin_amdgcn_wave_barrier();
-    }
-    if (PD == 2) {
-        if (++p_uu == nU) { p_uu = 0; p_slab += G; }
-        issue_w(p_slab, p_uu, requested < total, wb1);
-        ++requested;
     }
 
     auto step = [&](uintx4 (&cur)[8], uintx4 (&pre)[8]) {
@@ -290,20 +286,10 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowslab(const uint16_t* x_,
         // s_sum / s_ssq only after the next slab's first barrier, which follows this epilogue
     };
 
-    if constexpr (PD == 2) {
-        for (int i = 0; i < total; i += 3) {
-            step(wb0, wb2);
-            if (i + 1 >= total) break;
-            step(wb1, wb0);
-            if (i + 2 >= total) break;
-            step(wb2, wb1);
-        }
-    } else {
-        for (int i = 0; i < total; i += 2) {
-            step(wb0, wb1);
-            if (i + 1 >= total) break;
-            step(wb1, wb0);
-        }
+    for (int i = 0; i < total; i += 2) {
+        step(wb0, wb1);
+        if (i + 1 >= total) break;
+        step(wb1, wb0);
     }
 }
 

@@ -34,14 +34,15 @@ struct RopeArgs {
 constexpr int ROPE_TABLE_MAX_HEAD_DIM = 256;     // what the workspace reserves per token for that table
 
 // ---- workspace layout (bytes from the workspace base) ----------------------
-// [0, 64 KiB)             : status words (uint32), zero between calls: the decode kernels' hand-over
-//                           flags (one per workgroup), the GEMM's tile counters; last word: time-out marker
-// [64 KiB, 64 KiB + 1 MiB): prefill GEMM: per-workgroup partial sums of squares for RMSNorm
+// [0, 64 KiB)             : status words (uint32), zero between calls: the stream-K decode kernel's
+//                           hand-over flags (one per workgroup), the shared row blocks' arrival counters
+//                           (one per block); last word: time-out marker
 // [.., + hand-over bytes) : decode kernels: one hand-over slot per workgroup
 // [.., + partial bytes)   : prefill GEMM: per-workgroup partial accumulator tiles (fp32)
 // [.., + M*I*2)           : h = silu(gate)*up of the MLP (fp16)
+// [.., + M*K*2)           : the normalised activations of the RMSNorm-fronted operators (prefill), then
+//                           the rotary table of the QKV operator
 constexpr size_t WS_COUNTER_BYTES = 64 * 1024;
-constexpr size_t WS_SSQ_BYTES = 1024 * 1024;
 constexpr int WS_MAX_COUNTERS = (int)(WS_COUNTER_BYTES / 4);
 
 // ---- skinny (decode) kernel geometry ---------------------------------------
@@ -98,18 +99,14 @@ hipError_t launch_rowblock(const SkinnyArgs& a, int epilogue, int num_cus, hipSt
 
 // ---- GEMM (prefill) kernel ---------------------------------------------------
 struct GemmArgs {
-    const uint16_t* x;       // [M,K]
-    const uint16_t* gamma;   // [K] or nullptr
+    const uint16_t* x;       // [M,K] (already normalised where RMSNorm sits in front)
     const uint16_t* w0;      // [N,K]
     const uint16_t* w1;      // up weights for SwiGLU
     uint16_t* out;           // [M,ldo]
     const uint16_t* residual; // [M,ldo] added behind the product (plain / RMSNorm kinds), or nullptr
     float* partials;         // [grid][2][tile] fp32 partial tiles of tiles that were cut along K
-    float* ssq;              // [grid][2][256]
-    unsigned* counters;      // [tiles]
     int M, N, K, ldo;        // N = physical rows of w0
     int tiles;               // filled in by the launcher
-    float eps;
     RopeArgs rope;
 };
 constexpr int GEMM_MAX_GRID = 2048;   // in units of 128x128 partial tiles (a 256x256 tile takes four)
