@@ -74,30 +74,8 @@ Workspace carve(void* base, size_t h_size = 0, size_t xn_size = 0)
     return w;
 }
 
-// Decode: which of the three weight-streaming kernels?
-//   stream-K   : work units of 128 rows x 256 k in equal contiguous shares: perfect balance whatever the
-//                shape, a hand-over between workgroups at the end;
-//   row slabs  : slabs of 16 rows over the whole of K, dealt round-robin: no hand-over, but the slabs
-//                must divide well among the compute units and every wave reads its slice of x per slab;
-//   row blocks : N / #CUs rows per workgroup in one contiguous block, several 16-row tiles in flight
-//                sharing the wave's slice of x: no hand-over, balanced whenever N >> #CUs.
-// Decided by a time model in microseconds whose constants were fitted to measured (shape, M) points on
-// MI355X (17 shapes: the 7B..70B projections and a 32000-row output head, M = 1..32; the pick is within
-// 3 % of the best of the three on all but a handful, 5 % at worst).  t_w = weight bytes / 7.0 TB/s; a wave's last unit of 256 k may be
-// partly empty (ragged, slabs and blocks).
-//   stream-K   : ~5.5 us fixed + 1.06 t_w + the hand-over, 0.5 + 0.05 M us up to M = 16 and ~5 us above;
-//   row slabs  : ~3.5 us fixed; slowed by the slots a ragged last round leaves empty, by the activation
-//                traffic (x1.02 at M<=4, x1.09 at M<=8, x1.15 at M<=16, x1.45 above) and by ~10 % for
-//                the RMSNorm prologue;
-//   row blocks : ~3.8 us fixed (all tiles of a pass finish together: their reduction is not hidden),
-//                0.5 us per further pass over K, 4 us more with one or two tiles per workgroup and
-//                8192 <= K < 16384 (measured on the 70B O and 13B down projections); the activation
-//                traffic is shared by the tiles of a pass (+5 % / +15 % / +40 % at M <= 8 / 16 / 32,
-//                divided by the tiles per pass); a ragged last unit costs about a fifth of what it
-//                costs the slabs; slowed by the rows the last workgroup lacks.  With S workgroups per
-//                block (plain kind): S x the tiles share a load of x, the eight waves of S workgroups
-//                divide K, and the hand-over at the end costs ~2 us.
-// Row blocks, modelled time in microseconds with `split` workgroups per block (constants: see below)
+// Row blocks, modelled time in microseconds with `split` workgroups per block (the constants are
+// explained with the other two kernels' above pick_decode_kernel)
 double rowblock_time(int M, int N, int K, int epilogue, int cus, int split)
 {
     const bool swiglu = is_swiglu(epilogue);
@@ -132,6 +110,29 @@ int pick_rowblock_split(int M, int N, int K, int epilogue, int cus)
     return best;
 }
 
+// Decode: which of the three weight-streaming kernels?
+//   stream-K   : work units of 128 rows x 256 k in equal contiguous shares: perfect balance whatever the
+//                shape, a hand-over between workgroups at the end;
+//   row slabs  : slabs of 16 rows over the whole of K, dealt round-robin: no hand-over, but the slabs
+//                must divide well among the compute units and every wave reads its slice of x per slab;
+//   row blocks : N / #CUs rows per workgroup in one contiguous block, several 16-row tiles in flight
+//                sharing the wave's slice of x: no hand-over, balanced whenever N >> #CUs.
+// Decided by a time model in microseconds whose constants were fitted to measured (shape, M) points on
+// MI355X (17 shapes: the 7B..70B projections and a 32000-row output head, M = 1..32; the pick is within
+// 3 % of the best of the three on all but a handful, 5 % at worst).  t_w = weight bytes / 7.0 TB/s; a
+// wave's last unit of 256 k may be partly empty (ragged, slabs and blocks).
+//   stream-K   : ~5.5 us fixed + 1.06 t_w + the hand-over, 0.5 + 0.05 M us up to M = 16 and ~5 us above;
+//   row slabs  : ~3.5 us fixed; slowed by the slots a ragged last round leaves empty, by the activation
+//                traffic (x1.02 at M<=4, x1.09 at M<=8, x1.15 at M<=16, x1.45 above) and by ~10 % for
+//                the RMSNorm prologue;
+//   row blocks : ~3.8 us fixed (all tiles of a pass finish together: their reduction is not hidden),
+//                0.5 us per further pass over K, 4 us more with one or two tiles per workgroup and
+//                8192 <= K < 16384 (measured on the 70B O and 13B down projections); the activation
+//                traffic is shared by the tiles of a pass (+5 % / +15 % / +40 % at M <= 8 / 16 / 32,
+//                divided by the tiles per pass); a ragged last unit costs about a fifth of what it
+//                costs the slabs; slowed by the rows the last workgroup lacks.  With S workgroups per
+//                block (plain kind): S x the tiles share a load of x, the eight waves of S workgroups
+//                divide K, and the hand-over at the end costs ~2 us.
 enum DecodeKernel { DK_STREAMK = 1, DK_ROWSLAB = 3, DK_ROWBLOCK = 4 };
 int pick_decode_kernel(int M, int N, int K, int epilogue, int cus)
 {
