@@ -415,12 +415,15 @@ int thi_decode_attention(const void* q, const void* k_cache, const void* v_cache
     a.part = (float*)workspace;
     a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.D = D; a.S_max = S_max;
     a.group = Hq / Hkv;
-    // enough workgroups to fill the chip about four times over, cut along the positions if need be
+    // cut along the positions only as far as it takes to give every compute unit a workgroup: more,
+    // shorter chunks measured slower (32 requests x 8 cache heads x 2048 positions: 52 -> 42 us going from
+    // four workgroups per compute unit to one; 8 requests: 28 -> 19 us), and with a workgroup per compute
+    // unit already there the second pass is not needed at all
     const int gt = attention_heads_per_workgroup(a.group);
     const int passes = (a.group + gt - 1) / gt;
     const int quantum = attention_chunk_quantum(D, gt);
     const long base = (long)B * Hkv * passes;
-    long want = (4L * device_cu_count() + base - 1) / base;
+    long want = ((long)device_cu_count() + base - 1) / base;
     if (want < 1) want = 1;
     if (want > AT_MAX_SPLIT) want = AT_MAX_SPLIT;
     int chunk = (int)((S_max + want - 1) / want);
