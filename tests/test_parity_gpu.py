@@ -480,6 +480,42 @@ def test_rowblock_shared_reduction(thi, oracle_mod, M, N, K, split):
     assert (d <= 2e-3 * np.abs(a1.astype(np.float64)) + 2e-3 * np.sqrt((a1.astype(np.float64) ** 2).mean())).all()
 
 
+def test_handover_users_leave_the_workspace_clean(thi):
+    """The stream-K kernel's flags and the shared row blocks' arrival counters live in the same status
+    words and are reset by the kernels themselves: calls of different shapes and kinds, interleaved many
+    times on one workspace, must keep giving the bits of their first run."""
+    import torch
+    say("[case] hand-over flags and arrival counters across interleaved calls")
+    rng = np.random.Generator(np.random.Philox(key=5300))
+    shapes = [(32, 4096, 4096, 4, 2), (32, 4096, 11008, 4, 4), (17, 5120, 5160, 4, 3), (32, 4096, 4096, 1, 0),
+              (5, 1000, 8192, 1, 0), (48, 2048, 4096, 1, 0), (20, 4096, 11008, 4, 0)]
+    runs = []
+    r = Runner(48, 11008, 11008, 5120)
+    for M, N, K, family, split in shapes:
+        x = to_dev(f16(rng.standard_normal((M, K))))
+        w = to_dev(f16(rng.standard_normal((N, K)) * 0.02))
+        runs.append((x, w, family, split))
+    first = [None] * len(runs)
+    try:
+        for it in range(25):
+            for i, (x, w, family, split) in enumerate(runs):
+                thi.thi_set_kernel_family(family)
+                thi.thi_set_rowblock_split(split)
+                out = r.linear(x, w)
+                if first[i] is None:
+                    first[i] = out.clone()
+                else:
+                    assert torch.equal(out, first[i]), f"call {i} changed its result in round {it}"
+    finally:
+        thi.thi_set_rowblock_split(0)
+        thi.thi_set_kernel_family(0)
+    # the status words are zero again (the last one is the time-out marker)
+    torch.cuda.synchronize()
+    off = (-r.ws.buffer.data_ptr()) % 256
+    words = r.ws.buffer[off:off + 64 * 1024].cpu().numpy().view(np.uint32)
+    assert not words.any()
+
+
 @pytest.mark.parametrize("M,N", [(17, 20800), (17, 17920), (9, 17920), (9, 20800)])
 def test_rowblock_largest_lds_footprint(thi, oracle_mod, M, N):
     """K = 32768 with RMSNorm (a wave's slice of gamma: 8 KiB of LDS), five or six tiles in flight, one or
