@@ -46,7 +46,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
     constexpr int RT = (T * MT <= 6 && T <= 5) ? T : (T + 1) / 2;
     constexpr int OUT_PER_TILE = is_swiglu(EPI) ? 8 : 16;
     __shared__ uintx4 wt[SK_WAVES][WT_UNITS];          // wave-private transposition buffers
-    __shared__ float s_part[SK_WAVES][RT][MT * 4 * 64]; // the waves' partial tiles
+    __shared__ floatx4 s_part[SK_WAVES][RT][MT * 64];  // the waves' partial tiles, a lane's four registers together
     __shared__ float s_sum[RT][32][17];                // finished sums [tile][token][row]
     __shared__ float s_red[SK_WAVES][32];
     __shared__ float s_ssq[32];
@@ -308,9 +308,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
                 if (rr * RT + tt < T) {
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) {
-#pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            s_part[wv][tt][(mt * 4 + i) * 64 + lane] = acc[rr * RT + tt < T ? rr * RT + tt : 0][mt][i];
+                        s_part[wv][tt][mt * 64 + lane] = acc[rr * RT + tt < T ? rr * RT + tt : 0][mt];
                         acc[rr * RT + tt < T ? rr * RT + tt : 0][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
                     }
                 }
@@ -326,13 +324,14 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
             }
             __syncthreads();
             const int round_tiles = (rr + 1) * RT <= T ? RT : T - rr * RT;
-            for (int e = tid; e < round_tiles * MT * 256; e += SK_THREADS) {
-                const int tt = e / (MT * 256), q = e % (MT * 256);
-                float v = 0.f;       // fixed order: waves 0..7
+            for (int e = tid; e < round_tiles * MT * 64; e += SK_THREADS) {
+                const int tt = e / (MT * 64), q = e % (MT * 64);
+                floatx4 v = {0.f, 0.f, 0.f, 0.f};       // fixed order: waves 0..7
 #pragma unroll
                 for (int w = 0; w < SK_WAVES; ++w) v += s_part[w][tt][q];
-                const int l = q & 63, i = (q >> 6) & 3, mt = q >> 8;
-                s_sum[tt][mt * 16 + (l & 15)][4 * (l >> 4) + i] = v;
+                const int l = q & 63, mt = q >> 6;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) s_sum[tt][mt * 16 + (l & 15)][4 * (l >> 4) + i] = v[i];
             }
             if (is_rms(EPI) && first_pass && rr == 0 && tid < 32) {      // kept in s_ssq for the later passes
                 float v = 0.f;

@@ -38,7 +38,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowslab(const uint16_t* x_,
     // into registers at wave launch, so the first weight request does not wait for an argument fetch.
     a.x = x_; a.w0 = w0_; a.w1 = w1_; a.gamma = gamma_; a.M = M_; a.N = N_; a.K = K_; a.tiles = tiles_;
     __shared__ uintx4 wt[SK_WAVES][WT_UNITS];          // wave-private transposition buffers
-    __shared__ float s_part[SK_WAVES][MT * 4 * 64];    // the waves' partial tiles
+    __shared__ floatx4 s_part[SK_WAVES][MT * 64];      // the waves' partial tiles, a lane's four registers together
     __shared__ float s_sum[32][17];                    // finished sums [token][row]
     __shared__ float s_red[SK_WAVES][32];
     __shared__ float s_ssq[32];
@@ -221,8 +221,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowslab(const uint16_t* x_,
         // ---- the eight partial tiles meet in LDS ---------------------------------------------------
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) s_part[wv][(mt * 4 + i) * 64 + lane] = acc[mt][i];
+            s_part[wv][mt * 64 + lane] = acc[mt];
             if (is_rms(EPI) && first_slab) {
                 float v = ssq[mt];
                 v += __shfl_xor(v, 16);
@@ -233,13 +232,14 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowslab(const uint16_t* x_,
         }
         if (is_rms(EPI) && first_slab && MT == 1 && kg == 0) s_red[wv][16 + c] = 0.f;
         __syncthreads();
-        if (tid < MT * 256) {
+        if (tid < MT * 64) {
             // fixed order: waves 0..7
-            float v = 0.f;
+            floatx4 v = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int w = 0; w < SK_WAVES; ++w) v += s_part[w][tid];
-            const int l = tid & 63, i = (tid >> 6) & 3, mt = tid >> 8;
-            s_sum[mt * 16 + (l & 15)][4 * (l >> 4) + i] = v;
+            const int l = tid & 63, mt = tid >> 6;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) s_sum[mt * 16 + (l & 15)][4 * (l >> 4) + i] = v[i];
         }
         if (is_rms(EPI) && first_slab && tid < 32) {      // kept in s_ssq for the later slabs
             float v = 0.f;
