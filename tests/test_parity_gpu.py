@@ -441,6 +441,7 @@ ROWBLOCK_SPLIT = [
     (16, 1000, 4104, 4),         # few rows: 16 per block even when shared, one tile of two in flight
     (32, 8190, 8192, 2),         # 64 rows per block, the last block two short
     (9, 3000, 1024, 2),          # not admissible (K < 1024 * split): runs unshared
+    (40, 4096, 4096, 2),         # two launches (32 + 8 tokens) on the same counters and slots
 ]
 
 
