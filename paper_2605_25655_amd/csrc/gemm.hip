@@ -525,9 +525,13 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
 // time or the panels they share are fetched once per workgroup (measured: a 30B-shaped down projection,
 // 208 tiles of 256x256 on 256 workgroups in equal contiguous shares, ran HBM-bound at 585 us against 485
 // us for whole tiles on 208 workgroups).  So every remainder tile is cut into the same `parts` = grid /
-// remainder equal k ranges (whole tiles if that is 1).  With one token tile every weight panel is read
-// exactly once by one workgroup whatever the cut and the kernel is bound by its weight traffic: equal
-// contiguous shares (parts = 0) keep every workgroup busy.
+// remainder equal k ranges (whole tiles if that is 1) -- also with a single token tile of 256, whose
+// activation panel is shared by every workgroup and too large for an L2 (measured on the 30B-shaped down
+// projection at M = 256: 88 us against 97-113 us with contiguous shares), unless equal ranges would leave
+// more than a tenth of the workgroups idle (7B-shaped gate/up at M = 160: 86 tiles x 2 ranges on 256
+// workgroups, 81 against 75 us; 13B-shaped, 108 tiles x 2: 106 against 97 us).  The few-token configurations (one token tile of at most 128) are bound
+// by their weight traffic, every weight panel is read exactly once whatever the cut, and equal contiguous
+// shares (parts = 0) keep every workgroup busy.
 // A workgroup's speed by configuration, fitted to measurements of every configuration and cut on the four
 // projections of the 7B..70B shapes at M = 256..2048 (weight copies rotated so that they come from HBM;
 // clocks settled under each shape's load for 40 ms first -- after a lighter kernel the first launches run
@@ -543,25 +547,27 @@ struct Schedule {
 
 Schedule plan_schedule(int tiles, int tiles_m, int grid, int BN, int BM, int K, double wg_tflops, double tile_fixed_us)
 {
-    const double flops_us = 2.0 * BN * BM * (double)K / (wg_tflops * 1e6);
-    double tile_us = tile_fixed_us + flops_us;
+    double work_us = 2.0 * BN * BM * (double)K / (wg_tflops * 1e6);
+    if (tiles_m == 1) {      // every weight panel is read by one workgroup only: its traffic is a second bound
+        const double stream_us = (double)BN * K * 2.0 / (6.0e6 / grid);
+        work_us = work_us > stream_us ? work_us : stream_us;
+    }
+    const double tile_us = tile_fixed_us + work_us;
     const int rem = tiles % grid, full = tiles / grid;
     const double tile_bytes = (double)BN * BM * 4.0;
-    if (tiles_m == 1) {
-        const double stream_us = (double)BN * K * 2.0 / (6.0e6 / grid);
-        tile_us = tile_us > stream_us ? tile_us : stream_us;
-        const double whole = (double)((tiles + grid - 1) / grid) * tile_us;
-        if (rem == 0) return Schedule{0, 0, whole};
-        const double shared = ((double)full + (double)rem / grid) * tile_us + 5.0 + (double)(grid + rem) * tile_bytes * 2.0 / 4.0e6;
-        return shared < whole ? Schedule{rem, 0, shared} : Schedule{0, 0, whole};
-    }
     const double whole = (double)((tiles + grid - 1) / grid) * tile_us;
-    if (rem == 0) return Schedule{0, 1, whole};
+    if (rem == 0) return Schedule{0, tiles_m == 1 ? 0 : 1, whole};
     const int ktiles = (K + 63) / 64;
     int parts = grid / rem;
     if (parts > ktiles) parts = ktiles;
+    // One token tile: equal contiguous shares for the few-token configurations, and for a 256-token tile
+    // when equal ranges would leave more than a tenth of the workgroups idle.
+    if (tiles_m == 1 && (BM <= 128 || (long)rem * parts * 10 < (long)grid * 9)) {
+        const double shared = ((double)full + (double)rem / grid) * tile_us + 5.0 + (double)(grid + rem) * tile_bytes * 2.0 / 4.0e6;
+        return shared < whole ? Schedule{rem, 0, shared} : Schedule{0, 0, whole};
+    }
     if (parts < 2) return Schedule{0, 1, whole};
-    const double shared = (double)full * tile_us + tile_fixed_us + flops_us / parts + 5.0 +
+    const double shared = (double)full * tile_us + tile_fixed_us + work_us / parts + 5.0 +
                           (double)rem * parts * tile_bytes * 2.0 / 8.0e6;
     return shared < whole ? Schedule{rem, parts, shared} : Schedule{0, 1, whole};
 }
