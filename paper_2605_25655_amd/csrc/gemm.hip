@@ -706,8 +706,16 @@ hipError_t launch_gemm(const GemmArgs& a, int epilogue, int num_cus, hipStream_t
     if (direct && a.M <= 128) {
         // Few tokens: one token tile, the weights are read once and the kernel is bound by how many
         // bytes a CU keeps in flight: three stages of 128 rows x 128 k against 64 tokens (K a multiple of
-        // 128), else of 256 rows x 64 k against 128 tokens.
+        // 128), else of 128 rows x 64 k against 128 tokens.  Every tile is cut along K here (far fewer
+        // tiles than workgroups) and the second pass costs by the partial tiles' bytes, (workgroups +
+        // tiles) x tile size: 128-row tiles halve them against 256-row tiles (7B-shaped O projection at
+        // M = 128: 24.8 -> 18.5 us, gate/up 61 -> 53; second pass alone 8.5-9.7 us with 256 rows).  With
+        // many more tiles than workgroups (70B-shaped gate/up: 448) the 256-row tile's smaller share of
+        // activation staging wins instead (188 against 230 us).
         if (a.M <= 64 && a.K % 128 == 0) return launch_cfg<128, 64, 4, 1, 128, 3, false>(a, epilogue, g_big, stream, FEW_TFLOPS, 0.0);
+        const int per_tile = is_swiglu(epilogue) ? 64 : 128;
+        if ((a.N + per_tile - 1) / per_tile <= num_cus + num_cus / 8)
+            return launch_cfg<128, 128, 2, 2, 64, 3, false>(a, epilogue, g_big, stream, FEW_TFLOPS, 0.0);
         return launch_cfg<256, 128, 4, 1, 64, 3, false>(a, epilogue, g_big, stream, FEW_TFLOPS, 0.0);
     }
     // Several token tiles: the configuration with the smallest modelled time.  The three-stage 128x128
