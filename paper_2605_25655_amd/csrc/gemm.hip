@@ -718,6 +718,17 @@ hipError_t launch_gemm(const GemmArgs& a, int epilogue, int num_cus, hipStream_t
             return launch_cfg<128, 128, 2, 2, 64, 3, false>(a, epilogue, g_big, stream, FEW_TFLOPS, 0.0);
         return launch_cfg<256, 128, 4, 1, 64, 3, false>(a, epilogue, g_big, stream, FEW_TFLOPS, 0.0);
     }
+    // 129..256 tokens and about as many 128-row tiles as workgroups (0.65..1.2 x: the gate/up shapes):
+    // one token tile of 256 against 128 rows, so that the weights are read once and few tiles are cut
+    // (7B-shaped gate/up at M = 192: 74.9 -> 67.4 us, 13B 98.9 -> 94.2, 30B 161 -> 152).  With fewer tiles
+    // the 128 KiB partial tiles of the workgroups that share one cost more than reading the weights twice
+    // (7B-shaped O projection 22.5 -> 31 us), with more the 256-row tile wins: both stay with the rule below.
+    if (direct && a.M <= 256) {
+        const int per_tile = is_swiglu(epilogue) ? 64 : 128;
+        const long t128 = (a.N + per_tile - 1) / per_tile;
+        if (t128 * 20 >= (long)num_cus * 13 && t128 * 5 <= (long)num_cus * 6)
+            return launch_cfg<128, 256, 2, 4, 64, 3, false>(a, epilogue, g_big, stream, FEW_TFLOPS, 0.0);
+    }
     // Several token tiles: the configuration with the smallest modelled time.  The three-stage 128x128
     // configuration runs one workgroup per CU, which only pays where the two-per-CU one would not have a
     // second workgroup for most CUs anyway (at most one 128x128 tile per CU).

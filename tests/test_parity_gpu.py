@@ -227,6 +227,8 @@ SCHED = [
     (2048, 8192 + 256, 1088, "256-tile: one whole round + 8 tiles in 17 ranges each (as many as k-tiles)"),
     (2048, 2560, 4160, "256-tile: 80 tiles in 3 ranges each, 65 k-tiles (uneven ranges)"),
     (1024, 10240, 8256, "128-tile: one whole round + 128 tiles in 4 ranges each, 129 k-tiles"),
+    (160, 22016 + 40, 1024, "129..256 tokens, 173 tiles of 128 rows: one token tile of 256"),
+    (256, 30000, 1088, "the same configuration, 235 tiles, ragged N"),
 ]
 
 
@@ -250,7 +252,9 @@ def test_prefill_schedules(thi, oracle_mod, M, N, K, why):
     assert np.isfinite(a1.astype(np.float32)).all() and np.isfinite(b1.astype(np.float32)).all()
 
 
-@pytest.mark.parametrize("M,H,I", [(512, 1024, 2816), (768, 512, 1376), (2048, 1024, 1536)])
+@pytest.mark.parametrize("M,H,I", [(512, 1024, 2816), (768, 512, 1376), (2048, 1024, 1536),
+                                   (200, 1024, 11008),      # 129..256 tokens, 172 gate/up tiles: the 128 x 256 configuration
+                                   (256, 512, 13824 + 8)])
 def test_prefill_swiglu_schedules(thi, oracle_mod, M, H, I):
     say(f"[case] prefill swiglu M={M} H={H} I={I}")
     rng = np.random.Generator(np.random.Philox(key=7000 + M + H + I))
