@@ -3,9 +3,15 @@
 
 A "step" is one pass of the whole hot path over one batch of synthetic input:
 thi_rmsnorm_qkv, thi_linear (O projection) and thi_swiglu_mlp enqueued
-back-to-back on one stream.  Default workload: the Llama-7B-shaped layer at
-decode M=32 (the configuration the metric is quoted on).  Weight copies are
+back-to-back on one stream.  Headline workload: the Llama-7B-shaped layer at
+decode M=32 (the configuration the metric is quoted on); the same line carries
+the prefill half of the metric (`prefill`: the 70B-shaped layer at M=2048 and
+the 13B-shaped layer at M=512, each with its own `roofline`).  Weight copies are
 rotated between steps so that the 256 MB last-level cache cannot serve them.
+
+Every figure is the MEDIAN of >= 5 blocks of >= 50 launches, each block
+bracketed by HIP events on the launch stream (`timing` in the output says how
+many); --steps only raises the launches per block.
 
 Prints ONE JSON line (see README for the fields).
 """
@@ -22,11 +28,19 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
-# per-launch HBM KiB (fetch, write) of the gate/up kernel, scaled, from the rocprofv3 --pmc runs in profiles/
-MEASURED_TRAFFIC_KIB = {
-    (2, 32): ((178861.0, 928.0), "profiles/skinny_rowblock_llama7b_decode_m32.txt"),
-    (5, 2048): ((2770494.0, 115073.0), "profiles/gemm_streamk_llama70b_prefill_m2048.txt"),
-}
+BLOCKS = 5                 # timed blocks per figure (the median is reported)
+MIN_PER_BLOCK = 50         # launches per block at least
+
+
+def committed_traffic():
+    """Per-launch HBM KiB (fetch, write) of the gate/up kernel from the rocprofv3 --pmc runs summarised under
+    profiles/, already scaled by the copy-kernel factor, keyed "config/M" -- with the commit they were
+    measured at, which is reported next to the figure (a later kernel change makes them stale)."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
+            return json.load(f)
+    except (OSError, ValueError):
+        return {}
 
 
 def parse_args():
@@ -41,6 +55,7 @@ def parse_args():
     ap.add_argument("--context", type=int, default=2048,
                     help="cached positions per request for the decode-attention timing (extra, decode only; 0 = skip)")
     ap.add_argument("--sweep", action="store_true", help="also time the other configs/M (extra, not the headline)")
+    ap.add_argument("--no-prefill", action="store_true", help="skip the prefill legs (70B M=2048, 13B M=512)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="run one plain 1 GiB device copy before the timed region (scales rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     ap.add_argument("--traffic-kib", type=float, nargs=2, default=None, metavar=("FETCH", "WRITE"),
@@ -51,8 +66,12 @@ def parse_args():
 def device_weights(cfg, copies, host_layer):
     """copies of the layer's weights on the device: copy 0 is the seeded host layer,
     the others are seeded device draws with the same distribution."""
+    import numpy as np
     import torch
-    from tests.gpu_common import to_dev
+
+    def to_dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda().view(torch.float16)
+
     names = ("w_qkv", "w_o", "w_gate", "w_up", "w_down")
     shapes = {"w_qkv": (cfg.n_qkv, cfg.hidden), "w_o": (cfg.hidden, cfg.hidden), "w_gate": (cfg.inter, cfg.hidden),
               "w_up": (cfg.inter, cfg.hidden), "w_down": (cfg.hidden, cfg.inter)}
@@ -139,21 +158,28 @@ class LayerBench:
         else:
             raise KeyError(name)
 
-    def time_loop(self, fn, steps, warmup):
-        """ms per call of fn(i): HIP events on the stream the kernels are launched on."""
+    def time_loop(self, fn, per_block, warmup, blocks=BLOCKS):
+        """ms per call of fn(i): the median over `blocks` blocks of `per_block` launches, each block between two
+        HIP events on the stream the kernels are launched on (torch's current stream, which the binding
+        passes to the library).  Also returns the host wall time per call and the per-block figures."""
         torch = self.torch
         for i in range(warmup):
             fn(i)
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        per, n = [], warmup
         t0 = time.perf_counter()
-        e0.record()
-        for i in range(steps):
-            fn(warmup + i)
-        e1.record()
-        torch.cuda.synchronize()
-        wall = (time.perf_counter() - t0) * 1e3 / steps
-        return e0.elapsed_time(e1) / steps, wall
+        for _ in range(blocks):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(per_block):
+                fn(n + i)
+            e1.record()
+            torch.cuda.synchronize()
+            per.append(e0.elapsed_time(e1) / per_block)
+            n += per_block
+        wall = (time.perf_counter() - t0) * 1e3 / (blocks * per_block)
+        per.sort()
+        return per[len(per) // 2], wall, per
 
 
 def op_bytes_flops(cfg, M, name):
@@ -238,6 +264,73 @@ def measure_ceilings(same_bytes=None):
     return out
 
 
+def measure_layer(cfg, M, args, host_layer, per_block, warmup, op_names, traffic_kib=None):
+    """Times the layer step and the named operators for one (config, M); returns the parts of the report:
+    step figures, per-operator figures and the roofline object of the dominant kernel (gate/up projection with
+    the fused SiLU*up epilogue, timed alone through thi_swiglu_gate_up with the same weight rotation)."""
+    import torch
+    from paper_2605_25655_amd import roofline as rf
+    import paper_2605_25655_amd as thi
+
+    decode = M <= 64
+    lb = LayerBench(cfg, M, args.rotate_bytes, host_layer)
+    ms_step, wall_ms, step_blocks = lb.time_loop(lb.step, per_block, warmup)
+    layer_bytes = rf.layer_bytes(M, cfg.hidden, cfg.n_qkv, cfg.inter)
+    layer_flops = rf.layer_flops(M, cfg.hidden, cfg.n_qkv, cfg.inter)
+    ops = {}
+    for name in op_names:
+        ms, _, _ = lb.time_loop(lambda i, n=name: lb.op(n, i), per_block, max(5, warmup // 2))
+        b, f = op_bytes_flops(cfg, M, name)
+        ops[name] = {"us": round(ms * 1e3, 2), "GBps": round(b / (ms * 1e-3) / 1e9, 1),
+                     "TFLOPs": round(f / (ms * 1e-3) / 1e12, 2)}
+    gu_ms = ops["gate_up"]["us"] * 1e-3
+    gu_bytes, gu_flops = op_bytes_flops(cfg, M, "gate_up")
+    if decode:
+        fam = thi.thi_query_kernel_family(M, cfg.inter, cfg.hidden, 2)
+        roof = {"bound": "hbm",
+                "kernel": f"gate_up ({ {3: 'skinny_rowslab', 4: 'skinny_rowblock'}.get(fam, 'skinny_streamk') }, SwiGLU epilogue)",
+                "achieved": round(gu_bytes / (gu_ms * 1e-3) / 1e9, 1), "peak": rf.MI355X_HBM_GBS, "unit": "GB/s",
+                "traffic": None}
+    else:
+        roof = {"bound": "mfma", "kernel": "gate_up (gemm_streamk, SwiGLU epilogue)",
+                "achieved": round(gu_flops / (gu_ms * 1e-3) / 1e12, 2), "peak": rf.MI355X_FP16_TFLOPS,
+                "unit": "TFLOP/s", "traffic": None}
+    # HBM traffic of the dominant kernel per launch comes from separate rocprofv3 --pmc runs of this same
+    # command (FETCH_SIZE, WRITE_SIZE, scaled by the --calib-copy kernel): --traffic-kib, else the committed
+    # figure for this workload together with the commit it was measured at.
+    src = "--traffic-kib"
+    if traffic_kib is None:
+        rec = committed_traffic().get(f"{cfg.index}/{M}")
+        if rec:
+            traffic_kib = (rec["fetch_kib"], rec["write_kib"])
+            src = f"{rec['source']} (measured at commit {rec['commit']})"
+    if traffic_kib is not None:
+        roof["traffic"] = (traffic_kib[0] + traffic_kib[1]) * 1024
+        roof["traffic_detail"] = {"fetch_bytes": traffic_kib[0] * 1024, "write_bytes": traffic_kib[1] * 1024,
+                                  "algorithmic_bytes": gu_bytes, "source": src}
+    roof["frac"] = round(roof["achieved"] / roof["peak"], 4)
+    roof["launch_us"] = ops["gate_up"]["us"]
+    part = {
+        "ms_per_step": round(ms_step, 5),
+        "ms_per_step_blocks": [round(v, 5) for v in step_blocks],
+        "tokens_s": round(M / (ms_step * 1e-3), 1),
+        "layer_GBps": round(layer_bytes / (ms_step * 1e-3) / 1e9, 1),
+        "layer_hbm_frac": round(layer_bytes / (ms_step * 1e-3) / 1e9 / rf.MI355X_HBM_GBS, 4),
+        "layer_TFLOPs": round(layer_flops / (ms_step * 1e-3) / 1e12, 2),
+        "layer_mfma_frac": round(layer_flops / (ms_step * 1e-3) / 1e12 / rf.MI355X_FP16_TFLOPS, 4),
+        "host_wall_ms_per_step": round(wall_ms, 5),
+        "weight_copies_rotated": lb.copies,
+        "ops": ops,
+        "roofline": roof,
+    }
+    return lb, part, gu_bytes
+
+
+def workload_name(cfg, M):
+    return (f"{cfg.name} decoder-layer linear ops (rmsnorm_qkv + o_proj + swiglu_mlp), "
+            f"{'decode' if M <= 64 else 'prefill'} M={M}")
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -254,7 +347,8 @@ def main():
     M = args.m
     decode = M <= 64
     host_layer = synth.make_layer(cfg, ms=())
-    lb = LayerBench(cfg, M, args.rotate_bytes, host_layer)
+    per_block = max(MIN_PER_BLOCK, args.steps)
+    warmup = max(10, args.warmup)
 
     if args.calib_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
@@ -262,61 +356,28 @@ def main():
         dst.copy_(src)                       # 1 GiB read + 1 GiB written, a kernel of known size
         torch.cuda.synchronize()
         del src, dst
-    ms_step, wall_ms = lb.time_loop(lb.step, args.steps, args.warmup)
-    tokens_s = M / (ms_step * 1e-3)
-    layer_bytes = rf.layer_bytes(M, cfg.hidden, cfg.n_qkv, cfg.inter)
-    layer_flops = rf.layer_flops(M, cfg.hidden, cfg.n_qkv, cfg.inter)
-
-    ops = {}
-    for name in ("rmsnorm_qkv", "rmsnorm_qkv_rope", "o_proj", "gate_up", "down", "swiglu_mlp", "o_proj_residual",
-                 "rmsnorm_swiglu_mlp_residual"):
-        ms, _ = lb.time_loop(lambda i, n=name: lb.op(n, i), max(20, args.steps // 2), max(5, args.warmup // 2))
-        b, f = op_bytes_flops(cfg, M, name)
-        ops[name] = {"us": round(ms * 1e3, 2), "GBps": round(b / (ms * 1e-3) / 1e9, 1),
-                     "TFLOPs": round(f / (ms * 1e-3) / 1e12, 2)}
-
-    # roofline of the dominant kernel: the gate/up projection with the fused SiLU*up epilogue
-    gu_ms = ops["gate_up"]["us"] * 1e-3
-    gu_bytes, gu_flops = op_bytes_flops(cfg, M, "gate_up")
-    if decode:
-        fam = thi.thi_query_kernel_family(M, cfg.inter, cfg.hidden, 2)
-        roof = {"bound": "hbm",
-                "kernel": f"gate_up ({ {3: 'skinny_rowslab', 4: 'skinny_rowblock'}.get(fam, 'skinny_streamk') }, SwiGLU epilogue)",
-                "achieved": round(gu_bytes / (gu_ms * 1e-3) / 1e9, 1), "peak": rf.MI355X_HBM_GBS, "unit": "GB/s",
-                "traffic": None}
-    else:
-        roof = {"bound": "mfma", "kernel": "gate_up (gemm, SwiGLU epilogue)",
-                "achieved": round(gu_flops / (gu_ms * 1e-3) / 1e12, 2), "peak": rf.MI355X_FP16_TFLOPS,
-                "unit": "TFLOP/s", "traffic": None}
-    # HBM traffic of the dominant kernel per launch comes from separate rocprofv3 --pmc runs of this same
-    # command (FETCH_SIZE, WRITE_SIZE, scaled by the --calib-copy kernel).  For the two profiled workloads
-    # the committed figures are used unless --traffic-kib gives fresher ones.
-    traffic_kib, traffic_src = args.traffic_kib, "--traffic-kib"
-    if traffic_kib is None and (args.config, M) in MEASURED_TRAFFIC_KIB:
-        traffic_kib, traffic_src = MEASURED_TRAFFIC_KIB[(args.config, M)]
-    if traffic_kib is not None:
-        # HBM bytes per launch (reads + writes); the parts and where they come from next to it
-        roof["traffic"] = (traffic_kib[0] + traffic_kib[1]) * 1024
-        roof["traffic_detail"] = {"fetch_bytes": traffic_kib[0] * 1024, "write_bytes": traffic_kib[1] * 1024,
-                                  "algorithmic_bytes": gu_bytes, "source": traffic_src}
-    roof["frac"] = round(roof["achieved"] / roof["peak"], 4)
-    roof["launch_us"] = ops["gate_up"]["us"]
+    all_ops = ("rmsnorm_qkv", "rmsnorm_qkv_rope", "o_proj", "gate_up", "down", "swiglu_mlp", "o_proj_residual",
+               "rmsnorm_swiglu_mlp_residual")
+    lb, head, gu_bytes = measure_layer(cfg, M, args, host_layer, per_block, warmup, all_ops, args.traffic_kib)
+    roof = head["roofline"]
 
     out = {
         "metric": "decode layer tokens/s" if decode else "prefill layer tokens/s",
-        "value": round(tokens_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": head["tokens_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16 storage, f32 accumulate", "data": "synthetic (seeded random fp16 weights/activations, Llama shapes)",
-        "config": {"workload": f"{cfg.name} decoder-layer linear ops (rmsnorm_qkv + o_proj + swiglu_mlp), "
-                               f"{'decode' if decode else 'prefill'} M={M}",
+        "config": {"workload": workload_name(cfg, M),
                    "hidden": cfg.hidden, "n_qkv": cfg.n_qkv, "intermediate": cfg.inter, "M": M,
-                   "weight_copies_rotated": lb.copies},
-        "layer_GBps": round(layer_bytes / (ms_step * 1e-3) / 1e9, 1),
-        "layer_hbm_frac": round(layer_bytes / (ms_step * 1e-3) / 1e9 / rf.MI355X_HBM_GBS, 4),
-        "layer_TFLOPs": round(layer_flops / (ms_step * 1e-3) / 1e12, 2),
-        "layer_mfma_frac": round(layer_flops / (ms_step * 1e-3) / 1e12 / rf.MI355X_FP16_TFLOPS, 4),
-        "host_wall_ms_per_step": round(wall_ms, 5),
-        "ops": ops,
+                   "weight_copies_rotated": head["weight_copies_rotated"]},
+        "timing": {"blocks": BLOCKS, "launches_per_block": per_block, "warmup_launches": warmup,
+                   "reported": "median of the blocks; HIP events on the launch stream",
+                   "ms_per_step_blocks": head["ms_per_step_blocks"]},
+        "layer_GBps": head["layer_GBps"],
+        "layer_hbm_frac": head["layer_hbm_frac"],
+        "layer_TFLOPs": head["layer_TFLOPs"],
+        "layer_mfma_frac": head["layer_mfma_frac"],
+        "host_wall_ms_per_step": head["host_wall_ms_per_step"],
+        "ops": head["ops"],
         "roofline": roof,
     }
 
@@ -333,30 +394,47 @@ def main():
         la = torch.full((M,), S, dtype=torch.int32, device="cuda")
         oa = torch.empty((M, Hq, D), dtype=torch.float16, device="cuda")
         wa = thi.Workspace(thi.thi_attention_workspace_bytes(M, Hq, Hkv, D, S), init=False)
-        ms, _ = lb.time_loop(lambda i: thi.thi_decode_attention(qa, ka, va, la, D ** -0.5, oa, wa),
-                             max(20, args.steps // 2), max(5, args.warmup // 2))
+        ms, _, _ = lb.time_loop(lambda i: thi.thi_decode_attention(qa, ka, va, la, D ** -0.5, oa, wa), MIN_PER_BLOCK, 5)
         kv_bytes = 2.0 * M * Hkv * S * D * 2
         out["decode_attention"] = {"context": S, "q_heads": Hq, "kv_heads": Hkv, "head_dim": D, "us": round(ms * 1e3, 2),
                                    "GBps": round(kv_bytes / (ms * 1e-3) / 1e9, 1),
                                    "hbm_frac": round(kv_bytes / (ms * 1e-3) / 1e9 / rf.MI355X_HBM_GBS, 4)}
         del qa, ka, va, oa, wa
+    del lb
+    torch.cuda.empty_cache()
+
+    # The prefill half of the metric: TFLOP/s against the fp16 MFMA peak, per layer step and for the dominant
+    # kernel, on the largest prefill workload (70B-shaped, M = 2048) and the hardest one (13B-shaped, M = 512).
+    if decode and not args.no_prefill:
+        legs = []
+        for ci, m in ((5, 2048), (3, 512)):
+            c2 = synth.CONFIGS[ci]
+            lb2, part, _ = measure_layer(c2, m, args, None, MIN_PER_BLOCK, 10,
+                                         ("rmsnorm_qkv", "o_proj", "gate_up", "down", "swiglu_mlp"))
+            del lb2
+            torch.cuda.empty_cache()
+            legs.append({"workload": workload_name(c2, m), "metric": "prefill TFLOP/s vs fp16 MFMA peak",
+                         "value": part["layer_TFLOPs"], "unit": "TFLOP/s", "frac_of_peak": part["layer_mfma_frac"],
+                         "timing": {"blocks": BLOCKS, "launches_per_block": MIN_PER_BLOCK}, **part})
+            print(f"# prefill {c2.name} M={m}: {part['ms_per_step']} ms/step, {part['layer_TFLOPs']} TFLOP/s", file=sys.stderr,
+                  flush=True)
+        out["prefill"] = legs
 
     if args.sweep:
         extra = {}
-        for ci, m in ((2, 1), (2, 8), (3, 16), (3, 512), (5, 1), (5, 32), (4, 1024), (5, 2048)):
+        for ci, m in ((2, 1), (2, 8), (3, 16), (3, 512), (5, 1), (5, 32), (4, 32), (4, 1024), (4, 2048), (5, 2048)):
             if (ci, m) == (args.config, M):
                 continue
             c2 = synth.CONFIGS[ci]
-            del lb
             torch.cuda.empty_cache()
             lb = LayerBench(c2, m, args.rotate_bytes, None)
-            steps = max(50, min(args.steps, int(2e11 / (2.0 * m * c2.weight_elems + 2e8))))
-            ms, _ = lb.time_loop(lb.step, steps, 20)        # clocks ramp under load: warm up properly
+            ms, _, _ = lb.time_loop(lb.step, MIN_PER_BLOCK, 20)        # clocks ramp under load: warm up properly
             extra[f"{c2.name}/M={m}"] = {
                 "ms_per_step": round(ms, 4), "tokens_s": round(m / (ms * 1e-3), 1),
                 "GBps": round(rf.layer_bytes(m, c2.hidden, c2.n_qkv, c2.inter) / (ms * 1e-3) / 1e9, 1),
                 "TFLOPs": round(rf.layer_flops(m, c2.hidden, c2.n_qkv, c2.inter) / (ms * 1e-3) / 1e12, 2)}
             print(f"# sweep {c2.name} M={m}: {extra[f'{c2.name}/M={m}']}", file=sys.stderr, flush=True)
+            del lb
         out["sweep"] = extra
 
     out["ceilings"] = measure_ceilings(gu_bytes if decode else None)
@@ -365,6 +443,10 @@ def main():
     roof["frac_of_attainable"] = round(roof["achieved"] / roof["attainable"], 4)
     if decode:      # against a kernel that only reads the same bytes, launch included
         roof["frac_of_read_only_kernel"] = round(out["ceilings"]["hbm_stream_read_same_bytes"]["us"] / roof["launch_us"], 4)
+    for leg in out.get("prefill", []):      # the register-only MFMA probe beside each prefill roofline
+        r2 = leg["roofline"]
+        r2["attainable"] = out["ceilings"]["mfma_f16_random_operands_TFLOPs"]
+        r2["frac_of_attainable"] = round(r2["achieved"] / r2["attainable"], 4)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, M, host_layer)
     print(json.dumps(out), flush=True)

@@ -22,11 +22,13 @@
  *     Every call leaves the workspace ready for the next call.  One workspace
  *     must not be used by two calls that may run concurrently.  The decode
  *     kernels (M <= 64) hand partial results from workgroup to workgroup inside
- *     one launch of one workgroup per compute unit; the waits are bounded, so a
- *     launch always terminates, but if the GPU is shared so heavily that a wait
- *     runs out, the last 32-bit word of the first 64 KiB of the workspace is set
- *     to 1 and the outputs of that call are undefined (re-initialise the
- *     workspace).  This cannot happen on a GPU the process has to itself.
+ *     one launch of one workgroup per compute unit, which assumes that all of
+ *     them are resident together (true on a GPU the process has to itself); the
+ *     waits are bounded, so a launch always terminates, but if the GPU is shared
+ *     so heavily (another stream or process, a compute-unit mask) that a wait
+ *     runs out, the outputs of that call are undefined and the workspace's
+ *     time-out marker is set: thi_workspace_status() reports it as
+ *     THI_ERR_TIMEOUT until the workspace is re-initialised.
  *   - Execution: work is enqueued on `hip_stream` (a hipStream_t passed as
  *     void*, NULL = the default stream); the call returns without
  *     synchronising.  Results are bitwise reproducible from run to run.
@@ -49,7 +51,8 @@ typedef enum {
     THI_ERR_SHAPE = 2,     /* non-positive extent, or K/H/I not a multiple of 8 */
     THI_ERR_ALIGN = 3,     /* a pointer is not 16-byte (workspace: 256-byte) aligned */
     THI_ERR_WORKSPACE = 4, /* workspace smaller than thi_workspace_bytes() */
-    THI_ERR_HIP = 5        /* the HIP runtime refused a launch */
+    THI_ERR_HIP = 5,       /* the HIP runtime refused a launch */
+    THI_ERR_TIMEOUT = 6    /* thi_workspace_status: a hand-over between workgroups ran out of time */
 } thi_status;
 
 typedef enum {
@@ -67,8 +70,11 @@ typedef enum {
  *   out[m,n] = sum_k ( x[m,k] * r[m] * gamma[k] ) * w_qkv[n,k]
  *
  * x [M,K], gamma [K], w_qkv [N,K] (rows of Wq, Wk, Wv stacked; grouped-query
- * attention only changes N), out [M,N]; all fp16 device memory.  The
- * normalised activations are never written to HBM.
+ * attention only changes N), out [M,N]; all fp16 device memory.  Up to 64
+ * tokens the normalised activations are never written to memory (the decode
+ * kernels scale x by gamma on its way to the matrix cores and apply r[m] to the
+ * accumulator); where the GEMM kernels run (M > 64, some shapes from 33) a
+ * small pass of its own writes them to the workspace once, as fp16.
  */
 int thi_rmsnorm_qkv(const void* x, const void* gamma, float eps, const void* w_qkv,
                     void* out, int M, int N, int K,
@@ -170,7 +176,9 @@ int thi_rmsnorm_swiglu_mlp(const void* x, const void* gamma, float eps, const vo
  * the current token's key and value.  D is 64 or 128, Hq a multiple of Hkv (THI_ERR_SHAPE
  * otherwise).  scale is usually 1/sqrt(D).  Scores, weights and sums are fp32; one fp16 rounding
  * at the end.  Workspace: thi_attention_workspace_bytes(), 256-byte aligned, no preparation
- * needed, may be the workspace of the other calls if large enough.  Reproducible bit for bit.
+ * needed; it may be the (prepared) workspace of the other calls if large enough: the partial results
+ * lie behind the status words and hand-over slots of those calls, which are left untouched.
+ * Reproducible bit for bit.
  */
 size_t thi_attention_workspace_bytes(int B, int Hq, int Hkv, int D, int S_max);
 int thi_decode_attention(const void* q, const void* k_cache, const void* v_cache, const int* seq_lens, float scale,
@@ -181,6 +189,12 @@ int thi_decode_attention(const void* q, const void* k_cache, const void* v_cache
  * Bytes of workspace the given operator needs for the given shape
  * (op = thi_op; (M, N, K) for the first two operators, (M, H, I) for the MLP).
  * Pure host arithmetic: touches no device.  Returns 0 for invalid arguments.
+ * Up to 32 tokens (the decode kernels) this is the fixed part -- 64 KiB of status
+ * words and about 17 MiB of hand-over slots -- plus M*I*2 bytes for the MLP;
+ * above, 256 MiB for the GEMM kernels' partial tiles and the buffers of the
+ * prefill path are added (also below 33 tokens while thi_set_kernel_family(2) is
+ * in force).  A call whose kernel needs the larger layout on a workspace that
+ * lacks it returns THI_ERR_WORKSPACE.
  */
 size_t thi_workspace_bytes(int op, int M, int N_or_H, int K_or_I);
 
@@ -189,10 +203,19 @@ size_t thi_workspace_bytes(int op, int M, int N_or_H, int K_or_I);
  * enqueues a small fill kernel on `hip_stream` that zeroes the status words
  * (hand-over flags, arrival counters) the split-K reductions use.
  * `workspace_bytes` must be what thi_workspace_bytes() returned (at least its
- * fixed part, about 18 MiB; THI_ERR_WORKSPACE otherwise).  Needed once per
+ * fixed part, about 17 MiB; THI_ERR_WORKSPACE otherwise).  Needed once per
  * allocation (and again only if a call on that workspace was aborted half-way).
  */
 int thi_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Has a hand-over between workgroups timed out on this workspace since it was
+ * last initialised (see the workspace conventions above)?  Copies the marker
+ * word to the host behind everything enqueued on `hip_stream` and WAITS for that
+ * stream.  Returns THI_OK, THI_ERR_TIMEOUT (the outputs of some earlier call on
+ * this workspace are undefined; re-initialise it), or an argument / HIP error.
+ */
+int thi_workspace_status(const void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Human-readable name of a thi_status value (static storage). */
 const char* thi_status_string(int status);
@@ -201,6 +224,11 @@ const char* thi_status_string(int status);
 int thi_version(void);
 
 /*
+ * The three thi_set_* / thi_debug_* switches below are PROCESS-GLOBAL
+ * diagnostics (atomics read by every later call of any thread); they are not
+ * needed for normal use and are not meant to be toggled while calls are in
+ * flight on other threads.
+ *
  * Tuning/diagnostic hook used by the benchmark and tests: force a kernel
  * family for subsequent calls from this process.  family: 0 = automatic
  * (default: a decode kernel up to 32 tokens, the stream-K decode kernel or the
@@ -223,6 +251,15 @@ int thi_set_kernel_family(int family);
  * 16 rows per block), else as 1.  Returns the previous setting.
  */
 int thi_set_rowblock_split(int split);
+
+/*
+ * Test hook for the time-out path of the stream-K decode kernel's hand-over:
+ * spin_limit = polls of a contributor's flag before the finishing workgroup
+ * gives up (0 = the default, 2^24); withhold_flags != 0 makes the contributors
+ * keep their flags down, so that the give-up is certain and every kernel still
+ * exits normally.  Returns THI_OK.
+ */
+int thi_debug_handover(unsigned spin_limit, int withhold_flags);
 
 /*
  * Diagnostic: the kernel family (numbered as above, never 0 for valid arguments)

@@ -137,6 +137,24 @@ def swiglu_mlp(x: np.ndarray, wg: np.ndarray, wu: np.ndarray, wd: np.ndarray, re
     return (y, s, h) if return_h else (y, s)
 
 
+def swiglu_gate_up(x: np.ndarray, wg: np.ndarray, wu: np.ndarray):
+    """h = silu(x wg^T) * (x wu^T) in fp64 (Sec. III-C.1: the low-density operator behind the gate and up
+    projections) and the magnitude S_h that the tolerance 4e-3 * S is taken against for h.
+
+    g = x wg^T and u = x wu^T are two calls of the linear operator, with their magnitude sums S_g, S_u.
+    h is not a plain sum of products, so S_h is the first-order image of (S_g, S_u) under
+    h(g, u) = silu(g) u:   S_h = |silu'(g) u| S_g + |silu(g)| S_u,   silu'(g) = s (1 + g (1 - s)),
+    s = 1 / (1 + exp(-g)) -- an error of eps*S_g in g and eps*S_u in u moves h by eps*S_h to first order."""
+    g, sg = linear(x, wg)
+    u, su = linear(x, wu)
+    sig = 1.0 / (1.0 + np.exp(-g))
+    silu_g = g * sig
+    dsilu = sig * (1.0 + g * (1.0 - sig))
+    h = silu_g * u
+    s = np.abs(dsilu * u) * sg + np.abs(silu_g) * su
+    return h, s
+
+
 def linear_residual(x: np.ndarray, w: np.ndarray, res: np.ndarray):
     """y = res + x w^T and S = |res| + sum_k |x w|, in fp64."""
     M, K = x.shape

@@ -11,6 +11,8 @@ import ctypes
 import os
 
 THI_OK = 0
+THI_ERR_WORKSPACE = 4
+THI_ERR_TIMEOUT = 6
 THI_OP_RMSNORM_QKV, THI_OP_LINEAR, THI_OP_SWIGLU_MLP = 0, 1, 2
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -21,7 +23,7 @@ EXPORTED_SYMBOLS = (
     "thi_rmsnorm_qkv", "thi_rmsnorm_qkv_rope", "thi_linear", "thi_swiglu_mlp", "thi_swiglu_gate_up",
     "thi_linear_residual", "thi_rmsnorm_swiglu_mlp", "thi_decode_attention", "thi_attention_workspace_bytes",
     "thi_workspace_bytes",
-    "thi_workspace_init", "thi_status_string", "thi_version", "thi_set_kernel_family", "thi_set_rowblock_split", "thi_query_kernel_family",
+    "thi_workspace_init", "thi_workspace_status", "thi_debug_handover", "thi_status_string", "thi_version", "thi_set_kernel_family", "thi_set_rowblock_split", "thi_query_kernel_family",
     "thi_probe_stream_read", "thi_probe_mfma_f16",
 )
 
@@ -72,6 +74,10 @@ def load_library():
     lib.thi_workspace_bytes.restype = sz
     lib.thi_workspace_init.argtypes = [vp, sz, vp]
     lib.thi_workspace_init.restype = ci
+    lib.thi_workspace_status.argtypes = [vp, sz, vp]
+    lib.thi_workspace_status.restype = ci
+    lib.thi_debug_handover.argtypes = [ctypes.c_uint, ci]
+    lib.thi_debug_handover.restype = ci
     lib.thi_status_string.argtypes = [ci]
     lib.thi_status_string.restype = ctypes.c_char_p
     lib.thi_version.argtypes = []
@@ -142,6 +148,9 @@ class Workspace:
         if init:
             thi_workspace_init(self.ptr, self.nbytes, stream)
 
+    def reinit(self, stream=None) -> None:
+        thi_workspace_init(self.ptr, self.nbytes, stream)
+
     @classmethod
     def for_ops(cls, shapes, device="cuda", stream=None):
         """shapes: iterable of (op, M, N_or_H, K_or_I); sized for the largest."""
@@ -160,6 +169,17 @@ def thi_workspace_init(ptr: int, nbytes: int, stream=None) -> None:
     rc = load_library().thi_workspace_init(ctypes.c_void_p(int(ptr)), int(nbytes), _stream(stream))
     if rc != THI_OK:
         raise ThiError(rc, "thi_workspace_init")
+
+
+def thi_workspace_status(workspace, stream=None) -> int:
+    """THI_OK, or THI_ERR_TIMEOUT if a hand-over timed out on this workspace since its last init (waits for the stream)."""
+    wp, wb = _ws(workspace)
+    return int(load_library().thi_workspace_status(wp, wb, _stream(stream)))
+
+
+def thi_debug_handover(spin_limit: int, withhold_flags: bool) -> None:
+    """Test hook: force the stream-K hand-over's bounded wait to run out (0, False restores the defaults)."""
+    load_library().thi_debug_handover(int(spin_limit), int(bool(withhold_flags)))
 
 
 def thi_rmsnorm_qkv(x, gamma, eps: float, w_qkv, out, workspace, stream=None, check: bool = True) -> int:

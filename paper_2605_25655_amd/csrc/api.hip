@@ -16,6 +16,8 @@ constexpr int SKINNY_MAX_M = 32;          // automatic dispatch: M <= this -> sk
 
 std::atomic<int> g_family{0};
 std::atomic<int> g_rowblock_split{0};      // 0: chosen per call; >= 1: forced where the shape admits it
+std::atomic<unsigned> g_spin_limit{SK_SPIN_LIMIT};   // polls of a hand-over flag before a workgroup gives up
+std::atomic<int> g_withhold_flags{0};      // test hook: contributors never raise their flags
 
 int device_cu_count()
 {
@@ -37,40 +39,59 @@ inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Workspace {
     unsigned* counters;
     unsigned* handover;
-    float* partials;
+    float* partials;  // GEMM kernels: partial accumulator tiles; nullptr when the workspace was sized for decode only
     uint16_t* h;     // MLP: silu(gate)*up [M,I]
-    uint16_t* xn;    // prefill: normalised activations [M,K] of the RMSNorm-fronted operators
+    uint16_t* xn;    // prefill: normalised activations [M,K] of the RMSNorm-fronted operators (with the GEMM region only)
     float* rope_cs;  // prefill, QKV with the rotary epilogue: (cos, sin) table [M][head_dim/2][2], behind xn
 };
 
-// Both kernel families keep their own regions (either may be forced for any M).
+// The decode kernels' part: status words, then the hand-over slots.  Decode attention puts its partial
+// results behind it, so that a workspace shared with the other calls keeps its status words.
 size_t fixed_bytes() { return WS_COUNTER_BYTES + round_up(skinny_handover_bytes(), 256); }
 
-// (op, M, a, b) = (RMSNORM_QKV or LINEAR, M, N, K) or (SWIGLU_MLP, M, H, I)
-size_t h_bytes(int op, int M, int b) { return op == THI_OP_SWIGLU_MLP ? round_up((size_t)M * (size_t)b * 2, 256) : 0; }
-size_t xn_bytes(int op, int M, int a, int b)
+// The GEMM kernels run above SKINNY_MAX_M tokens (or when they are forced): only then does a workspace
+// carry their partial-tile region and the normalised activations of the RMSNorm pass.
+bool gemm_possible(int M) { return M > SKINNY_MAX_M || g_family.load(std::memory_order_relaxed) == 2; }
+
+// (op, M, a, b) = (RMSNORM_QKV or LINEAR, M, N, K) or (SWIGLU_MLP, M, H, I); byte offsets from the base
+struct Layout {
+    size_t partials, h, xn, rope_cs, total;
+};
+Layout layout(int op, int M, int a, int b, bool gemm)
 {
-    if (op == THI_OP_RMSNORM_QKV)      // [M,K], then the rotary table [M][<= 128][2] fp32
-        return round_up((size_t)M * (size_t)b * 2, 256) + (size_t)M * (ROPE_TABLE_MAX_HEAD_DIM / 2) * 8;
-    if (op == THI_OP_SWIGLU_MLP) return round_up((size_t)M * (size_t)a * 2, 256);      // [M,H]
-    return 0;
+    Layout l;
+    l.partials = fixed_bytes();
+    l.h = l.partials + (gemm ? gemm_partial_bytes() : 0);
+    l.xn = l.h + (op == THI_OP_SWIGLU_MLP ? round_up((size_t)M * (size_t)b * 2, 256) : 0);
+    size_t xn = 0, cs = 0;
+    if (gemm && op == THI_OP_RMSNORM_QKV) {      // [M,K], then the rotary table [M][<= 128][2] fp32
+        xn = round_up((size_t)M * (size_t)b * 2, 256);
+        cs = (size_t)M * (ROPE_TABLE_MAX_HEAD_DIM / 2) * 8;
+    } else if (gemm && op == THI_OP_SWIGLU_MLP) {
+        xn = round_up((size_t)M * (size_t)a * 2, 256);      // [M,H]
+    }
+    l.rope_cs = l.xn + xn;
+    l.total = l.rope_cs + cs;
+    return l;
 }
 
-size_t workspace_need(int op, int M, int a, int b)
-{
-    return fixed_bytes() + gemm_partial_bytes() + h_bytes(op, M, b) + xn_bytes(op, M, a, b);
-}
+size_t workspace_need(int op, int M, int a, int b) { return layout(op, M, a, b, gemm_possible(M)).total; }
 
-Workspace carve(void* base, size_t h_size = 0, size_t xn_size = 0)
+// A workspace large enough for the GEMM layout is carved that way (so one sized while the GEMM kernels were
+// forced keeps working afterwards); a smaller one holds the decode layout.
+Workspace carve(void* base, size_t bytes, int op, int M, int a, int b)
 {
+    const Layout with = layout(op, M, a, b, true);
+    const bool gemm = bytes >= with.total;
+    const Layout l = gemm ? with : layout(op, M, a, b, false);
     char* p = static_cast<char*>(base);
     Workspace w;
     w.counters = reinterpret_cast<unsigned*>(p);
     w.handover = reinterpret_cast<unsigned*>(p + WS_COUNTER_BYTES);
-    w.partials = reinterpret_cast<float*>(p + fixed_bytes());
-    w.h = reinterpret_cast<uint16_t*>(p + fixed_bytes() + gemm_partial_bytes());
-    w.xn = reinterpret_cast<uint16_t*>(p + fixed_bytes() + gemm_partial_bytes() + h_size);
-    w.rope_cs = reinterpret_cast<float*>(p + fixed_bytes() + gemm_partial_bytes() + h_size + xn_size);
+    w.partials = gemm ? reinterpret_cast<float*>(p + l.partials) : nullptr;
+    w.h = reinterpret_cast<uint16_t*>(p + l.h);
+    w.xn = reinterpret_cast<uint16_t*>(p + l.xn);
+    w.rope_cs = reinterpret_cast<float*>(p + l.rope_cs);
     return w;
 }
 
@@ -226,6 +247,8 @@ int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const ui
             a.kchunks = (K + SK_KC - 1) / SK_KC;
             a.eps = eps;
             a.rope = rope;
+            a.spin_limit = g_spin_limit.load(std::memory_order_relaxed);
+            a.withhold_flags = g_withhold_flags.load(std::memory_order_relaxed);
             if (rope.pos) a.rope.pos = rope.pos + m0;
             hipError_t e;
             if (!slab) e = launch_skinny(a, epilogue, cus, stream);
@@ -235,6 +258,7 @@ int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const ui
         }
         return THI_OK;
     }
+    if (!ws.partials) return THI_ERR_WORKSPACE;      // sized for the decode kernels only (see thi_workspace_bytes)
     {
         const long tn = (N + 63) / 64, tm = (M + 127) / 128;     // upper bound on tiles of any configuration
         if (tn * tm > WS_MAX_COUNTERS) return THI_ERR_SHAPE;
@@ -289,7 +313,7 @@ int thi_rmsnorm_qkv(const void* x, const void* gamma, float eps, const void* w_q
     int rc = check_common(M, N, K, workspace, workspace_bytes, workspace_need(THI_OP_RMSNORM_QKV, M, N, K));
     if (rc != THI_OK) return rc;
     if (misaligned(x, 16) || misaligned(gamma, 16) || misaligned(w_qkv, 16) || misaligned(out, 16)) return THI_ERR_ALIGN;
-    Workspace ws = carve(workspace);
+    Workspace ws = carve(workspace, workspace_bytes, THI_OP_RMSNORM_QKV, M, N, K);
     return run_projection((const uint16_t*)x, (const uint16_t*)gamma, eps, (const uint16_t*)w_qkv, nullptr,
                           (uint16_t*)out, M, N, K, N, EPI_RMSNORM, ws, (hipStream_t)hip_stream);
 }
@@ -305,7 +329,7 @@ int thi_rmsnorm_qkv_rope(const void* x, const void* gamma, float eps, const void
     if (misaligned(x, 16) || misaligned(gamma, 16) || misaligned(w_qkv, 16) || misaligned(out, 16) ||
         misaligned(positions, 4) || misaligned(theta, 4))
         return THI_ERR_ALIGN;
-    Workspace ws = carve(workspace, 0, round_up((size_t)M * (size_t)K * 2, 256));
+    Workspace ws = carve(workspace, workspace_bytes, THI_OP_RMSNORM_QKV, M, N, K);
     return run_projection((const uint16_t*)x, (const uint16_t*)gamma, eps, (const uint16_t*)w_qkv, nullptr,
                           (uint16_t*)out, M, N, K, N, EPI_RMSNORM_ROPE, ws, (hipStream_t)hip_stream,
                           RopeArgs{positions, theta, n_rot, head_dim, nullptr});
@@ -318,7 +342,7 @@ int thi_linear(const void* x, const void* w, void* out, int M, int N, int K,
     int rc = check_common(M, N, K, workspace, workspace_bytes, workspace_need(THI_OP_LINEAR, M, N, K));
     if (rc != THI_OK) return rc;
     if (misaligned(x, 16) || misaligned(w, 16) || misaligned(out, 16)) return THI_ERR_ALIGN;
-    Workspace ws = carve(workspace);
+    Workspace ws = carve(workspace, workspace_bytes, THI_OP_LINEAR, M, N, K);
     return run_projection((const uint16_t*)x, nullptr, 0.f, (const uint16_t*)w, nullptr, (uint16_t*)out,
                           M, N, K, N, EPI_PLAIN, ws, (hipStream_t)hip_stream);
 }
@@ -333,7 +357,7 @@ int thi_swiglu_mlp(const void* x, const void* w_gate, const void* w_up, const vo
     if (misaligned(x, 16) || misaligned(w_gate, 16) || misaligned(w_up, 16) || misaligned(w_down, 16) ||
         misaligned(out, 16))
         return THI_ERR_ALIGN;
-    Workspace ws = carve(workspace, h_bytes(THI_OP_SWIGLU_MLP, M, I));
+    Workspace ws = carve(workspace, workspace_bytes, THI_OP_SWIGLU_MLP, M, H, I);
     hipStream_t stream = (hipStream_t)hip_stream;
     rc = run_projection((const uint16_t*)x, nullptr, 0.f, (const uint16_t*)w_gate, (const uint16_t*)w_up, ws.h,
                         M, I, H, I, EPI_SWIGLU, ws, stream);
@@ -350,7 +374,7 @@ int thi_swiglu_gate_up(const void* x, const void* w_gate, const void* w_up, void
     int rc = check_common(M, H, H, workspace, workspace_bytes, workspace_need(THI_OP_SWIGLU_MLP, M, H, I));
     if (rc != THI_OK) return rc;
     if (misaligned(x, 16) || misaligned(w_gate, 16) || misaligned(w_up, 16) || misaligned(h, 16)) return THI_ERR_ALIGN;
-    Workspace ws = carve(workspace);
+    Workspace ws = carve(workspace, workspace_bytes, THI_OP_SWIGLU_MLP, M, H, I);
     return run_projection((const uint16_t*)x, nullptr, 0.f, (const uint16_t*)w_gate, (const uint16_t*)w_up,
                           (uint16_t*)h, M, I, H, I, EPI_SWIGLU, ws, (hipStream_t)hip_stream);
 }
@@ -362,7 +386,7 @@ int thi_linear_residual(const void* x, const void* w, const void* residual, void
     int rc = check_common(M, N, K, workspace, workspace_bytes, workspace_need(THI_OP_LINEAR, M, N, K));
     if (rc != THI_OK) return rc;
     if (misaligned(x, 16) || misaligned(w, 16) || misaligned(residual, 16) || misaligned(out, 16)) return THI_ERR_ALIGN;
-    Workspace ws = carve(workspace);
+    Workspace ws = carve(workspace, workspace_bytes, THI_OP_LINEAR, M, N, K);
     return run_projection((const uint16_t*)x, nullptr, 0.f, (const uint16_t*)w, nullptr, (uint16_t*)out,
                           M, N, K, N, EPI_PLAIN, ws, (hipStream_t)hip_stream, RopeArgs{nullptr, nullptr, 0, 2, nullptr},
                           (const uint16_t*)residual);
@@ -379,7 +403,7 @@ int thi_rmsnorm_swiglu_mlp(const void* x, const void* gamma, float eps, const vo
     if (misaligned(x, 16) || misaligned(gamma, 16) || misaligned(w_gate, 16) || misaligned(w_up, 16) ||
         misaligned(w_down, 16) || misaligned(out, 16) || (residual && misaligned(residual, 16)))
         return THI_ERR_ALIGN;
-    Workspace ws = carve(workspace, h_bytes(THI_OP_SWIGLU_MLP, M, I));
+    Workspace ws = carve(workspace, workspace_bytes, THI_OP_SWIGLU_MLP, M, H, I);
     hipStream_t stream = (hipStream_t)hip_stream;
     rc = run_projection((const uint16_t*)x, (const uint16_t*)gamma, eps, (const uint16_t*)w_gate,
                         (const uint16_t*)w_up, ws.h, M, I, H, I, EPI_RMSNORM_SWIGLU, ws, stream);
@@ -391,7 +415,7 @@ int thi_rmsnorm_swiglu_mlp(const void* x, const void* gamma, float eps, const vo
 size_t thi_attention_workspace_bytes(int B, int Hq, int Hkv, int D, int S_max)
 {
     if (B < 1 || Hq < 1 || Hkv < 1 || S_max < 1 || (D != 64 && D != 128) || Hq % Hkv) return 0;
-    return round_up((size_t)B * Hq * AT_MAX_SPLIT * (D + 2) * sizeof(float), 256);
+    return fixed_bytes() + round_up((size_t)B * Hq * AT_MAX_SPLIT * (D + 2) * sizeof(float), 256);
 }
 
 int thi_decode_attention(const void* q, const void* k_cache, const void* v_cache, const int* seq_lens, float scale,
@@ -412,7 +436,8 @@ int thi_decode_attention(const void* q, const void* k_cache, const void* v_cache
     a.v = (const uint16_t*)v_cache;
     a.seq_lens = seq_lens;
     a.out = (uint16_t*)out;
-    a.part = (float*)workspace;
+    // behind the other calls' status words and hand-over slots: a shared workspace keeps them intact
+    a.part = reinterpret_cast<float*>(static_cast<char*>(workspace) + fixed_bytes());
     a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.D = D; a.S_max = S_max;
     a.group = Hq / Hkv;
     // cut along the positions only as far as it takes to give every compute unit a workgroup: more,
@@ -451,6 +476,27 @@ int thi_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream
     return launch_fill_words(workspace, WS_COUNTER_BYTES, 0u, stream) == hipSuccess ? THI_OK : THI_ERR_HIP;
 }
 
+int thi_workspace_status(const void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!workspace) return THI_ERR_NULL;
+    if (misaligned(workspace, 256)) return THI_ERR_ALIGN;
+    if (workspace_bytes < fixed_bytes()) return THI_ERR_WORKSPACE;
+    (void)hipGetLastError();
+    hipStream_t stream = (hipStream_t)hip_stream;
+    unsigned marker = 0;
+    const unsigned* word = static_cast<const unsigned*>(workspace) + (WS_MAX_COUNTERS - 1);
+    if (hipMemcpyAsync(&marker, word, sizeof(marker), hipMemcpyDeviceToHost, stream) != hipSuccess) return THI_ERR_HIP;
+    if (hipStreamSynchronize(stream) != hipSuccess) return THI_ERR_HIP;
+    return marker ? THI_ERR_TIMEOUT : THI_OK;
+}
+
+int thi_debug_handover(unsigned spin_limit, int withhold_flags)
+{
+    g_spin_limit.store(spin_limit ? spin_limit : SK_SPIN_LIMIT);
+    g_withhold_flags.store(withhold_flags ? 1 : 0);
+    return THI_OK;
+}
+
 const char* thi_status_string(int status)
 {
     switch (status) {
@@ -460,6 +506,7 @@ const char* thi_status_string(int status)
     case THI_ERR_ALIGN: return "THI_ERR_ALIGN: pointers must be 16-byte aligned (workspace 256-byte)";
     case THI_ERR_WORKSPACE: return "THI_ERR_WORKSPACE: workspace smaller than thi_workspace_bytes()";
     case THI_ERR_HIP: return "THI_ERR_HIP: kernel launch failed";
+    case THI_ERR_TIMEOUT: return "THI_ERR_TIMEOUT: a hand-over between workgroups timed out; results undefined, re-initialise the workspace";
     default: return "THI_ERR_UNKNOWN";
     }
 }

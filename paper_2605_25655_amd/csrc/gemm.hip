@@ -34,6 +34,8 @@
 // the workgroups running on it at that moment.
 #include "thi_internal.h"
 
+#include <mutex>
+
 namespace thi {
 
 namespace {
@@ -598,12 +600,11 @@ hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream
 #define THI_LAUNCH_K(E, KT)                                                                                  \
     do {                                                                                                     \
         auto kern = gemm_streamk<BN, BM, WN, WM, GK, NS, E, KT>;                                                    \
-        static bool attr_set = false;                                                                        \
-        if (!attr_set) {                                                                                     \
+        static std::once_flag attr_once;      /* one opt-in per kernel variant, safe from several threads */  \
+        std::call_once(attr_once, [&] {                                                                      \
             (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                   \
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                 \
-            attr_set = true;                                                                                 \
-        }                                                                                                    \
+        });                                                                                                  \
         hipLaunchKernelGGL(kern, g, b, lds, stream, a, tiles_m, ktiles, sk_tiles, parts);                    \
         if (sk_tiles > 0)                                                                                    \
             hipLaunchKernelGGL((gemm_fixup<BN, BM, WN, WM, E>), dim3(2 * sk_tiles * (BN / WN / 32) * (BM / WM / 32)), \

@@ -24,6 +24,7 @@
 // result does not depend on the order of arrival, and nobody waits for anybody.
 #include "thi_internal.h"
 
+#include <mutex>
 #include <type_traits>
 
 namespace thi {
@@ -423,8 +424,8 @@ hipError_t launch_t_mt(const SkinnyArgs& a, int epilogue, const RowBlockPlan& p,
     dim3 g(p.grid), b(SK_THREADS);
     const int per_wg = p.per_wg;
     const size_t gamma_lds = (size_t)SK_WAVES * gamma_pieces(a.K) * sizeof(uintx4);
-    static bool attr_set = false;       // static (+ dynamic) LDS passes 64 KiB: every variant needs the opt-in
-    if (!attr_set) {
+    static std::once_flag attr_once;    // static (+ dynamic) LDS passes 64 KiB: every variant needs the opt-in
+    std::call_once(attr_once, [] {
         // largest static part: ~90 KiB (T = 3 or 5 with two token tiles); with this it stays inside the 160 KiB of a CU
         const int most = (int)((size_t)SK_WAVES * gamma_pieces(ROWSLAB_MAX_K) * sizeof(uintx4));
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_PLAIN>),
@@ -439,8 +440,7 @@ hipError_t launch_t_mt(const SkinnyArgs& a, int epilogue, const RowBlockPlan& p,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, most);
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_RMSNORM_SWIGLU>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, most);
-        attr_set = true;
-    }
+    });
     if (p.ksplit > 1) {      // plain kind only (checked by the caller); the share count travels in kchunks
         SkinnyArgs s = a;
         s.kchunks = p.ksplit;

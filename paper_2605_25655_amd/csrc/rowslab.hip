@@ -16,6 +16,7 @@
 // there the hand-over between workgroups (several microseconds across the chip) is the larger loss.
 #include "thi_internal.h"
 
+#include <mutex>
 #include <type_traits>
 
 namespace thi {
@@ -301,8 +302,8 @@ hipError_t launch_mt(const SkinnyArgs& a, int epilogue, int grid, hipStream_t st
 {
     dim3 g(grid), b(SK_THREADS);
     const size_t gamma_lds = (size_t)SK_WAVES * rowslab_gamma_pieces(a.K) * sizeof(uintx4);
-    static bool attr_set = false;       // static + dynamic LDS can pass 64 KiB for large K
-    if (!attr_set) {
+    static std::once_flag attr_once;    // static + dynamic LDS can pass 64 KiB for large K
+    std::call_once(attr_once, [] {
         const int most = (int)((size_t)SK_WAVES * rowslab_gamma_pieces(ROWSLAB_MAX_K) * sizeof(uintx4));
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowslab<MT, EPI_RMSNORM, XT>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, most);
@@ -310,8 +311,7 @@ hipError_t launch_mt(const SkinnyArgs& a, int epilogue, int grid, hipStream_t st
                                   hipFuncAttributeMaxDynamicSharedMemorySize, most);
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowslab<MT, EPI_RMSNORM_SWIGLU, XT>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, most);
-        attr_set = true;
-    }
+    });
     switch (epilogue) {
     case EPI_PLAIN: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_PLAIN, XT>), g, b, 0, stream, a.x, a.w0, a.w1, a.gamma, a.M, a.N, a.K, a.tiles, a); break;
     case EPI_RMSNORM: hipLaunchKernelGGL((skinny_rowslab<MT, EPI_RMSNORM, XT>), g, b, gamma_lds, stream, a.x, a.w0, a.w1, a.gamma, a.M, a.N, a.K, a.tiles, a); break;

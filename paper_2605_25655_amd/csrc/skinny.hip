@@ -290,7 +290,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(const uint16_t* x_,
                 // fence alone does not wait for that); only then may the flag go up
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 __syncthreads();
-                if (tid == 0)
+                if (tid == 0 && !a.withhold_flags)
                     __hip_atomic_store(a.counters + wg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             } else {
                 if (wv == 0) {
@@ -306,7 +306,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_streamk(const uint16_t* x_,
                                 seen = __hip_atomic_load(a.counters + wc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
                             if (__builtin_amdgcn_ballot_w64(!seen) == 0ull) break;
                             __builtin_amdgcn_s_sleep(1);
-                            if (++spins > SK_SPIN_LIMIT) { ok = 0u; break; }      // bounded: every wave exits
+                            if (++spins > a.spin_limit) { ok = 0u; break; }      // bounded: every wave exits
                         }
                         if (mine && seen)
                             __hip_atomic_store(a.counters + wc, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -71,6 +71,8 @@ struct SkinnyArgs {
     int tiles, kchunks;      // tiles of SK_ROWS virtual rows; chunks of SK_KC along K
     float eps;
     RopeArgs rope;
+    unsigned spin_limit;     // stream-K: polls of a contributor's flag before the finishing workgroup gives up
+    int withhold_flags;      // stream-K, test hook: contributors do not raise their flags (forces the give-up)
 };
 
 size_t skinny_handover_bytes();

@@ -34,10 +34,13 @@ class Runner:
     def __init__(self, M: int, H: int, I: int, n_max: int):
         import paper_2605_25655_amd as thi
         self.thi = thi
+        # sized as for more than 32 tokens, so that the tests may force any kernel family (the GEMM kernels
+        # need their partial-tile region) on the same workspace at any M
+        Mw = max(M, 33)
         need = max(
-            thi.thi_workspace_bytes(0, M, n_max, max(H, I)),
-            thi.thi_workspace_bytes(1, M, n_max, max(H, I)),
-            thi.thi_workspace_bytes(2, M, H, I),
+            thi.thi_workspace_bytes(0, Mw, n_max, max(H, I)),
+            thi.thi_workspace_bytes(1, Mw, n_max, max(H, I)),
+            thi.thi_workspace_bytes(2, Mw, H, I),
         )
         self.ws = thi.Workspace(need)
 

@@ -35,7 +35,7 @@ def test_header_symbols_are_exported(lib):
 def test_version_and_status_strings(lib):
     assert lib.thi_version() >= 100
     assert lib.thi_status_string(0) == b"THI_OK"
-    for s in range(1, 6):
+    for s in range(1, 7):
         assert lib.thi_status_string(s).startswith(b"THI_ERR_")
     assert lib.thi_status_string(77) == b"THI_ERR_UNKNOWN"
 
@@ -48,6 +48,39 @@ def test_workspace_bytes_is_pure_and_monotone(lib):
     assert f(1, 32, 4096, 4096) >= a
     mlp1, mlp2 = f(2, 32, 4096, 11008), f(2, 2048, 4096, 11008)
     assert mlp2 - mlp1 >= (2048 - 32) * 11008 * 2      # h buffer grows with M*I
+
+
+def test_decode_workspace_is_small_and_gemm_needs_the_larger_one(lib):
+    """Up to 32 tokens a workspace holds the status words and hand-over slots only (plus h for the MLP);
+    the GEMM kernels' 256 MiB of partial tiles are added above, or while those kernels are forced -- and
+    a forced GEMM call on a decode-sized workspace is refused on the host."""
+    f = lib.thi_workspace_bytes
+    small = f(1, 32, 4096, 4096)
+    assert small < 20 << 20
+    assert f(2, 32, 4096, 11008) == small + 32 * 11008 * 2
+    assert f(1, 33, 4096, 4096) >= small + (256 << 20)
+    buf = ctypes.create_string_buffer(1 << 12)
+    p = ctypes.c_void_p((ctypes.addressof(buf) + 255) // 256 * 256)
+    null = ctypes.c_void_p(0)
+    prev = lib.thi_set_kernel_family(2)
+    try:
+        assert f(1, 32, 4096, 4096) >= small + (256 << 20)
+        assert lib.thi_linear(p, p, p, 32, 4096, 4096, p, small, null) == 4
+    finally:
+        lib.thi_set_kernel_family(prev)
+    # attention's workspace starts behind the other calls' status words and slots
+    assert lib.thi_attention_workspace_bytes(1, 32, 32, 128, 4096) > small - 32 * 4096 * 0
+
+
+def test_workspace_status_validates(lib):
+    null = ctypes.c_void_p(0)
+    buf = ctypes.create_string_buffer(1 << 12)
+    p = ctypes.c_void_p((ctypes.addressof(buf) + 255) // 256 * 256)
+    assert lib.thi_workspace_status(null, 1 << 30, null) == 1
+    assert lib.thi_workspace_status(ctypes.c_void_p(p.value + 4), 1 << 30, null) == 3
+    assert lib.thi_workspace_status(p, 1024, null) == 4
+    assert lib.thi_status_string(6).startswith(b"THI_ERR_TIMEOUT")
+    assert lib.thi_debug_handover(0, 0) == 0
 
 
 def test_argument_errors_return_codes_without_launching(lib):

@@ -270,6 +270,40 @@ def test_swiglu_gate_and_up_are_not_swapped(oracle_mod):
     assert y[0, 1] == 0.0
 
 
+def test_gate_up_alone_matches_the_mlp_oracle_and_its_magnitude_is_first_order(oracle_mod):
+    """h from swiglu_gate_up is the h the (pinned) MLP oracle forms; S_h is pinned three ways: the closed form
+    for selector weights, the derivative silu' against a central difference of the C silu, and the defining
+    property -- moving g by eps*S_g and u by eps*S_u (worst signs) moves h by eps*S_h to first order."""
+    rng = np.random.default_rng(21)
+    M, H, I = 4, 32, 40
+    x = f16(rng.standard_normal((M, H)))
+    wg, wu = f16(rng.standard_normal((I, H)) * 0.3), f16(rng.standard_normal((I, H)) * 0.3)
+    h, sh = oracle_mod.swiglu_gate_up(x, wg, wu)
+    _, _, h_mlp = oracle_mod.swiglu_mlp(x, wg, wu, np.zeros((H, I), np.float16), return_h=True)
+    np.testing.assert_allclose(h, h_mlp, rtol=1e-14, atol=1e-300)
+    g, sg = oracle_mod.linear(x, wg)
+    u, su = oracle_mod.linear(x, wu)
+    eps = 1e-7
+    silu = np.vectorize(oracle_mod.silu)
+    worst = np.zeros_like(h)
+    for dg in (-1, 1):
+        for du in (-1, 1):
+            hp = silu(g + dg * eps * sg) * (u + du * eps * su)
+            worst = np.maximum(worst, np.abs(hp - h))
+    np.testing.assert_allclose(worst, eps * sh, rtol=1e-4, atol=1e-18)
+    # selector weights: g = x[p], u = x[q], S_g = |x[p]|, S_u = |x[q]|
+    p_, q_ = rng.integers(0, H, I), rng.integers(0, H, I)
+    sel_g = np.zeros((I, H), np.float16); sel_g[np.arange(I), p_] = 1
+    sel_u = np.zeros((I, H), np.float16); sel_u[np.arange(I), q_] = 1
+    h2, s2 = oracle_mod.swiglu_gate_up(x, sel_g, sel_u)
+    xd = x.astype(np.float64)
+    gg, uu = xd[:, p_], xd[:, q_]
+    d = 1e-6
+    dsilu = (silu(gg + d) - silu(gg - d)) / (2 * d)
+    np.testing.assert_allclose(h2, silu(gg) * uu, rtol=1e-15)
+    np.testing.assert_allclose(s2, np.abs(dsilu * uu) * np.abs(gg) + np.abs(silu(gg)) * np.abs(uu), rtol=1e-8, atol=1e-12)
+
+
 def test_swiglu_composition_with_numpy_witness(oracle_mod):
     cfg = synth.CONFIGS[1]
     rng = np.random.Generator(np.random.Philox(key=11))

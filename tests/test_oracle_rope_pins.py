@@ -28,6 +28,22 @@ def test_quarter_turn_swaps_pair_with_sign(oracle_mod):
     np.testing.assert_allclose(s[0], [1 * abs(c) + 2 * sn, 2 * abs(c) + 1 * sn, 4 * abs(c) + 8 * sn, 8 * abs(c) + 4 * sn], rtol=1e-15)
 
 
+def test_three_quarter_turn_uses_the_magnitude_of_a_negative_sine(oracle_mod):
+    """At 3*pi/2 the sine is -1: (a, b) -> (b, -a), and the magnitude map must take |sin| (with the sign kept
+    S' would come out negative)."""
+    th = np.array([np.float32(np.pi / 2)], np.float32)          # head_dim 2, one pair; position 3
+    y = np.array([[3.0, 5.0, 7.0, 11.0]]); s = np.array([[1.0, 2.0, 4.0, 8.0]])
+    oracle_mod.rope_inplace(y, s, np.array([3], np.int32), th, 4, 2)
+    ang = 3.0 * float(th[0])
+    c, sn = np.cos(ang), np.sin(ang)
+    assert sn < -0.999999
+    np.testing.assert_allclose(y[0], [3 * c - 5 * sn, 5 * c + 3 * sn, 7 * c - 11 * sn, 11 * c + 7 * sn], rtol=1e-15)
+    assert abs(y[0, 0] - 5.0) < 1e-5 and abs(y[0, 1] + 3.0) < 1e-5   # (a,b) -> (b,-a)
+    np.testing.assert_allclose(s[0], [1 * abs(c) + 2 * abs(sn), 2 * abs(c) + 1 * abs(sn),
+                                      4 * abs(c) + 8 * abs(sn), 8 * abs(c) + 4 * abs(sn)], rtol=1e-15)
+    assert (s > 0).all() and abs(s[0, 0] - 2.0) < 1e-5 and abs(s[0, 1] - 1.0) < 1e-5
+
+
 def test_matches_complex_multiplication(oracle_mod):
     rng = np.random.default_rng(2)
     M, heads, d = 5, 3, 8
