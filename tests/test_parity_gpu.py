@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 from paper_2605_25655_amd import synth
-from tests.gpu_common import Runner, say, to_dev, to_host
+from tests.gpu_common import Runner, new_out, say, to_dev, to_host
 from tests.parity import check
 
 pytestmark = pytest.mark.gpu
