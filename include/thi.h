@@ -109,6 +109,22 @@ int thi_linear(const void* x, const void* w, void* out, int M, int N, int K,
                void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * thi_linear for callers that cannot allocate or pass a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same operator and same kernels as
+ * thi_linear for up to THI_STATIC_MAX_M tokens (the weight-streaming decode kernels), bit-identical
+ * results; the kernels' scratch memory (status words and hand-over slots, about 17 MiB) is a static
+ * device array inside the library instead of a caller's workspace.  The call allocates and frees
+ * nothing.  M > THI_STATIC_MAX_M returns THI_ERR_SHAPE (the GEMM kernels' scratch is not held
+ * statically); with thi_set_kernel_family(2) in force every call returns THI_ERR_WORKSPACE.
+ * Every GPU the library is used on holds its own copy of the array until the process ends.  All
+ * calls on one GPU share that array: calls that may overlap on one GPU (different streams) race;
+ * calls on one stream, or otherwise ordered, are fine.  The first call on a device also enqueues a
+ * small clearing kernel in front of the operator, on `hip_stream`.
+ */
+#define THI_STATIC_MAX_M 32
+int thi_linear_static(const void* x, const void* w, void* out, int M, int N, int K, void* hip_stream);
+
+/*
  * SwiGLU MLP with SiLU(gate)*up fused behind the gate/up projections (the
  * "high-density - [low-density]" half of the fusion unit, Sec. III-C.1):
  *

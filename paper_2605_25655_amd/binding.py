@@ -20,7 +20,7 @@ _LIB_PATH = os.path.join(_PKG, "libthi.so")
 _lib = None
 
 EXPORTED_SYMBOLS = (
-    "thi_rmsnorm_qkv", "thi_rmsnorm_qkv_rope", "thi_linear", "thi_swiglu_mlp", "thi_swiglu_gate_up",
+    "thi_rmsnorm_qkv", "thi_rmsnorm_qkv_rope", "thi_linear", "thi_linear_static", "thi_swiglu_mlp", "thi_swiglu_gate_up",
     "thi_linear_residual", "thi_rmsnorm_swiglu_mlp", "thi_decode_attention", "thi_attention_workspace_bytes",
     "thi_workspace_bytes",
     "thi_workspace_init", "thi_workspace_status", "thi_debug_handover", "thi_status_string", "thi_version", "thi_set_kernel_family", "thi_set_rowblock_split", "thi_query_kernel_family",
@@ -58,6 +58,8 @@ def load_library():
     lib.thi_rmsnorm_qkv_rope.restype = ci
     lib.thi_linear.argtypes = [vp, vp, vp, ci, ci, ci, vp, sz, vp]
     lib.thi_linear.restype = ci
+    lib.thi_linear_static.argtypes = [vp, vp, vp, ci, ci, ci, vp]
+    lib.thi_linear_static.restype = ci
     lib.thi_swiglu_mlp.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, vp, sz, vp]
     lib.thi_swiglu_mlp.restype = ci
     lib.thi_swiglu_gate_up.argtypes = [vp, vp, vp, vp, ci, ci, ci, vp, sz, vp]
@@ -202,6 +204,16 @@ def thi_linear(x, w, out, workspace, stream=None, check: bool = True) -> int:
     rc = load_library().thi_linear(_ptr(x), _ptr(w), _ptr(out), M, N, K, wp, wb, _stream(stream))
     if check and rc != THI_OK:
         raise ThiError(rc, "thi_linear")
+    return rc
+
+
+def thi_linear_static(x, w, out, stream=None, check: bool = True) -> int:
+    """out[M,N] = x[M,K] @ w[N,K]^T for M <= 32, on the library's static scratch array (nothing is allocated)."""
+    M, K = x.shape
+    N = w.shape[0]
+    rc = load_library().thi_linear_static(_ptr(x), _ptr(w), _ptr(out), M, N, K, _stream(stream))
+    if check and rc != THI_OK:
+        raise ThiError(rc, "thi_linear_static")
     return rc
 
 

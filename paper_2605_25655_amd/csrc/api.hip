@@ -5,6 +5,7 @@
 #include "thi_internal.h"
 
 #include <atomic>
+#include <mutex>
 
 namespace {
 
@@ -474,6 +475,46 @@ int thi_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream
     hipStream_t stream = (hipStream_t)hip_stream;
     (void)hipGetLastError();      // an error another user of the runtime left behind is not ours to report
     return launch_fill_words(workspace, WS_COUNTER_BYTES, 0u, stream) == hipSuccess ? THI_OK : THI_ERR_HIP;
+}
+
+// ---- the entry point that allocates nothing ---------------------------------------------------------
+// The decode kernels' scratch memory (status words, then the hand-over slots: the fixed part of a workspace)
+// as a file-scope device array.  Each GPU the library runs on holds its own copy until the process ends.
+// In host code the array's name is only a stand-in for the symbol: the device address is looked up once
+// per device and that pointer is what the kernels are given.
+constexpr size_t STATIC_SCRATCH_BYTES = WS_COUNTER_BYTES + (size_t)SK_MAX_GRID * SK_SLOT_WORDS * sizeof(unsigned);
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+int thi_linear_static(const void* x, const void* w, void* out, int M, int N, int K, void* hip_stream)
+{
+    if (!x || !w || !out) return THI_ERR_NULL;
+    if (M < 1 || N < 1 || K < 1 || (K & 7)) return THI_ERR_SHAPE;
+    if (M > THI_STATIC_MAX_M) return THI_ERR_SHAPE;       // the static scratch array holds the decode kernels' part only
+    if (misaligned(x, 16) || misaligned(w, 16) || misaligned(out, 16)) return THI_ERR_ALIGN;
+    if (fixed_bytes() > STATIC_SCRATCH_BYTES) return THI_ERR_WORKSPACE;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    (void)hipGetLastError();      // an error another user of the runtime left behind is not ours to report
+
+    // once per device, with that device current: the array's address on this GPU
+    static std::mutex lock;
+    static void* scratch_ptr[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return THI_ERR_HIP;
+    void* ptr;
+    {
+        std::lock_guard<std::mutex> guard(lock);
+        ptr = scratch_ptr[dev];
+        if (!ptr) {
+            if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return THI_ERR_HIP;
+            // the status words must be zero before the first kernel uses them (a fill kernel, so that a
+            // caller under stream capture records no memset node); every kernel leaves them zero again
+            if (launch_fill_words(ptr, WS_COUNTER_BYTES, 0u, stream) != hipSuccess) return THI_ERR_HIP;
+            scratch_ptr[dev] = ptr;
+        }
+    }
+    Workspace ws = carve(ptr, fixed_bytes(), THI_OP_LINEAR, M, N, K);      // decode layout: no GEMM region
+    return run_projection((const uint16_t*)x, nullptr, 0.f, (const uint16_t*)w, nullptr, (uint16_t*)out,
+                          M, N, K, N, EPI_PLAIN, ws, stream);
 }
 
 int thi_workspace_status(const void* workspace, size_t workspace_bytes, void* hip_stream)
