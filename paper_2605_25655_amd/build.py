@@ -14,7 +14,7 @@ from concurrent.futures import ThreadPoolExecutor
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libthi.so")
-SOURCES = ["api.hip", "skinny.hip", "rowslab.hip", "rowblock.hip", "attention.hip", "gemm.hip", "probes.hip"]
+SOURCES = ["api.hip", "plan.hip", "skinny.hip", "rowslab.hip", "rowblock.hip", "attention.hip", "gemm.hip", "probes.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",

@@ -455,15 +455,6 @@ hipError_t launch_d(const AttnArgs& a, int gt, hipStream_t stream)
 
 }  // namespace
 
-int attention_heads_per_workgroup(int group) { return group >= 8 ? 8 : group >= 4 ? 4 : group >= 2 ? 2 : 1; }
-
-// chunks are whole multiples of this (a multiple of every kernel's positions per workgroup iteration)
-int attention_chunk_quantum(int D, int gt)
-{
-    (void)D; (void)gt;
-    return 128;
-}
-
 hipError_t launch_attention(const AttnArgs& a, hipStream_t stream)
 {
     const int gt = attention_heads_per_workgroup(a.group);

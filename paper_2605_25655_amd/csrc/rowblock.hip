@@ -466,35 +466,6 @@ hipError_t launch_t(const SkinnyArgs& a, int epilogue, const RowBlockPlan& p, hi
 
 }  // namespace
 
-RowBlockPlan plan_rowblock(int N, int epilogue, int num_cus, int ksplit)
-{
-    RowBlockPlan p;
-    const int out_per_tile = is_swiglu(epilogue) ? 8 : 16;
-    if (ksplit < 1) ksplit = 1;
-    int groups = num_cus / ksplit;          // row blocks: ksplit workgroups each
-    if (groups < 1) groups = 1;
-    int per_wg = (N + groups - 1) / groups;
-    if (!is_swiglu(epilogue)) per_wg = (per_wg + 1) & ~1;      // rotary pairs (n, n + 1) stay in one block
-    p.per_wg = per_wg;
-    p.ksplit = ksplit;
-    p.grid = ((N + per_wg - 1) / per_wg) * ksplit;
-    p.tiles = (per_wg + out_per_tile - 1) / out_per_tile;
-    p.passes = (p.tiles + 5) / 6;
-    const int per_pass = (p.tiles + p.passes - 1) / p.passes;
-    p.T = per_pass < 2 ? 2 : per_pass;
-    return p;
-}
-
-bool rowblock_split_ok(int N, int K, int epilogue, int num_cus, int ksplit)
-{
-    if (ksplit < 2 || ksplit > ROWBLOCK_MAX_SPLIT || epilogue != EPI_PLAIN) return false;
-    if (((K + 127) >> 7) < 8 * ksplit) return false;           // every wave of every share gets k of its own
-    const RowBlockPlan p = plan_rowblock(N, epilogue, num_cus, ksplit);
-    // one pass (the hand-over happens once, at the end), one workgroup per compute unit at most, and a
-    // slot / a counter per workgroup / block within the workspace
-    return p.passes == 1 && p.grid <= num_cus && p.grid <= SK_MAX_GRID && p.T * 512 <= SK_SLOT_WORDS;
-}
-
 hipError_t launch_rowblock(const SkinnyArgs& a, int epilogue, int num_cus, hipStream_t stream, int ksplit)
 {
     if (a.K < 1024 || a.K > ROWSLAB_MAX_K || a.N < 1) return hipErrorInvalidValue;

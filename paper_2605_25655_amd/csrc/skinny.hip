@@ -441,8 +441,6 @@ __global__ void fill_words_kernel(uint32_t* p, size_t words, uint32_t value)
 
 }  // namespace
 
-size_t skinny_handover_bytes() { return (size_t)SK_MAX_GRID * SK_SLOT_WORDS * sizeof(unsigned); }
-
 hipError_t launch_skinny(const SkinnyArgs& a, int epilogue, int num_cus, hipStream_t stream)
 {
     const long U = (long)a.tiles * a.kchunks;
