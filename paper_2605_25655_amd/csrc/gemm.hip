@@ -34,7 +34,6 @@
 // the workgroups running on it at that moment.
 #include "thi_internal.h"
 
-#include <cstdlib>
 #include <mutex>
 
 namespace thi {
@@ -235,12 +234,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_fixup(GemmArgs a, int tiles
 
 // BN x BM output tile, WN x WM waves; wave tile (BN/WN) x (BM/WM) built from 32x32 MFMA tiles.
 // KTAIL: K is not a multiple of 64 (pieces past K are zero-filled; operands then go through VGPRs).
-// PP ("ping-pong", the 256x256 configuration): the two waves of a SIMD work half a period apart.  Between two
-// barriers one of them issues nothing but the MFMAs of a whole staged k-tile, from registers, while the
-// other brings its fragments of the next k-tile from LDS into registers (and both have issued their share
-// of the direct loads of the k-tile after that); at the barrier they swap roles.  The matrix pipe then
-// never waits for an LDS read or a wait counter inside a wave's instruction stream.
-template <int BN, int BM, int WN, int WM, int GK, int NS, int EPI, bool KTAIL, bool PP = false>
+template <int BN, int BM, int WN, int WM, int GK, int NS, int EPI, bool KTAIL>
 __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int tiles_m, int ktiles, int sk_tiles, int parts)
 {
     constexpr int NWAVES = WN * WM;
@@ -458,58 +452,6 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
         __syncthreads();
 
         constexpr int LPT = (W_DMA ? WPASS : 0) + (X_DMA ? XPASS : 0);   // direct loads per k-tile per wave
-        if constexpr (PP) {
-            static_assert(NS == 2 && W_DMA && X_DMA && WM == 2, "ping-pong: two stages, direct loads, two wave groups");
-            // a whole k-tile's fragments of this wave: KSTEPS x (TN + TM) 16-byte registers
-            half8 fa[KSTEPS][TN], fb[KSTEPS][TM];
-            auto load_all = [&](int buf) {
-#pragma unroll
-                for (int kk = 0; kk < KSTEPS; ++kk) {
-#pragma unroll
-                    for (int tn = 0; tn < TN; ++tn)
-                        fa[kk][tn] = __builtin_bit_cast(half8, smem[buf * STAGE + swz<GPIECES>(wn * (BN / WN) + tn * 32 + lr, 2 * kk + lg)]);
-#pragma unroll
-                    for (int tm = 0; tm < TM; ++tm)
-                        fb[kk][tm] = __builtin_bit_cast(half8, smem[buf * STAGE + BN * GPIECES + swz<GPIECES>(wm * (BM / WM) + tm * 32 + lr, 2 * kk + lg)]);
-                }
-            };
-            auto mfma_all = [&]() {
-#pragma unroll
-                for (int kk = 0; kk < KSTEPS; ++kk)
-#pragma unroll
-                    for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-                        for (int tm = 0; tm < TM; ++tm)
-                            acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[kk][tn], fb[kk][tm], acc[tn][tm], 0, 0, 0);
-            };
-            // Both groups pass the same barriers.  Per k-tile `it`: the first group multiplies it while the
-            // second loads its fragments of it; at the middle barrier k-tile it+1 has landed (every wave
-            // waited for its own direct loads) and stage it%2 has been read by everybody, so both issue
-            // their direct loads of k-tile it+2 into it; then the first group loads its fragments of it+1
-            // while the second multiplies it.
-            if (wm == 0) {
-                load_all(0);
-                __syncthreads();
-                for (int it = 0; it < nk; ++it) {
-                    mfma_all();
-                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                    __syncthreads();
-                    if (it + 2 < nk) { load_w(kb + it + 2, it & 1); load_x(kb + it + 2, it & 1); }
-                    if (it + 1 < nk) load_all((it + 1) & 1);
-                    __syncthreads();
-                }
-            } else {
-                __syncthreads();
-                for (int it = 0; it < nk; ++it) {
-                    load_all(it & 1);
-                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                    __syncthreads();
-                    if (it + 2 < nk) { load_w(kb + it + 2, it & 1); load_x(kb + it + 2, it & 1); }
-                    mfma_all();
-                    __syncthreads();
-                }
-            }
-        } else {
         frags(0, 0, 0);
         for (int it = 0; it < nk; ++it) {
             const int st = it % NS;
@@ -546,7 +488,6 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
             }
             if (it + 1 < nk) frags((it + 1) % NS, 0, 0);
             mfmas((KSTEPS - 1) & 1);
-        }
         }
 
         // ---- whole tile: finished below; shared tile: leave the fp32 partial for the fix-up kernel ---
@@ -641,7 +582,7 @@ constexpr double FEW_TFLOPS = 900.0 / 256;                    // one token tile:
 
 // ALL = also build the variant for a ragged K (operands staged through VGPRs); the direct-to-LDS
 // configurations leave it to the 128x128 one.
-template <int BN, int BM, int WN, int WM, int GK, int NS, bool ALL, bool PP = false>
+template <int BN, int BM, int WN, int WM, int GK, int NS, bool ALL>
 hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream, double wg_tflops, double tile_fixed_us)
 {
     const int per_tile = is_swiglu(epilogue) ? BN / 2 : BN;
@@ -658,7 +599,7 @@ hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream
     dim3 g((unsigned)grid), b(64 * WN * WM);
 #define THI_LAUNCH_K(E, KT)                                                                                  \
     do {                                                                                                     \
-        auto kern = gemm_streamk<BN, BM, WN, WM, GK, NS, E, KT, PP>;                                                  \
+        auto kern = gemm_streamk<BN, BM, WN, WM, GK, NS, E, KT>;                                                    \
         static std::once_flag attr_once;      /* one opt-in per kernel variant, safe from several threads */  \
         std::call_once(attr_once, [&] {                                                                      \
             (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                   \
@@ -800,11 +741,7 @@ hipError_t launch_gemm(const GemmArgs& a, int epilogue, int num_cus, hipStream_t
             if (c_deep < c_big && c_deep < c_small)
                 return launch_cfg<128, 128, 2, 2, 64, 3, false>(a, epilogue, num_cus, stream, DEEP_TFLOPS, DEEP_FIXED_US);
         }
-        if (c_big <= c_small) {
-            static const bool pp = getenv("THI_GEMM_PP") != nullptr;
-            if (pp) return launch_cfg<256, 256, 4, 2, 64, 2, false, true>(a, epilogue, g_big, stream, BIG_TFLOPS, BIG_FIXED_US);
-            return launch_cfg<256, 256, 4, 2, 64, 2, false>(a, epilogue, g_big, stream, BIG_TFLOPS, BIG_FIXED_US);
-        }
+        if (c_big <= c_small) return launch_cfg<256, 256, 4, 2, 64, 2, false>(a, epilogue, g_big, stream, BIG_TFLOPS, BIG_FIXED_US);
     }
     return launch_cfg<128, 128, 2, 2, 64, 2, true>(a, epilogue, g_small, stream, SMALL_TFLOPS, SMALL_FIXED_US);
 }
