@@ -381,6 +381,27 @@ def main():
         "roofline": roof,
     }
 
+    # Extra: the same step replayed from a captured HIP graph (one graph launch per pass over all weight copies;
+    # the paper's unified kernel scheduling, one launch per operator graph).  The eager figure above stays the
+    # headline: on this GPU the gaps between dependent kernels are on the device side and a graph does not remove them.
+    if decode:
+        try:
+            stream = torch.cuda.Stream()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(stream):
+                lb.step(0)
+                stream.synchronize()
+                with torch.cuda.graph(graph, stream=stream):
+                    for c in range(lb.copies):
+                        lb.step(c)
+                ms_g, _, _ = lb.time_loop(lambda i: graph.replay(), max(MIN_PER_BLOCK, per_block // lb.copies), 5)
+            torch.cuda.synchronize()
+            out["captured_graph"] = {"us_per_step": round(ms_g * 1e3 / lb.copies, 2), "steps_per_graph": lb.copies,
+                                     "eager_us_per_step": round(head["ms_per_step"] * 1e3, 2)}
+            del graph
+        except Exception as e:      # reported, never fatal: the figure is an extra
+            out["captured_graph"] = {"error": repr(e)[:200]}
+
     # Extra (not part of the step): decode attention for the same batch, every request with `--context`
     # cached positions, heads as in the Llama model of this shape.  Algorithmic bytes: K and V read once.
     if decode and args.context > 0:

@@ -35,6 +35,7 @@
 #include "thi_internal.h"
 
 #include <mutex>
+#include <type_traits>
 
 namespace thi {
 
@@ -234,7 +235,15 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_fixup(GemmArgs a, int tiles
 
 // BN x BM output tile, WN x WM waves; wave tile (BN/WN) x (BM/WM) built from 32x32 MFMA tiles.
 // KTAIL: K is not a multiple of 64 (pieces past K are zero-filled; operands then go through VGPRs).
-template <int BN, int BM, int WN, int WM, int GK, int NS, int EPI, bool KTAIL>
+// FD: how many k-steps ahead of the MFMAs the operand fragments are read from LDS (1: two fragment buffers;
+// 2: three, the 256x256 configuration).  The two waves of a SIMD do not share the matrix pipe evenly -- the
+// older one is served first, finishes its k-tile early and waits at the barrier, and the other then runs
+// alone, with MFMA blocks of 256 cycles per k-step instead of 512 to hide its LDS reads behind (cycle counters
+// in the loop, 2048 x 8192 x 28672: the waves 0..3 waited ~1100 cycles per k-tile at the barrier, the waves 4..7
+// ~170; the wait for the direct loads was 40..80 cycles).  One more k-step of distance gives the wave that runs
+// alone more slack: 2757 -> 2625 cycles per k-tile (2048 would be the matrix pipe's own time), +2.2 % in
+// throughput -- the clock gives back half of what the cycles gain.
+template <int BN, int BM, int WN, int WM, int GK, int NS, int EPI, bool KTAIL, int FD = 1>
 __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int tiles_m, int ktiles, int sk_tiles, int parts)
 {
     constexpr int NWAVES = WN * WM;
@@ -452,6 +461,48 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
         __syncthreads();
 
         constexpr int LPT = (W_DMA ? WPASS : 0) + (X_DMA ? XPASS : 0);   // direct loads per k-tile per wave
+        if constexpr (FD == 2) {
+            static_assert(NS == 2 && KSTEPS == 4 && W_DMA && X_DMA, "three fragment buffers: two stages of four k-steps, direct loads");
+            half8 wa3[3][TN], xb3[3][TM];
+            auto frags3 = [&](int buf, int kk, int fs) {
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+                    wa3[fs][tn] = __builtin_bit_cast(half8, smem[buf * STAGE + swz<GPIECES>(wn * (BN / WN) + tn * 32 + lr, 2 * kk + lg)]);
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+                    xb3[fs][tm] = __builtin_bit_cast(half8, smem[buf * STAGE + BN * GPIECES + swz<GPIECES>(wm * (BM / WM) + tm * 32 + lr, 2 * kk + lg)]);
+            };
+            auto mfmas3 = [&](int fs) {
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm)
+                        acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wa3[fs][tn], xb3[fs][tm], acc[tn][tm], 0, 0, 0);
+            };
+            frags3(0, 0, 0);
+            frags3(0, 1, 1);
+            // k-step s of k-tile `it` is global step 4 it + s and lives in fragment buffer (it + s) mod 3; while it is
+            // multiplied, step + 2 is read.  The barrier sits in the middle of the k-tile: all four k-steps of
+            // stage st have been read by then, k-tile it+1 must have landed, and its first fragments are read
+            // right behind it.  (A k-tile that does not exist is "read" from the current stage and never used.)
+            auto tile = [&](auto ph, int it) __attribute__((always_inline)) {
+                constexpr int P = decltype(ph)::value;
+                const int st = it % NS;
+                const int nx = (it + 1 < nk) ? (it + 1) % NS : st;
+                frags3(st, 2, (P + 2) % 3); mfmas3(P % 3); interleave();
+                frags3(st, 3, (P + 3) % 3); mfmas3((P + 1) % 3); interleave();
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __syncthreads();
+                if (it + NS < nk) { load_w(kb + it + NS, st); load_x(kb + it + NS, st); }
+                frags3(nx, 0, (P + 4) % 3); mfmas3((P + 2) % 3); interleave();
+                frags3(nx, 1, (P + 5) % 3); mfmas3((P + 3) % 3); interleave();
+            };
+            for (int it = 0; it < nk; it += 3) {
+                tile(std::integral_constant<int, 0>{}, it);
+                if (it + 1 < nk) tile(std::integral_constant<int, 1>{}, it + 1);
+                if (it + 2 < nk) tile(std::integral_constant<int, 2>{}, it + 2);
+            }
+        } else {
         frags(0, 0, 0);
         for (int it = 0; it < nk; ++it) {
             const int st = it % NS;
@@ -488,6 +539,7 @@ __global__ __launch_bounds__(64 * WN * WM) void gemm_streamk(GemmArgs a, int til
             }
             if (it + 1 < nk) frags((it + 1) % NS, 0, 0);
             mfmas((KSTEPS - 1) & 1);
+        }
         }
 
         // ---- whole tile: finished below; shared tile: leave the fp32 partial for the fix-up kernel ---
@@ -582,7 +634,7 @@ constexpr double FEW_TFLOPS = 900.0 / 256;                    // one token tile:
 
 // ALL = also build the variant for a ragged K (operands staged through VGPRs); the direct-to-LDS
 // configurations leave it to the 128x128 one.
-template <int BN, int BM, int WN, int WM, int GK, int NS, bool ALL>
+template <int BN, int BM, int WN, int WM, int GK, int NS, bool ALL, int FD = 1>
 hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream, double wg_tflops, double tile_fixed_us)
 {
     const int per_tile = is_swiglu(epilogue) ? BN / 2 : BN;
@@ -599,7 +651,7 @@ hipError_t launch_cfg(GemmArgs a, int epilogue, int grid_cap, hipStream_t stream
     dim3 g((unsigned)grid), b(64 * WN * WM);
 #define THI_LAUNCH_K(E, KT)                                                                                  \
     do {                                                                                                     \
-        auto kern = gemm_streamk<BN, BM, WN, WM, GK, NS, E, KT>;                                                    \
+        auto kern = gemm_streamk<BN, BM, WN, WM, GK, NS, E, KT, FD>;                                                  \
         static std::once_flag attr_once;      /* one opt-in per kernel variant, safe from several threads */  \
         std::call_once(attr_once, [&] {                                                                      \
             (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                   \
@@ -741,7 +793,7 @@ hipError_t launch_gemm(const GemmArgs& a, int epilogue, int num_cus, hipStream_t
             if (c_deep < c_big && c_deep < c_small)
                 return launch_cfg<128, 128, 2, 2, 64, 3, false>(a, epilogue, num_cus, stream, DEEP_TFLOPS, DEEP_FIXED_US);
         }
-        if (c_big <= c_small) return launch_cfg<256, 256, 4, 2, 64, 2, false>(a, epilogue, g_big, stream, BIG_TFLOPS, BIG_FIXED_US);
+        if (c_big <= c_small) return launch_cfg<256, 256, 4, 2, 64, 2, false, 2>(a, epilogue, g_big, stream, BIG_TFLOPS, BIG_FIXED_US);
     }
     return launch_cfg<128, 128, 2, 2, 64, 2, true>(a, epilogue, g_small, stream, SMALL_TFLOPS, SMALL_FIXED_US);
 }

@@ -828,6 +828,63 @@ def test_power_of_two_scaling_is_exact_at_full_size(thi, M, N, K):
     assert torch.equal((a.float() * 4)[ok], b.float()[ok])
 
 
+# ------------------------------------- the layer's calls as one captured graph
+@pytest.mark.parametrize("M", [1, 32])
+def test_layer_calls_replay_from_a_captured_graph(thi, M):
+    """The layer's projections (RMSNorm-QKV with the rotary epilogue, O projection with its residual,
+    RMSNorm-fronted MLP with its residual: five kernels on the 7B shape) captured once into a HIP graph and
+    launched as ONE graph per layer pass (the paper's unified kernel scheduling: one launch per operator graph).
+    The library only launches kernels on the caller's stream and allocates nothing, so its calls can be
+    captured as they are.  Every replay -- with new activations written in between, eager work and
+    synchronisations between the replays -- must reproduce the eager calls bit for bit."""
+    import torch
+    say(f"[case] captured graph of the layer's calls, M={M}")
+    H, NQ, I, hd = 4096, 12288, 11008, 128
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(8800 + M)
+
+    def rnd(shape, scale=1.0):
+        return (torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32) * scale).half()
+
+    w_qkv, w_o, w_g, w_u, w_d = rnd((NQ, H), 0.02), rnd((H, H), 0.02), rnd((I, H), 0.02), rnd((I, H), 0.02), rnd((H, I), 0.02)
+    gamma1, gamma2 = (1 + rnd((H,), 0.1).float()).half(), (1 + rnd((H,), 0.1).float()).half()
+    x, attn = rnd((M, H)), rnd((M, H))
+    pos = (torch.arange(M, device="cuda", dtype=torch.int32) * 37) % 4096
+    theta = torch.from_numpy(_theta(hd)).cuda()
+    qkv, hid, out = new_out(M, NQ), new_out(M, H), new_out(M, H)
+    ws = thi.Workspace(max(thi.thi_workspace_bytes(0, M, NQ, H), thi.thi_workspace_bytes(2, M, H, I)))
+
+    def layer():
+        thi.thi_rmsnorm_qkv_rope(x, gamma1, 1e-6, w_qkv, pos, theta, 2 * H, hd, qkv, ws)
+        thi.thi_linear_residual(attn, w_o, x, hid, ws)                      # hid = x + attn Wo^T
+        thi.thi_rmsnorm_swiglu_mlp(hid, gamma2, 1e-6, w_g, w_u, w_d, hid, out, ws)
+
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        layer()
+        stream.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            layer()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        # new inputs, eager reference first
+        x.copy_(rnd((M, H)))
+        attn.copy_(rnd((M, H)))
+        layer()
+        torch.cuda.synchronize()
+        ref = [t.clone() for t in (qkv, hid, out)]
+        for t in (qkv, hid, out):
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, a, b in zip(("qkv", "hidden", "out"), ref, (qkv, hid, out)):
+            assert torch.equal(a.view(torch.int16), b.view(torch.int16)), f"replay {rep}: {name} differs from the eager calls"
+        assert np.isfinite(to_host(out).astype(np.float32)).all()
+    assert not _status_words(ws).any()
+
+
 # ------------------------------------------------- the five layer configs
 def tile_edge_columns(seed: int, N: int, extra: int = 256) -> np.ndarray:
     """Column sample for the all-rows pass: the first and last column of every 128-column tile (every tile
