@@ -269,6 +269,17 @@ int thi_set_kernel_family(int family);
 int thi_set_rowblock_split(int split);
 
 /*
+ * Opt-in: on != 0 lets thi_swiglu_mlp / thi_rmsnorm_swiglu_mlp run as ONE launch -- gate/up, a grid-wide rendezvous
+ * on h inside the kernel, the down projection (the paper's unified kernel scheduling, Sec. III-C.4) -- where the
+ * library has that kernel for the shape (the 7B-shaped layer at 17..32 tokens); 0 (default) = always two launches,
+ * which measured faster on MI355X.  Results are identical bit for bit either way.  The single launch keeps its
+ * rendezvous tags in status words 2047..2559 of the workspace, which are then not zero between calls (every other
+ * status word is); like the other in-kernel hand-overs it needs all workgroups resident at once and reports a
+ * time-out through thi_workspace_status().  Returns the previous setting.
+ */
+int thi_set_mlp_fusion(int on);
+
+/*
  * Test hook for the time-out path of the stream-K decode kernel's hand-over:
  * spin_limit = polls of a contributor's flag before the finishing workgroup
  * gives up (0 = the default, 2^24); withhold_flags != 0 makes the contributors

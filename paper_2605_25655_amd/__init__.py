@@ -25,6 +25,7 @@ from .binding import (  # noqa: F401
     thi_rmsnorm_qkv_rope,
     thi_rmsnorm_swiglu_mlp,
     thi_set_kernel_family,
+    thi_set_mlp_fusion,
     thi_set_rowblock_split,
     thi_swiglu_gate_up,
     thi_swiglu_mlp,
@@ -37,6 +38,6 @@ from .binding import (  # noqa: F401
 
 __all__ = [
     "THI_ERR_TIMEOUT", "THI_ERR_WORKSPACE", "THI_OK", "ThiError", "Workspace", "library_path", "load_library", "thi_attention_workspace_bytes", "thi_decode_attention", "thi_linear", "thi_linear_residual", "thi_linear_static", "thi_probe_mfma_f16", "thi_probe_stream_read", "thi_query_kernel_family",
-    "thi_rmsnorm_qkv", "thi_rmsnorm_qkv_rope", "thi_rmsnorm_swiglu_mlp", "thi_set_kernel_family", "thi_set_rowblock_split", "thi_swiglu_gate_up", "thi_swiglu_mlp", "thi_status_string", "thi_version",
+    "thi_rmsnorm_qkv", "thi_rmsnorm_qkv_rope", "thi_rmsnorm_swiglu_mlp", "thi_set_kernel_family", "thi_set_mlp_fusion", "thi_set_rowblock_split", "thi_swiglu_gate_up", "thi_swiglu_mlp", "thi_status_string", "thi_version",
     "thi_workspace_bytes", "thi_workspace_init", "thi_workspace_status", "thi_debug_handover",
 ]

@@ -23,7 +23,7 @@ EXPORTED_SYMBOLS = (
     "thi_rmsnorm_qkv", "thi_rmsnorm_qkv_rope", "thi_linear", "thi_linear_static", "thi_swiglu_mlp", "thi_swiglu_gate_up",
     "thi_linear_residual", "thi_rmsnorm_swiglu_mlp", "thi_decode_attention", "thi_attention_workspace_bytes",
     "thi_workspace_bytes",
-    "thi_workspace_init", "thi_workspace_status", "thi_debug_handover", "thi_status_string", "thi_version", "thi_set_kernel_family", "thi_set_rowblock_split", "thi_query_kernel_family",
+    "thi_workspace_init", "thi_workspace_status", "thi_debug_handover", "thi_status_string", "thi_version", "thi_set_kernel_family", "thi_set_rowblock_split", "thi_set_mlp_fusion", "thi_query_kernel_family",
     "thi_probe_stream_read", "thi_probe_mfma_f16",
 )
 
@@ -88,6 +88,8 @@ def load_library():
     lib.thi_query_kernel_family.restype = ci
     lib.thi_set_kernel_family.argtypes = [ci]
     lib.thi_set_kernel_family.restype = ci
+    lib.thi_set_mlp_fusion.argtypes = [ci]
+    lib.thi_set_mlp_fusion.restype = ci
     lib.thi_set_rowblock_split.argtypes = [ci]
     lib.thi_set_rowblock_split.restype = ci
     lib.thi_probe_stream_read.argtypes = [vp, sz, vp, vp]
@@ -118,6 +120,11 @@ def thi_query_kernel_family(M: int, N: int, K: int, fused: int = 0) -> int:
 
 def thi_set_kernel_family(family: int) -> int:
     return int(load_library().thi_set_kernel_family(int(family)))
+
+
+def thi_set_mlp_fusion(on: bool) -> int:
+    """Opt-in: the decode MLP as one launch where the library has that kernel (default off); returns the previous setting."""
+    return int(load_library().thi_set_mlp_fusion(int(bool(on))))
 
 
 def thi_set_rowblock_split(split: int) -> int:

@@ -40,6 +40,18 @@ bool rowblock_split_ok(int N, int K, int epilogue, int num_cus, int ksplit)
     return p.passes == 1 && p.grid <= num_cus && p.grid <= SK_MAX_GRID && p.T * 512 <= SK_SLOT_WORDS;
 }
 
+// The single-launch decode MLP: which shapes the one fused kernel that is built serves.
+bool mlp_fused_ok(int M, int H, int I, int epilogue_up, int num_cus, int ksplit_down)
+{
+    if (M <= 16 || M > 32 || H < 1024 || H > ROWSLAB_MAX_K || I < 1024 || I > ROWSLAB_MAX_K) return false;
+    if (epilogue_up != EPI_SWIGLU && epilogue_up != EPI_RMSNORM_SWIGLU) return false;
+    if (!rowblock_split_ok(H, I, EPI_PLAIN, num_cus, ksplit_down)) return false;
+    const RowBlockPlan up = plan_rowblock(I, epilogue_up, num_cus, 1), down = plan_rowblock(H, EPI_PLAIN, num_cus, ksplit_down);
+    // the one pair of block shapes that is built: six gate/up tiles and four down tiles in flight, one pass each
+    return up.passes == 1 && up.T == 6 && up.grid <= num_cus && down.passes == 1 && down.T == 4 && down.grid <= num_cus &&
+           num_cus <= MLP_MAX_GRID;
+}
+
 // ---- prefill GEMM ----------------------------------------------------------------------------------
 size_t gemm_partial_bytes() { return (size_t)GEMM_MAX_GRID * 2 * 128 * 128 * sizeof(float); }
 

@@ -33,27 +33,44 @@ namespace {
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
-template <int T, int MT, int EPI, bool SPLIT = false>
-__global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_, const uint16_t* w0_, const uint16_t* w1_,
-                                                              const uint16_t* gamma_, int M_, int N_, int K_, int per_wg,
-                                                              SkinnyArgs a)
+// tiles per reduction round: all of them while the partial tiles and sums fit ~55 KiB of LDS (static
+// LDS <= 92 KiB leaves room for the largest gamma slice), else half a pass
+template <int T, int MT>
+constexpr int reduction_tiles() { return (T * MT <= 6 && T <= 5) ? T : (T + 1) / 2; }
+
+// The kernel's static LDS (one object per workgroup; the single-launch MLP overlays the objects of its two phases).
+template <int T, int MT>
+struct RowBlockShared {
+    uintx4 wt[SK_WAVES][WT_UNITS];                              // wave-private transposition buffers
+    floatx4 s_part[SK_WAVES][reduction_tiles<T, MT>()][MT * 64]; // the waves' partial tiles, a lane's four registers together
+    float s_sum[reduction_tiles<T, MT>()][32][17];              // finished sums [tile][token][row]
+    float s_red[SK_WAVES][32];
+    float s_ssq[32];
+    unsigned s_last;                                            // SPLIT: this workgroup closes its row block
+};
+
+// The whole kernel as a function of (block id, grid size), so that one launch can run two of them back to back.
+// DEVOUT: the outputs are stored with device-scope (write-through) stores, for a consumer that reads them later in
+// the SAME launch; pre(): called once, when the first weights have been requested and before the first activation
+// load (the single-launch MLP waits there for the whole of h).
+template <int T, int MT, int EPI, bool SPLIT, bool DEVOUT, typename Pre>
+__device__ __forceinline__ void rowblock_body(SkinnyArgs a, const int per_wg, const int block_id, const int grid,
+                                              RowBlockShared<T, MT>& sm, uintx4* s_gamma, Pre pre)
 {
-    // The operands the first loads need come as leading scalar arguments: the hardware preloads those
-    // into registers at wave launch, so the first weight request does not wait for an argument fetch.
-    a.x = x_; a.w0 = w0_; a.w1 = w1_; a.gamma = gamma_; a.M = M_; a.N = N_; a.K = K_;
     static_assert(T >= 2 && T <= 6, "tiles in flight");
-    // tiles per reduction round: all of them while the partial tiles and sums fit ~55 KiB of LDS (static
-    // LDS <= 92 KiB leaves room for the largest gamma slice), else half a pass
-    constexpr int RT = (T * MT <= 6 && T <= 5) ? T : (T + 1) / 2;
+    constexpr int RT = reduction_tiles<T, MT>();
     constexpr int OUT_PER_TILE = is_swiglu(EPI) ? 8 : 16;
-    __shared__ uintx4 wt[SK_WAVES][WT_UNITS];          // wave-private transposition buffers
-    __shared__ floatx4 s_part[SK_WAVES][RT][MT * 64];  // the waves' partial tiles, a lane's four registers together
-    __shared__ float s_sum[RT][32][17];                // finished sums [tile][token][row]
-    __shared__ float s_red[SK_WAVES][32];
-    __shared__ float s_ssq[32];
-    __shared__ unsigned s_last;                        // SPLIT: this workgroup closes its row block
-    extern __shared__ uintx4 s_gamma[];                // RMSNorm: each wave's slice of gamma
+    auto& wt = sm.wt;
+    auto& s_part = sm.s_part;
+    auto& s_sum = sm.s_sum;
+    auto& s_red = sm.s_red;
+    auto& s_ssq = sm.s_ssq;
+    unsigned& s_last = sm.s_last;
     static_assert(!SPLIT || EPI == EPI_PLAIN, "the reduction dimension is only shared for the plain kind");
+    auto put = [&](uint16_t* p, uint16_t bits) __attribute__((always_inline)) {
+        if constexpr (DEVOUT) __hip_atomic_store(p, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else *p = bits;
+    };
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -63,9 +80,9 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
     // this workgroup's block of outputs (rows of W; gate/up row pairs for SwiGLU); SPLIT: S workgroups
     // share a block, each with 1/S of the reduction dimension (S travels in a.kchunks)
     const int S = SPLIT ? a.kchunks : 1;
-    const int blocks = SPLIT ? (int)gridDim.x / S : (int)gridDim.x;
-    const int rb = SPLIT ? (int)blockIdx.x % blocks : (int)blockIdx.x;
-    const int ks = SPLIT ? (int)blockIdx.x / blocks : 0;
+    const int blocks = SPLIT ? grid / S : grid;
+    const int rb = SPLIT ? block_id % blocks : block_id;
+    const int ks = SPLIT ? block_id / blocks : 0;
     const int r0 = rb * per_wg;
     if (r0 >= a.N) return;
     const int r1 = r0 + per_wg < a.N ? r0 + per_wg : a.N;
@@ -141,6 +158,8 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
             s_gamma[wv * g_pieces + p] = ld_cached(a.gamma + k_begin + p * 8);
         __builtin_amdgcn_wave_barrier();
     }
+
+    pre();                                   // (the single-launch MLP: wait for the activations to be complete)
 
     uintx4 xr[8][MT];                        // the unit's activations, operand layout (x * gamma for RMSNorm)
 
@@ -219,7 +238,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
         if (is_swiglu(EPI)) {
             const int j = r0 + tile * 8 + r;
             if (r < 8 && j < r1)
-                a.out[(size_t)m * a.ldo + j] = to_half_bits(silu_mul(sum[m][r] * scale, sum[m][r + 8] * scale));
+                put(a.out + (size_t)m * a.ldo + j, to_half_bits(silu_mul(sum[m][r] * scale, sum[m][r + 8] * scale)));
         } else {
             const int n = r0 + tile * 16 + r;
             if (EPI == EPI_RMSNORM_ROPE) {
@@ -228,23 +247,23 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
                     rope_pair(a.rope, a.rope.pos[m], n, v0, v1);
                     if (n < r1) {
                         if (a.residual) v0 += half_bits_to_float(a.residual[(size_t)m * a.ldo + n]);
-                        a.out[(size_t)m * a.ldo + n] = to_half_bits(v0);
+                        put(a.out + (size_t)m * a.ldo + n, to_half_bits(v0));
                     }
                     if (n + 1 < r1) {
                         if (a.residual) v1 += half_bits_to_float(a.residual[(size_t)m * a.ldo + n + 1]);
-                        a.out[(size_t)m * a.ldo + n + 1] = to_half_bits(v1);
+                        put(a.out + (size_t)m * a.ldo + n + 1, to_half_bits(v1));
                     }
                 }
             } else if (n < r1) {
                 float v = sum[m][r] * scale;
                 if (a.residual) v += half_bits_to_float(a.residual[(size_t)m * a.ldo + n]);
-                a.out[(size_t)m * a.ldo + n] = to_half_bits(v);
+                put(a.out + (size_t)m * a.ldo + n, to_half_bits(v));
             }
         }
     };
 
     // SPLIT: the block's sums over this workgroup's share of K go to its hand-over slot, [tile][token][row]
-    unsigned* const slot = a.handover + (size_t)blockIdx.x * SK_SLOT_WORDS;
+    unsigned* const slot = a.handover + (size_t)block_id * SK_SLOT_WORDS;
     auto hand_in = [&](int tile, int tt) __attribute__((always_inline)) {
         const int r = tid & 15, m = tid >> 4;
         if (m < a.M)
@@ -409,10 +428,94 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
             if (t < nT && n < r1) {
                 float o = v[t];
                 if (a.residual) o += half_bits_to_float(a.residual[(size_t)m * a.ldo + n]);
-                a.out[(size_t)m * a.ldo + n] = to_half_bits(o);
+                put(a.out + (size_t)m * a.ldo + n, to_half_bits(o));
             }
         }
     }
+}
+
+template <int T, int MT, int EPI, bool SPLIT = false>
+__global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_, const uint16_t* w0_, const uint16_t* w1_,
+                                                              const uint16_t* gamma_, int M_, int N_, int K_, int per_wg,
+                                                              SkinnyArgs a)
+{
+    // The operands the first loads need come as leading scalar arguments: the hardware preloads those
+    // into registers at wave launch, so the first weight request does not wait for an argument fetch.
+    a.x = x_; a.w0 = w0_; a.w1 = w1_; a.gamma = gamma_; a.M = M_; a.N = N_; a.K = K_;
+    __shared__ RowBlockShared<T, MT> sm;
+    extern __shared__ uintx4 s_gamma[];                // RMSNorm: each wave's slice of gamma
+    rowblock_body<T, MT, EPI, SPLIT, false>(a, per_wg, (int)blockIdx.x, (int)gridDim.x, sm, s_gamma, [] {});
+}
+
+// The SwiGLU MLP of a decode step as ONE launch (the paper's unified kernel scheduling, Sec. III-C.4: one launch per
+// operator graph instead of one per operator): every workgroup first runs its row block of the gate/up projection
+// (storing its part of h = silu(g)*u with device-scope stores), announces its arrival, requests the first weights of
+// its row block of the down projection, and only then waits until the whole grid has arrived -- the wait for h
+// overlaps the latency of those first weights, and neither the tail of the first phase nor a kernel boundary leaves
+// the memory system idle.  All workgroups are resident at once (one per compute unit) and the wait is bounded
+// (time-out marker as for the other hand-overs).  Both phases are the row-block kernel above; their static LDS
+// objects are overlaid.
+// The rendezvous avoids read-modify-write traffic on one word (256 device-scope atomic adds on one address take
+// ~18 us): every workgroup stores a tag into its own status word and wave 0 of every waiting workgroup reads all of
+// them (four words per lane) until they all carry the tag.  The tag is the launch's number on this workspace plus
+// one, read from a status word at kernel entry and advanced by workgroup 0 once everybody has arrived -- nothing has
+// to be reset, the launch can be replayed from a captured graph, and a freshly initialised workspace (all zero)
+// never matches.  These words are the only status words that are not zero between calls.
+template <int T1, int T2, int MT, int EPI1>
+__global__ __launch_bounds__(SK_THREADS) void mlp_fused(const uint16_t* x_, const uint16_t* wg_, const uint16_t* wu_,
+                                                        const uint16_t* gamma_, int M_, int I_, int H_, int per_wg1,
+                                                        int per_wg2, int grid1, int grid2, SkinnyArgs a1, SkinnyArgs a2)
+{
+    a1.x = x_; a1.w0 = wg_; a1.w1 = wu_; a1.gamma = gamma_; a1.M = M_; a1.N = I_; a1.K = H_;
+    a2.M = M_; a2.N = H_; a2.K = I_;
+    union Shared {
+        RowBlockShared<T1, MT> up;
+        RowBlockShared<T2, MT> down;
+    };
+    __shared__ Shared sm;
+    extern __shared__ uintx4 s_gamma[];
+    const int bid = (int)blockIdx.x;
+    const int everybody = (int)gridDim.x;
+    unsigned* const epoch = a2.counters + MLP_EPOCH_WORD;
+    unsigned* const flags = a2.counters + MLP_FLAG_WORDS;
+    // (every lane reads the same word: the value is wave-uniform)
+    const unsigned launch_no = __hip_atomic_load(epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned tag = launch_no + 1u;                      // 1 .. 2^32 - 1: never the zero of a fresh workspace
+
+    if (bid < grid1) rowblock_body<T1, MT, EPI1, false, true>(a1, per_wg1, bid, grid1, sm.up, s_gamma, [] {});
+    // this workgroup's part of h is acknowledged by the memory system before its arrival is announced
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) __hip_atomic_store(flags + bid, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (bid >= grid2) return;
+
+    rowblock_body<T2, MT, EPI_PLAIN, true, false>(a2, per_wg2, bid, grid2, sm.down, s_gamma, [&] {
+        if (threadIdx.x < 64) {
+            const int lane = (int)threadIdx.x;
+            unsigned spins = 0;
+            bool ok = true;
+            while (true) {
+                bool all = true;
+#pragma unroll
+                for (int q = 0; q < MLP_MAX_GRID / 64; ++q) {
+                    const int w = q * 64 + lane;
+                    const unsigned f = __hip_atomic_load(flags + (w < everybody ? w : 0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    all = all && (w >= everybody || f == tag);
+                }
+                if (__builtin_amdgcn_ballot_w64(!all) == 0ull) break;
+                __builtin_amdgcn_s_sleep(1);
+                if (++spins > a2.spin_limit) { ok = false; break; }      // bounded: every wave exits
+            }
+            if (lane == 0) {
+                if (!ok) __hip_atomic_store(a2.counters + (WS_MAX_COUNTERS - 1), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                // everybody has read the launch number (at entry, before arriving): it may advance
+                if (bid == 0) __hip_atomic_store(epoch, tag == 0xffffffffu ? 0u : tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        __syncthreads();
+        // h was written by other compute units: nothing of it may be served from this one's vector cache
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    });
 }
 
 // 16-byte pieces of LDS per wave for its slice of gamma (same arithmetic as in the kernel)
@@ -465,6 +568,30 @@ hipError_t launch_t(const SkinnyArgs& a, int epilogue, const RowBlockPlan& p, hi
 }
 
 }  // namespace
+
+hipError_t launch_mlp_fused(const SkinnyArgs& up, const SkinnyArgs& down, int epilogue_up, int num_cus, hipStream_t stream,
+                            int ksplit_down)
+{
+    if (!mlp_fused_ok(up.M, up.K, up.N, epilogue_up, num_cus, ksplit_down)) return hipErrorInvalidValue;
+    const RowBlockPlan p1 = plan_rowblock(up.N, epilogue_up, num_cus, 1), p2 = plan_rowblock(down.N, EPI_PLAIN, num_cus, ksplit_down);
+    SkinnyArgs a2 = down;
+    a2.kchunks = ksplit_down;
+    const int grid = p1.grid > p2.grid ? p1.grid : p2.grid;
+    const size_t gamma_lds = epilogue_up == EPI_RMSNORM_SWIGLU ? (size_t)SK_WAVES * gamma_pieces(up.K) * sizeof(uintx4) : 0;
+    static std::once_flag attr_once;
+    std::call_once(attr_once, [] {
+        const int most = (int)((size_t)SK_WAVES * gamma_pieces(ROWSLAB_MAX_K) * sizeof(uintx4));
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_fused<6, 4, 2, EPI_SWIGLU>), hipFuncAttributeMaxDynamicSharedMemorySize, most);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_fused<6, 4, 2, EPI_RMSNORM_SWIGLU>), hipFuncAttributeMaxDynamicSharedMemorySize, most);
+    });
+    if (epilogue_up == EPI_SWIGLU)
+        hipLaunchKernelGGL((mlp_fused<6, 4, 2, EPI_SWIGLU>), dim3(grid), dim3(SK_THREADS), gamma_lds, stream, up.x, up.w0, up.w1, up.gamma,
+                           up.M, up.N, up.K, p1.per_wg, p2.per_wg, p1.grid, p2.grid, up, a2);
+    else
+        hipLaunchKernelGGL((mlp_fused<6, 4, 2, EPI_RMSNORM_SWIGLU>), dim3(grid), dim3(SK_THREADS), gamma_lds, stream, up.x, up.w0, up.w1,
+                           up.gamma, up.M, up.N, up.K, p1.per_wg, p2.per_wg, p1.grid, p2.grid, up, a2);
+    return hipGetLastError();
+}
 
 hipError_t launch_rowblock(const SkinnyArgs& a, int epilogue, int num_cus, hipStream_t stream, int ksplit)
 {

@@ -98,6 +98,14 @@ constexpr int ROWBLOCK_MAX_SPLIT = 6;
 RowBlockPlan plan_rowblock(int N, int epilogue, int num_cus, int ksplit = 1);
 bool rowblock_split_ok(int N, int K, int epilogue, int num_cus, int ksplit);
 hipError_t launch_rowblock(const SkinnyArgs& a, int epilogue, int num_cus, hipStream_t stream, int ksplit = 1);
+// The decode MLP as one launch: gate/up row blocks (up: N = I, K = H, out = h), a grid-wide rendezvous on two status
+// words, then the down projection's shared row blocks (down: x = h, N = H, K = I) with ksplit_down workgroups per block.
+// status words of its rendezvous (the other users stay below 1024): the launch number on this workspace, then one
+// tag word per workgroup; unlike all other status words these are not zero between calls
+constexpr int MLP_EPOCH_WORD = 2047, MLP_FLAG_WORDS = 2048, MLP_MAX_GRID = 512;
+bool mlp_fused_ok(int M, int H, int I, int epilogue_up, int num_cus, int ksplit_down);
+hipError_t launch_mlp_fused(const SkinnyArgs& up, const SkinnyArgs& down, int epilogue_up, int num_cus, hipStream_t stream,
+                            int ksplit_down);
 
 // ---- GEMM (prefill) kernel ---------------------------------------------------
 struct GemmArgs {

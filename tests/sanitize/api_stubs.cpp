@@ -27,6 +27,11 @@ hipError_t launch_rowblock(const SkinnyArgs& a, int epilogue, int num_cus, hipSt
     const RowBlockPlan p = plan_rowblock(a.N, epilogue, num_cus, ksplit);
     return (p.T >= 2 && p.T <= 6 && p.grid >= 1) ? hipSuccess : hipErrorInvalidValue;
 }
+hipError_t launch_mlp_fused(const SkinnyArgs& up, const SkinnyArgs& down, int epilogue_up, int num_cus, hipStream_t, int ksplit_down)
+{
+    ++g_launches;
+    return (mlp_fused_ok(up.M, up.K, up.N, epilogue_up, num_cus, ksplit_down) && down.x == up.out) ? hipSuccess : hipErrorInvalidValue;
+}
 hipError_t launch_gemm(const GemmArgs& a, int epilogue, int, hipStream_t)
 {
     ++g_launches;

@@ -828,9 +828,50 @@ def test_power_of_two_scaling_is_exact_at_full_size(thi, M, N, K):
     assert torch.equal((a.float() * 4)[ok], b.float()[ok])
 
 
+# ------------------------------------- the decode MLP as one launch (opt-in)
+@pytest.mark.parametrize("M", [17, 32])
+def test_single_launch_mlp_matches_two_launches(thi, oracle_mod, M):
+    """thi_set_mlp_fusion(1): gate/up, an in-kernel grid-wide rendezvous on h, and the down projection in one launch
+    (7B-shaped MLP, 17..32 tokens).  Same kernels' arithmetic in the same order: the result must equal the two-launch
+    path bit for bit (which is itself held to the oracle here), for the plain and the RMSNorm-fronted / residual
+    operator, repeatedly (the rendezvous tags advance from launch to launch), and the other status words stay zero."""
+    import torch
+    say(f"[case] single-launch MLP M={M}")
+    H, I = 4096, 11008
+    rng = np.random.Generator(np.random.Philox(key=9900 + M))
+    x = f16(rng.standard_normal((M, H)))
+    res = f16(rng.standard_normal((M, H)))
+    wg, wu = f16(rng.standard_normal((I, H)) * 0.02), f16(rng.standard_normal((I, H)) * 0.02)
+    wd = f16(rng.standard_normal((H, I)) * 0.02)
+    g = f16(1 + 0.1 * rng.standard_normal(H))
+    r = Runner(M, H, I, H)
+    xd, resd, wgd, wud, wdd, gd = (to_dev(t) for t in (x, res, wg, wu, wd, g))
+    two = to_host(r.swiglu_mlp(xd, wgd, wud, wdd))
+    two_n = to_host(r.rmsnorm_swiglu_mlp(xd, gd, 1e-6, wgd, wud, wdd, resd))
+    rows = synth.sample_rows(77, M, 4)
+    y, s = oracle_mod.swiglu_mlp(x[rows], wg, wu, wd)
+    check(two[rows], y, s, "two-launch MLP", argmax=False)
+    prev = thi.thi_set_mlp_fusion(1)
+    try:
+        for rep in range(5):
+            one = to_host(r.swiglu_mlp(xd, wgd, wud, wdd))
+            one_n = to_host(r.rmsnorm_swiglu_mlp(xd, gd, 1e-6, wgd, wud, wdd, resd))
+            assert np.array_equal(one.view(np.uint16), two.view(np.uint16)), f"plain MLP differs (repeat {rep})"
+            assert np.array_equal(one_n.view(np.uint16), two_n.view(np.uint16)), f"RMSNorm-fronted MLP differs (repeat {rep})"
+    finally:
+        thi.thi_set_mlp_fusion(prev)
+    words = _status_words(r.ws).copy()
+    assert words[2047] == 10 and (words[2048:2048 + 256] == 10).all(), "ten single launches: tag 10 everywhere"
+    words[2047:2048 + 512] = 0
+    assert not words.any()
+    assert thi.thi_workspace_status(r.ws) == thi.THI_OK
+    # and the two-launch path is unaffected afterwards
+    assert np.array_equal(to_host(r.swiglu_mlp(xd, wgd, wud, wdd)).view(np.uint16), two.view(np.uint16))
+
+
 # ------------------------------------- the layer's calls as one captured graph
-@pytest.mark.parametrize("M", [1, 32])
-def test_layer_calls_replay_from_a_captured_graph(thi, M):
+@pytest.mark.parametrize("M,single_launch_mlp", [(1, False), (32, False), (32, True)])
+def test_layer_calls_replay_from_a_captured_graph(thi, M, single_launch_mlp):
     """The layer's projections (RMSNorm-QKV with the rotary epilogue, O projection with its residual,
     RMSNorm-fronted MLP with its residual: five kernels on the 7B shape) captured once into a HIP graph and
     launched as ONE graph per layer pass (the paper's unified kernel scheduling: one launch per operator graph).
@@ -838,7 +879,8 @@ def test_layer_calls_replay_from_a_captured_graph(thi, M):
     captured as they are.  Every replay -- with new activations written in between, eager work and
     synchronisations between the replays -- must reproduce the eager calls bit for bit."""
     import torch
-    say(f"[case] captured graph of the layer's calls, M={M}")
+    say(f"[case] captured graph of the layer's calls, M={M}, single-launch MLP {single_launch_mlp}")
+    prev_fusion = thi.thi_set_mlp_fusion(1 if single_launch_mlp else 0)
     H, NQ, I, hd = 4096, 12288, 11008, 128
     gen = torch.Generator(device="cuda")
     gen.manual_seed(8800 + M)
@@ -882,7 +924,12 @@ def test_layer_calls_replay_from_a_captured_graph(thi, M):
         for name, a, b in zip(("qkv", "hidden", "out"), ref, (qkv, hid, out)):
             assert torch.equal(a.view(torch.int16), b.view(torch.int16)), f"replay {rep}: {name} differs from the eager calls"
         assert np.isfinite(to_host(out).astype(np.float32)).all()
-    assert not _status_words(ws).any()
+    thi.thi_set_mlp_fusion(prev_fusion)
+    words = _status_words(ws).copy()
+    if single_launch_mlp:      # its rendezvous tags advance with every launch, replayed ones included
+        assert words[2047] == 9, words[2047]      # one eager warm-up, then four rounds of one eager call and one replay
+        words[2047:2048 + 512] = 0
+    assert not words.any()
 
 
 # ------------------------------------------------- the five layer configs
