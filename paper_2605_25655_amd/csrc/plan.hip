@@ -45,6 +45,7 @@ bool mlp_fused_ok(int M, int H, int I, int epilogue_up, int num_cus, int ksplit_
 {
     if (M <= 16 || M > 32 || H < 1024 || H > ROWSLAB_MAX_K || I < 1024 || I > ROWSLAB_MAX_K) return false;
     if (epilogue_up != EPI_SWIGLU && epilogue_up != EPI_RMSNORM_SWIGLU) return false;
+    if (epilogue_up == EPI_RMSNORM_SWIGLU && H > 24576) return false;      // gamma in LDS beside the two phases' ~104 KiB
     if (!rowblock_split_ok(H, I, EPI_PLAIN, num_cus, ksplit_down)) return false;
     const RowBlockPlan up = plan_rowblock(I, epilogue_up, num_cus, 1), down = plan_rowblock(H, EPI_PLAIN, num_cus, ksplit_down);
     // the one pair of block shapes that is built: six gate/up tiles and four down tiles in flight, one pass each

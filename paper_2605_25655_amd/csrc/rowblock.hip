@@ -34,16 +34,17 @@ namespace {
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
 // tiles per reduction round: all of them while the partial tiles and sums fit ~55 KiB of LDS (static
-// LDS <= 92 KiB leaves room for the largest gamma slice), else half a pass
-template <int T, int MT>
-constexpr int reduction_tiles() { return (T * MT <= 6 && T <= 5) ? T : (T + 1) / 2; }
+// LDS <= 92 KiB leaves room for the largest gamma slice), else half a pass.  The SPLIT variant (plain kind:
+// no gamma in LDS) always takes all of them in one round and needs no finished sums in LDS.
+template <int T, int MT, bool SPLIT>
+constexpr int reduction_tiles() { return SPLIT ? T : (T * MT <= 6 && T <= 5) ? T : (T + 1) / 2; }
 
 // The kernel's static LDS (one object per workgroup; the single-launch MLP overlays the objects of its two phases).
-template <int T, int MT>
+template <int T, int MT, bool SPLIT>
 struct RowBlockShared {
     uintx4 wt[SK_WAVES][WT_UNITS];                              // wave-private transposition buffers
-    floatx4 s_part[SK_WAVES][reduction_tiles<T, MT>()][MT * 64]; // the waves' partial tiles, a lane's four registers together
-    float s_sum[reduction_tiles<T, MT>()][32][17];              // finished sums [tile][token][row]
+    floatx4 s_part[SK_WAVES][reduction_tiles<T, MT, SPLIT>()][MT * 64]; // the waves' partial tiles, a lane's four registers together
+    float s_sum[SPLIT ? 1 : reduction_tiles<T, MT, SPLIT>()][32][17];   // finished sums [tile][token][row]
     float s_red[SK_WAVES][32];
     float s_ssq[32];
     unsigned s_last;                                            // SPLIT: this workgroup closes its row block
@@ -55,10 +56,10 @@ struct RowBlockShared {
 // load (the single-launch MLP waits there for the whole of h).
 template <int T, int MT, int EPI, bool SPLIT, bool DEVOUT, typename Pre>
 __device__ __forceinline__ void rowblock_body(SkinnyArgs a, const int per_wg, const int block_id, const int grid,
-                                              RowBlockShared<T, MT>& sm, uintx4* s_gamma, Pre pre)
+                                              RowBlockShared<T, MT, SPLIT>& sm, uintx4* s_gamma, Pre pre)
 {
     static_assert(T >= 2 && T <= 6, "tiles in flight");
-    constexpr int RT = reduction_tiles<T, MT>();
+    constexpr int RT = reduction_tiles<T, MT, SPLIT>();
     constexpr int OUT_PER_TILE = is_swiglu(EPI) ? 8 : 16;
     auto& wt = sm.wt;
     auto& s_part = sm.s_part;
@@ -108,10 +109,12 @@ __device__ __forceinline__ void rowblock_body(SkinnyArgs a, const int per_wg, co
     // Every load is unconditional.  A row past the block's end is read from the block's last row (the
     // same lines a neighbouring lane asks for); a piece past the wave's k range from the first piece of
     // the unit; a whole tile past the block (or past the wave's last tile-step: valid = false) from the
-    // first piece of its rows.  What such loads return is zeroed or never stored.
+    // start of the activations -- lines that every compute unit has just read, so that the wait for these
+    // loads at the end of the kernel is short.  What such loads return is zeroed or never stored.
     auto issue_w = [&](int tile, int uu, bool valid, uintx4 (&w)[8]) __attribute__((always_inline)) {
         const int k0 = k_begin + uu * SK_KC;
-        const int k_lim = (valid && tile < nT) ? k_end : 0;
+        const bool whole = valid && tile < nT;
+        const int k_lim = whole ? k_end : 0;
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
             const int v = 4 * jj + ld_i;                   // virtual row within the tile
@@ -128,7 +131,7 @@ __device__ __forceinline__ void rowblock_body(SkinnyArgs a, const int per_wg, co
 #pragma unroll
             for (int ph = 0; ph < 2; ++ph) {
                 const int k = k0 + ph * 128 + ld_p * 8;
-                w[ph * 4 + jj] = ld_stream(base + (k < k_lim ? k : k0));
+                w[ph * 4 + jj] = ld_stream(whole ? base + (k < k_lim ? k : k0) : a.x);
             }
         }
     };
@@ -264,12 +267,6 @@ __device__ __forceinline__ void rowblock_body(SkinnyArgs a, const int per_wg, co
 
     // SPLIT: the block's sums over this workgroup's share of K go to its hand-over slot, [tile][token][row]
     unsigned* const slot = a.handover + (size_t)block_id * SK_SLOT_WORDS;
-    auto hand_in = [&](int tile, int tt) __attribute__((always_inline)) {
-        const int r = tid & 15, m = tid >> 4;
-        if (m < a.M)
-            __hip_atomic_store(slot + (tile * 32 + m) * 16 + r, __builtin_bit_cast(unsigned, s_sum[tt][m][r]),
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    };
 
     // One unit of 256 k for all T tiles of the pass.  Tile-steps alternate between the two register
     // buffers; PAR says which of them holds tile 0 of this unit (with an odd T it flips from unit to unit).
@@ -321,6 +318,28 @@ __device__ __forceinline__ void rowblock_body(SkinnyArgs a, const int per_wg, co
         if (!pass_ends) return;
 
         // ---- the eight partial tiles of each of the pass's tiles meet in LDS, RT tiles per round -------
+        if constexpr (SPLIT) {
+            // One round, one barrier: every thread adds the eight partial values of (tile, lane, token tile)
+            // in wave order and stores its four rows of one token -- 16 contiguous bytes of the slot -- with
+            // a device-scope store.
+#pragma unroll
+            for (int tt = 0; tt < T; ++tt)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) s_part[wv][tt][mt * 64 + lane] = acc[tt][mt];
+            __syncthreads();
+            for (int e = tid; e < T * MT * 64; e += SK_THREADS) {
+                const int tt = e / (MT * 64), q = e % (MT * 64);
+                floatx4 v = {0.f, 0.f, 0.f, 0.f};       // fixed order: waves 0..7
+#pragma unroll
+                for (int w = 0; w < SK_WAVES; ++w) v += s_part[w][tt][q];
+                const int l = q & 63, m = (q >> 6) * 16 + (l & 15);
+                if (tt < nT && m < a.M) {
+                    unsigned* const dst = slot + (tt * 32 + m) * 16 + 4 * (l >> 4);
+                    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(dst), "v"(v) : "memory");
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int rr = 0; rr < (T + RT - 1) / RT; ++rr) {
 #pragma unroll
@@ -363,10 +382,7 @@ __device__ __forceinline__ void rowblock_body(SkinnyArgs a, const int per_wg, co
 #pragma unroll
             for (int tt = 0; tt < RT; ++tt) {
                 const int tile = this_pass * T + rr * RT + tt;
-                if (rr * RT + tt < T && tile < nT) {
-                    if constexpr (SPLIT) hand_in(tile, tt);
-                    else finish_tile(tile, tt);
-                }
+                if (rr * RT + tt < T && tile < nT) finish_tile(tile, tt);
             }
             // s_part is rewritten only after every thread has passed the second barrier above, s_sum only
             // after the next round's first barrier, which every thread reaches after these epilogues
@@ -442,7 +458,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
     // The operands the first loads need come as leading scalar arguments: the hardware preloads those
     // into registers at wave launch, so the first weight request does not wait for an argument fetch.
     a.x = x_; a.w0 = w0_; a.w1 = w1_; a.gamma = gamma_; a.M = M_; a.N = N_; a.K = K_;
-    __shared__ RowBlockShared<T, MT> sm;
+    __shared__ RowBlockShared<T, MT, SPLIT> sm;
     extern __shared__ uintx4 s_gamma[];                // RMSNorm: each wave's slice of gamma
     rowblock_body<T, MT, EPI, SPLIT, false>(a, per_wg, (int)blockIdx.x, (int)gridDim.x, sm, s_gamma, [] {});
 }
@@ -469,8 +485,8 @@ __global__ __launch_bounds__(SK_THREADS) void mlp_fused(const uint16_t* x_, cons
     a1.x = x_; a1.w0 = wg_; a1.w1 = wu_; a1.gamma = gamma_; a1.M = M_; a1.N = I_; a1.K = H_;
     a2.M = M_; a2.N = H_; a2.K = I_;
     union Shared {
-        RowBlockShared<T1, MT> up;
-        RowBlockShared<T2, MT> down;
+        RowBlockShared<T1, MT, false> up;
+        RowBlockShared<T2, MT, true> down;
     };
     __shared__ Shared sm;
     extern __shared__ uintx4 s_gamma[];
@@ -521,6 +537,20 @@ __global__ __launch_bounds__(SK_THREADS) void mlp_fused(const uint16_t* x_, cons
 // 16-byte pieces of LDS per wave for its slice of gamma (same arithmetic as in the kernel)
 int gamma_pieces(int K) { return ((((K + 127) >> 7) >> 3) + 1) * 128 >> 3; }
 
+// Opt a kernel in to more than 64 KiB of LDS: as much dynamic LDS as `want`, or as its static LDS leaves of a
+// compute unit's 160 KiB.  Returns the dynamic bytes now allowed.
+constexpr int CU_LDS_BYTES = 160 * 1024;
+int allow_lds(const void* kernel, int want)
+{
+    hipFuncAttributes fa;
+    if (hipFuncGetAttributes(&fa, kernel) != hipSuccess) return 0;
+    int room = CU_LDS_BYTES - (int)fa.sharedSizeBytes;
+    if (room < 0) room = 0;
+    const int most = want < room ? want : room;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, most) != hipSuccess) return 0;
+    return most;
+}
+
 template <int T, int MT>
 hipError_t launch_t_mt(const SkinnyArgs& a, int epilogue, const RowBlockPlan& p, hipStream_t stream)
 {
@@ -531,18 +561,12 @@ hipError_t launch_t_mt(const SkinnyArgs& a, int epilogue, const RowBlockPlan& p,
     std::call_once(attr_once, [] {
         // largest static part: ~90 KiB (T = 3 or 5 with two token tiles); with this it stays inside the 160 KiB of a CU
         const int most = (int)((size_t)SK_WAVES * gamma_pieces(ROWSLAB_MAX_K) * sizeof(uintx4));
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_PLAIN>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, most);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_PLAIN, true>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, most);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_SWIGLU>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, most);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_RMSNORM>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, most);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_RMSNORM_ROPE>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, most);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_RMSNORM_SWIGLU>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, most);
+        (void)allow_lds(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_PLAIN>), 0);
+        (void)allow_lds(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_PLAIN, true>), 0);
+        (void)allow_lds(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_SWIGLU>), 0);
+        (void)allow_lds(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_RMSNORM>), most);
+        (void)allow_lds(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_RMSNORM_ROPE>), most);
+        (void)allow_lds(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_RMSNORM_SWIGLU>), most);
     });
     if (p.ksplit > 1) {      // plain kind only (checked by the caller); the share count travels in kchunks
         SkinnyArgs s = a;
@@ -579,11 +603,13 @@ hipError_t launch_mlp_fused(const SkinnyArgs& up, const SkinnyArgs& down, int ep
     const int grid = p1.grid > p2.grid ? p1.grid : p2.grid;
     const size_t gamma_lds = epilogue_up == EPI_RMSNORM_SWIGLU ? (size_t)SK_WAVES * gamma_pieces(up.K) * sizeof(uintx4) : 0;
     static std::once_flag attr_once;
+    static int room_rms = 0;            // dynamic LDS the RMSNorm variant may use beside its static part
     std::call_once(attr_once, [] {
         const int most = (int)((size_t)SK_WAVES * gamma_pieces(ROWSLAB_MAX_K) * sizeof(uintx4));
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_fused<6, 4, 2, EPI_SWIGLU>), hipFuncAttributeMaxDynamicSharedMemorySize, most);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(mlp_fused<6, 4, 2, EPI_RMSNORM_SWIGLU>), hipFuncAttributeMaxDynamicSharedMemorySize, most);
+        (void)allow_lds(reinterpret_cast<const void*>(mlp_fused<6, 4, 2, EPI_SWIGLU>), 0);
+        room_rms = allow_lds(reinterpret_cast<const void*>(mlp_fused<6, 4, 2, EPI_RMSNORM_SWIGLU>), most);
     });
+    if ((int)gamma_lds > room_rms) return hipErrorInvalidValue;      // gamma for this H does not fit beside the two phases' LDS
     if (epilogue_up == EPI_SWIGLU)
         hipLaunchKernelGGL((mlp_fused<6, 4, 2, EPI_SWIGLU>), dim3(grid), dim3(SK_THREADS), gamma_lds, stream, up.x, up.w0, up.w1, up.gamma,
                            up.M, up.N, up.K, p1.per_wg, p2.per_wg, p1.grid, p2.grid, up, a2);

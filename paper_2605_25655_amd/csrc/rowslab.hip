@@ -82,9 +82,10 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowslab(const uint16_t* x_,
     };
     // Every load is unconditional; one that would leave the wave's k range is redirected to the first
     // piece of the unit (same cache line as a neighbour's load) and zeroed when the unit is consumed.
-    // A prefetch past the workgroup's last unit (valid = false) sends every lane to the first piece of
-    // its row (a few cached sectors, no traffic to speak of): the code stays free of branches around
-    // loads, which keeps the hardware wait counters exact.
+    // A prefetch past the workgroup's last unit (valid = false) sends every lane to the start of the
+    // activations (lines every compute unit has just read: the wait for these loads at the end of the
+    // kernel is short): the code stays free of branches around loads, which keeps the hardware wait
+    // counters exact.
     auto issue_w = [&](int slab, int uu, bool valid, uintx4 (&w)[8]) {
         const int k0 = k_begin + uu * SK_KC;
         const int k_lim = valid ? k_end : 0;
@@ -94,7 +95,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowslab(const uint16_t* x_,
 #pragma unroll
             for (int ph = 0; ph < 2; ++ph) {
                 const int k = k0 + ph * 128 + ld_p * 8;
-                w[ph * 4 + jj] = ld_stream(base + (k < k_lim ? k : k0));
+                w[ph * 4 + jj] = ld_stream(valid ? base + (k < k_lim ? k : k0) : a.x);
             }
         }
     };
