@@ -111,20 +111,23 @@ double rowblock_time(int M, int N, int K, int epilogue, int cus, int split)
     const double per_pass = (double)bp.per_wg / out_per_tile / bp.passes;      // tiles sharing one load of x
     const double x_extra = (M <= 4 ? 0.0 : M <= 8 ? 0.05 : M <= 16 ? 0.15 : 0.40) / per_pass;
     const double lacking = (double)bp.per_wg * (cus / split) / (double)N;
+    // plain kind: the rows a block's last tile lacks still cost their load instructions
+    const double fill = epilogue == EPI_PLAIN ? (double)bp.tiles * out_per_tile / (double)bp.per_wg : 1.0;
     return 3.8 + 0.5 * (bp.passes - 1) + ((split == 1 && bp.tiles <= 2 && K >= 8192 && K < 16384) ? 4.0 : 0.0) +
-           (split > 1 ? 2.0 : 0.0) + t_w * (1.0 + x_extra) * (1.0 + 0.2 * (ragged - 1.0)) * lacking;
+           (split > 1 ? 1.75 + (bp.tiles <= 2 ? 1.0 : 0.0) : 0.0) +
+           t_w * (1.0 + x_extra) * (1.0 + 0.2 * (ragged - 1.0)) * (1.0 + 0.5 * (fill - 1.0)) * lacking;
 }
 
-// Row blocks: how many workgroups share a block (1 = none)?  The smallest modelled time; sharing must
-// win by half a microsecond.  Not above K = 24576: the 70B down projection (K = 28672) measured 15 %
-// slower with two workgroups on the halves of its 56 KiB rows than the model says.
+// Row blocks: how many workgroups share a block (1 = none)?  The smallest modelled time.  Not above
+// K = 24576: the 70B down projection (K = 28672) measured 15 % slower with two workgroups on the halves
+// of its 56 KiB rows than the model says.
 int pick_rowblock_split(int M, int N, int K, int epilogue, int cus)
 {
     const int forced = g_rowblock_split.load(std::memory_order_relaxed);
     if (forced >= 1) return rowblock_split_ok(N, K, epilogue, cus, forced) ? forced : 1;
     if (epilogue != EPI_PLAIN || K > 24576) return 1;
     int best = 1;
-    double t_best = rowblock_time(M, N, K, epilogue, cus, 1) - 0.5;
+    double t_best = rowblock_time(M, N, K, epilogue, cus, 1);
     for (int s = 2; s <= 4; ++s) {
         if (!rowblock_split_ok(N, K, epilogue, cus, s)) continue;
         const double t = rowblock_time(M, N, K, epilogue, cus, s);
@@ -155,7 +158,9 @@ int pick_rowblock_split(int M, int N, int K, int epilogue, int cus)
 //                divided by the tiles per pass); a ragged last unit costs about a fifth of what it
 //                costs the slabs; slowed by the rows the last workgroup lacks.  With S workgroups per
 //                block (plain kind): S x the tiles share a load of x, the eight waves of S workgroups
-//                divide K, and the hand-over at the end costs ~2 us.
+//                divide K, and the hand-over at the end costs ~1.75 us (1 us more with one or two tiles
+//                per block); plain kind: the rows that the block's last tile lacks cost half of what
+//                rows with weights cost (20 rows in two tiles: +30 %).
 enum DecodeKernel { DK_STREAMK = 1, DK_ROWSLAB = 3, DK_ROWBLOCK = 4 };
 int pick_decode_kernel(int M, int N, int K, int epilogue, int cus)
 {
