@@ -33,18 +33,19 @@ namespace {
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
-// tiles per reduction round: all of them while the partial tiles and sums fit ~55 KiB of LDS (static
-// LDS <= 92 KiB leaves room for the largest gamma slice), else half a pass.  The SPLIT variant (plain kind:
-// no gamma in LDS) always takes all of them in one round and needs no finished sums in LDS.
-template <int T, int MT, bool SPLIT>
-constexpr int reduction_tiles() { return SPLIT ? T : (T * MT <= 6 && T <= 5) ? T : (T + 1) / 2; }
+// tiles per reduction round.  With RMSNorm in front a slice of gamma per wave lives in LDS as well (up to 66 KiB):
+// all tiles in one round while the partial tiles and sums fit ~55 KiB (static LDS <= 92 KiB), else half a pass.
+// Without gamma (plain and SwiGLU kinds) all tiles go in one round (up to 144 KiB of static LDS: one
+// workgroup per compute unit either way); the SPLIT variant needs no finished sums in LDS.
+template <int T, int MT, int EPI, bool SPLIT>
+constexpr int reduction_tiles() { return (SPLIT || !is_rms(EPI)) ? T : (T * MT <= 6 && T <= 5) ? T : (T + 1) / 2; }
 
 // The kernel's static LDS (one object per workgroup; the single-launch MLP overlays the objects of its two phases).
-template <int T, int MT, bool SPLIT>
+template <int T, int MT, int EPI, bool SPLIT>
 struct RowBlockShared {
     uintx4 wt[SK_WAVES][WT_UNITS];                              // wave-private transposition buffers
-    floatx4 s_part[SK_WAVES][reduction_tiles<T, MT, SPLIT>()][MT * 64]; // the waves' partial tiles, a lane's four registers together
-    float s_sum[SPLIT ? 1 : reduction_tiles<T, MT, SPLIT>()][32][17];   // finished sums [tile][token][row]
+    floatx4 s_part[SK_WAVES][reduction_tiles<T, MT, EPI, SPLIT>()][MT * 64]; // the waves' partial tiles, a lane's four registers together
+    float s_sum[SPLIT ? 1 : reduction_tiles<T, MT, EPI, SPLIT>()][32][17];   // finished sums [tile][token][row]
     float s_red[SK_WAVES][32];
     float s_ssq[32];
     unsigned s_last;                                            // SPLIT: this workgroup closes its row block
@@ -56,10 +57,10 @@ struct RowBlockShared {
 // load (the single-launch MLP waits there for the whole of h).
 template <int T, int MT, int EPI, bool SPLIT, bool DEVOUT, typename Pre>
 __device__ __forceinline__ void rowblock_body(SkinnyArgs a, const int per_wg, const int block_id, const int grid,
-                                              RowBlockShared<T, MT, SPLIT>& sm, uintx4* s_gamma, Pre pre)
+                                              RowBlockShared<T, MT, EPI, SPLIT>& sm, uintx4* s_gamma, Pre pre)
 {
     static_assert(T >= 2 && T <= 6, "tiles in flight");
-    constexpr int RT = reduction_tiles<T, MT, SPLIT>();
+    constexpr int RT = reduction_tiles<T, MT, EPI, SPLIT>();
     constexpr int OUT_PER_TILE = is_swiglu(EPI) ? 8 : 16;
     auto& wt = sm.wt;
     auto& s_part = sm.s_part;
@@ -458,7 +459,7 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
     // The operands the first loads need come as leading scalar arguments: the hardware preloads those
     // into registers at wave launch, so the first weight request does not wait for an argument fetch.
     a.x = x_; a.w0 = w0_; a.w1 = w1_; a.gamma = gamma_; a.M = M_; a.N = N_; a.K = K_;
-    __shared__ RowBlockShared<T, MT, SPLIT> sm;
+    __shared__ RowBlockShared<T, MT, EPI, SPLIT> sm;
     extern __shared__ uintx4 s_gamma[];                // RMSNorm: each wave's slice of gamma
     rowblock_body<T, MT, EPI, SPLIT, false>(a, per_wg, (int)blockIdx.x, (int)gridDim.x, sm, s_gamma, [] {});
 }
@@ -485,8 +486,8 @@ __global__ __launch_bounds__(SK_THREADS) void mlp_fused(const uint16_t* x_, cons
     a1.x = x_; a1.w0 = wg_; a1.w1 = wu_; a1.gamma = gamma_; a1.M = M_; a1.N = I_; a1.K = H_;
     a2.M = M_; a2.N = H_; a2.K = I_;
     union Shared {
-        RowBlockShared<T1, MT, false> up;
-        RowBlockShared<T2, MT, true> down;
+        RowBlockShared<T1, MT, EPI1, false> up;
+        RowBlockShared<T2, MT, EPI_PLAIN, true> down;
     };
     __shared__ Shared sm;
     extern __shared__ uintx4 s_gamma[];
