@@ -32,11 +32,12 @@ namespace thi {
 namespace {
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef unsigned uintx2 __attribute__((ext_vector_type(2)));
 
 // tiles per reduction round.  With RMSNorm in front a slice of gamma per wave lives in LDS as well (up to 66 KiB):
-// all tiles in one round while the partial tiles and sums fit ~55 KiB (static LDS <= 92 KiB), else half a pass.
-// Without gamma (plain and SwiGLU kinds) all tiles go in one round (up to 144 KiB of static LDS: one
-// workgroup per compute unit either way); the SPLIT variant needs no finished sums in LDS.
+// all tiles in one round while the partial tiles fit 48 KiB (static LDS <= 85 KiB), else half a pass.
+// Without gamma (plain and SwiGLU kinds) all tiles go in one round (up to 131 KiB of static LDS: one
+// workgroup per compute unit either way).
 template <int T, int MT, int EPI, bool SPLIT>
 constexpr int reduction_tiles() { return (SPLIT || !is_rms(EPI)) ? T : (T * MT <= 6 && T <= 5) ? T : (T + 1) / 2; }
 
@@ -45,7 +46,6 @@ template <int T, int MT, int EPI, bool SPLIT>
 struct RowBlockShared {
     uintx4 wt[SK_WAVES][WT_UNITS];                              // wave-private transposition buffers
     floatx4 s_part[SK_WAVES][reduction_tiles<T, MT, EPI, SPLIT>()][MT * 64]; // the waves' partial tiles, a lane's four registers together
-    float s_sum[SPLIT ? 1 : reduction_tiles<T, MT, EPI, SPLIT>()][32][17];   // finished sums [tile][token][row]
     float s_red[SK_WAVES][32];
     float s_ssq[32];
     unsigned s_last;                                            // SPLIT: this workgroup closes its row block
@@ -64,7 +64,6 @@ __device__ __forceinline__ void rowblock_body(SkinnyArgs a, const int per_wg, co
     constexpr int OUT_PER_TILE = is_swiglu(EPI) ? 8 : 16;
     auto& wt = sm.wt;
     auto& s_part = sm.s_part;
-    auto& s_sum = sm.s_sum;
     auto& s_red = sm.s_red;
     auto& s_ssq = sm.s_ssq;
     unsigned& s_last = sm.s_last;
@@ -146,6 +145,7 @@ __device__ __forceinline__ void rowblock_body(SkinnyArgs a, const int per_wg, co
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) ssq[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
 
+    float ssq_first = 0.f;                   // RMSNorm: this thread's token's sum of squares (first pass)
     int pass = 0, uu = 0;                    // the unit being consumed
     int p_pass = 0, p_uu = 0;                // the unit of the tile-step last requested
     int requested = 1;
@@ -232,40 +232,6 @@ __device__ __forceinline__ void rowblock_body(SkinnyArgs a, const int per_wg, co
         multiply(ti, cur);
     };
 
-    // Epilogue of one finished tile: thread -> (token m, row r)
-    auto finish_tile = [&](int tile, int tt) __attribute__((always_inline)) {
-        const float (&sum)[32][17] = s_sum[tt];
-        const int r = tid & 15, m = tid >> 4;
-        if (m >= a.M) return;
-        float scale = 1.0f;
-        if (is_rms(EPI)) scale = 1.0f / __builtin_sqrtf(s_ssq[m] / (float)K + a.eps);
-        if (is_swiglu(EPI)) {
-            const int j = r0 + tile * 8 + r;
-            if (r < 8 && j < r1)
-                put(a.out + (size_t)m * a.ldo + j, to_half_bits(silu_mul(sum[m][r] * scale, sum[m][r + 8] * scale)));
-        } else {
-            const int n = r0 + tile * 16 + r;
-            if (EPI == EPI_RMSNORM_ROPE) {
-                if ((r & 1) == 0) {       // this thread finishes the pair (n, n + 1); blocks start on even rows
-                    float v0 = sum[m][r] * scale, v1 = sum[m][r + 1] * scale;
-                    rope_pair(a.rope, a.rope.pos[m], n, v0, v1);
-                    if (n < r1) {
-                        if (a.residual) v0 += half_bits_to_float(a.residual[(size_t)m * a.ldo + n]);
-                        put(a.out + (size_t)m * a.ldo + n, to_half_bits(v0));
-                    }
-                    if (n + 1 < r1) {
-                        if (a.residual) v1 += half_bits_to_float(a.residual[(size_t)m * a.ldo + n + 1]);
-                        put(a.out + (size_t)m * a.ldo + n + 1, to_half_bits(v1));
-                    }
-                }
-            } else if (n < r1) {
-                float v = sum[m][r] * scale;
-                if (a.residual) v += half_bits_to_float(a.residual[(size_t)m * a.ldo + n]);
-                put(a.out + (size_t)m * a.ldo + n, to_half_bits(v));
-            }
-        }
-    };
-
     // SPLIT: the block's sums over this workgroup's share of K go to its hand-over slot, [tile][token][row]
     unsigned* const slot = a.handover + (size_t)block_id * SK_SLOT_WORDS;
 
@@ -341,8 +307,12 @@ __device__ __forceinline__ void rowblock_body(SkinnyArgs a, const int per_wg, co
             }
             return;
         }
+        // Every thread adds the eight partial values of (tile, token tile, lane) in wave order and finishes what it
+        // then holds -- four consecutive output features of one token (two gate/up pairs after an exchange between
+        // the wave's halves for SwiGLU) -- straight from registers: one barrier per round.
+        constexpr int ROUNDS = (T + RT - 1) / RT;
 #pragma unroll
-        for (int rr = 0; rr < (T + RT - 1) / RT; ++rr) {
+        for (int rr = 0; rr < ROUNDS; ++rr) {
 #pragma unroll
             for (int tt = 0; tt < RT; ++tt)
                 if (rr * RT + tt < T) {
@@ -363,30 +333,82 @@ __device__ __forceinline__ void rowblock_body(SkinnyArgs a, const int per_wg, co
                 if (MT == 1 && kg == 0) s_red[wv][16 + c] = 0.f;
             }
             __syncthreads();
+            // this thread's token in every iteration below (512 is a multiple of MT * 64) and its RMSNorm factor:
+            // the sum of squares of the first pass, added in wave order, kept in s_ssq for the later passes
+            const int q = tid % (MT * 64), l = q & 63, m = (q >> 6) * 16 + (l & 15), quad = l >> 4;
+            float scale = 1.0f;
+            if (is_rms(EPI)) {
+                float v = 0.f;
+                if (first_pass) {
+                    if (rr == 0) {
+#pragma unroll
+                        for (int w = 0; w < SK_WAVES; ++w) v += s_red[w][m];
+                        if (tid < MT * 64 && quad == 0) s_ssq[m] = v;
+                        ssq_first = v;
+                    } else {
+                        v = ssq_first;
+                    }
+                } else {
+                    v = s_ssq[m];
+                }
+                scale = 1.0f / __builtin_sqrtf(v / (float)K + a.eps);
+            }
             const int round_tiles = (rr + 1) * RT <= T ? RT : T - rr * RT;
             for (int e = tid; e < round_tiles * MT * 64; e += SK_THREADS) {
-                const int tt = e / (MT * 64), q = e % (MT * 64);
+                const int tt = e / (MT * 64);
                 floatx4 v = {0.f, 0.f, 0.f, 0.f};       // fixed order: waves 0..7
 #pragma unroll
                 for (int w = 0; w < SK_WAVES; ++w) v += s_part[w][tt][q];
-                const int l = q & 63, mt = q >> 6;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) s_sum[tt][mt * 16 + (l & 15)][4 * (l >> 4) + i] = v[i];
-            }
-            if (is_rms(EPI) && first_pass && rr == 0 && tid < 32) {      // kept in s_ssq for the later passes
-                float v = 0.f;
-#pragma unroll
-                for (int w = 0; w < SK_WAVES; ++w) v += s_red[w][tid];
-                s_ssq[tid] = v;
-            }
-            __syncthreads();
-#pragma unroll
-            for (int tt = 0; tt < RT; ++tt) {
                 const int tile = this_pass * T + rr * RT + tt;
-                if (rr * RT + tt < T && tile < nT) finish_tile(tile, tt);
+                if (is_swiglu(EPI)) {
+                    // rows 0..7 of a tile are gate rows, 8..15 the matching up rows: lane l holds rows 4*quad..+3,
+                    // its partner l ^ 32 the rows 8 further on
+                    floatx4 o;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) o[i] = __shfl_xor(v[i], 32);
+                    if (quad < 2 && tile < nT && m < a.M) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int j = r0 + tile * 8 + 4 * quad + i;
+                            if (j < r1) put(a.out + (size_t)m * a.ldo + j, to_half_bits(silu_mul(v[i] * scale, o[i] * scale)));
+                        }
+                    }
+                } else if (tile < nT && m < a.M) {
+                    const int n = r0 + tile * 16 + 4 * quad;
+                    float y[4];
+#pragma unroll
+                    for (int i = 0; i < 4; i += 2) {      // pairs (n + i, n + i + 1); blocks start on even rows
+                        y[i] = v[i] * scale;
+                        y[i + 1] = v[i + 1] * scale;
+                        if (EPI == EPI_RMSNORM_ROPE) rope_pair(a.rope, a.rope.pos[m], n + i, y[i], y[i + 1]);
+                    }
+                    uint16_t* const dst = a.out + (size_t)m * a.ldo + n;
+                    if (!DEVOUT && n + 3 < r1 && ((n | a.ldo) & 3) == 0) {
+                        // the thread's four features as one 8-byte access (out and residual are 16-byte aligned)
+                        if (a.residual) {
+                            const uintx2 rv = *reinterpret_cast<const uintx2*>(a.residual + (size_t)m * a.ldo + n);
+                            y[0] += half_bits_to_float((uint16_t)(rv[0] & 0xffffu));
+                            y[1] += half_bits_to_float((uint16_t)(rv[0] >> 16));
+                            y[2] += half_bits_to_float((uint16_t)(rv[1] & 0xffffu));
+                            y[3] += half_bits_to_float((uint16_t)(rv[1] >> 16));
+                        }
+                        uintx2 ov;
+                        ov[0] = (unsigned)to_half_bits(y[0]) | ((unsigned)to_half_bits(y[1]) << 16);
+                        ov[1] = (unsigned)to_half_bits(y[2]) | ((unsigned)to_half_bits(y[3]) << 16);
+                        *reinterpret_cast<uintx2*>(dst) = ov;
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (n + i < r1) {
+                                float o = y[i];
+                                if (a.residual) o += half_bits_to_float(a.residual[(size_t)m * a.ldo + n + i]);
+                                put(dst + i, to_half_bits(o));
+                            }
+                    }
+                }
             }
-            // s_part is rewritten only after every thread has passed the second barrier above, s_sum only
-            // after the next round's first barrier, which every thread reaches after these epilogues
+            // s_part (and s_red / s_ssq) are written again in the next round or pass: everybody must be done reading
+            if (rr + 1 < ROUNDS || P > 1) __syncthreads();
         }
     };
 
