@@ -24,6 +24,7 @@ namespace thi {
 namespace {
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef unsigned uintx2 __attribute__((ext_vector_type(2)));
 
 // XT: the activations are loaded the way the weights are (16 lanes cover 256 contiguous bytes of a token
 // row) and reach operand layout through the wave's LDS buffer.  From a handful of tokens up this is the
@@ -40,7 +41,6 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowslab(const uint16_t* x_,
     a.x = x_; a.w0 = w0_; a.w1 = w1_; a.gamma = gamma_; a.M = M_; a.N = N_; a.K = K_; a.tiles = tiles_;
     __shared__ uintx4 wt[SK_WAVES][WT_UNITS];          // wave-private transposition buffers
     __shared__ floatx4 s_part[SK_WAVES][MT * 64];      // the waves' partial tiles, a lane's four registers together
-    __shared__ float s_sum[32][17];                    // finished sums [token][row]
     __shared__ float s_red[SK_WAVES][32];
     __shared__ float s_ssq[32];
     extern __shared__ uintx4 s_gamma[];                // RMSNorm: each wave's slice of gamma
@@ -234,58 +234,75 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowslab(const uint16_t* x_,
         }
         if (is_rms(EPI) && first_slab && MT == 1 && kg == 0) s_red[wv][16 + c] = 0.f;
         __syncthreads();
+        // The first MT waves add the eight partial tiles in wave order (fixed: reproducible) and finish what each of
+        // their threads then holds -- four consecutive features of one token (two gate/up pairs after an exchange
+        // between the wave's halves for SwiGLU) -- straight from registers.
         if (tid < MT * 64) {
-            // fixed order: waves 0..7
             floatx4 v = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int w = 0; w < SK_WAVES; ++w) v += s_part[w][tid];
-            const int l = tid & 63, mt = tid >> 6;
+            const int l = tid & 63, quad = l >> 4, m = (tid >> 6) * 16 + (l & 15);
+            float scale = 1.0f;
+            if (is_rms(EPI)) {
+                float q = 0.f;
+                if (first_slab) {         // kept in s_ssq for the later slabs
 #pragma unroll
-            for (int i = 0; i < 4; ++i) s_sum[mt * 16 + (l & 15)][4 * (l >> 4) + i] = v[i];
-        }
-        if (is_rms(EPI) && first_slab && tid < 32) {      // kept in s_ssq for the later slabs
-            float v = 0.f;
-#pragma unroll
-            for (int w = 0; w < SK_WAVES; ++w) v += s_red[w][tid];
-            s_ssq[tid] = v;
-        }
-        __syncthreads();
-
-        // ---- epilogue: thread -> (token m, row r) ----------------------------------------------------
-        const int r = tid & 15, m = tid >> 4;
-        if (m < a.M) {
+                    for (int w = 0; w < SK_WAVES; ++w) q += s_red[w][m];
+                    if (quad == 0) s_ssq[m] = q;
+                } else {
+                    q = s_ssq[m];
+                }
+                scale = 1.0f / __builtin_sqrtf(q / (float)K + a.eps);
+            }
             if (is_swiglu(EPI)) {
-                const int j = this_slab * 8 + r;
-                float scale = 1.0f;      // RMSNorm in front: gate and up both carry the 1/rms factor
-                if (is_rms(EPI)) scale = 1.0f / __builtin_sqrtf(s_ssq[m] / (float)K + a.eps);
-                if (r < 8 && j < a.N)
-                    a.out[(size_t)m * a.ldo + j] = to_half_bits(silu_mul(s_sum[m][r] * scale, s_sum[m][r + 8] * scale));
-            } else {
-                float scale = 1.0f;
-                if (is_rms(EPI)) scale = 1.0f / __builtin_sqrtf(s_ssq[m] / (float)K + a.eps);
-                const int n = this_slab * 16 + r;
-                if (EPI == EPI_RMSNORM_ROPE) {
-                    if ((r & 1) == 0) {       // this thread finishes the pair (n, n + 1)
-                        float v0 = s_sum[m][r] * scale, v1 = s_sum[m][r + 1] * scale;
-                        rope_pair(a.rope, a.rope.pos[m], n, v0, v1);
-                        if (n < a.N) {
-                            if (a.residual) v0 += half_bits_to_float(a.residual[(size_t)m * a.ldo + n]);
-                            a.out[(size_t)m * a.ldo + n] = to_half_bits(v0);
-                        }
-                        if (n + 1 < a.N) {
-                            if (a.residual) v1 += half_bits_to_float(a.residual[(size_t)m * a.ldo + n + 1]);
-                            a.out[(size_t)m * a.ldo + n + 1] = to_half_bits(v1);
-                        }
+                // rows 0..7 of a slab are gate rows, 8..15 the matching up rows: lane l holds rows 4*quad..+3, its
+                // partner l ^ 32 the rows 8 further on
+                floatx4 o;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) o[i] = __shfl_xor(v[i], 32);
+                if (quad < 2 && m < a.M) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int j = this_slab * 8 + 4 * quad + i;
+                        if (j < a.N) a.out[(size_t)m * a.ldo + j] = to_half_bits(silu_mul(v[i] * scale, o[i] * scale));
                     }
-                } else if (n < a.N) {
-                    float v = s_sum[m][r] * scale;
-                    if (a.residual) v += half_bits_to_float(a.residual[(size_t)m * a.ldo + n]);
-                    a.out[(size_t)m * a.ldo + n] = to_half_bits(v);
+                }
+            } else if (m < a.M) {
+                const int n = this_slab * 16 + 4 * quad;
+                float y[4];
+#pragma unroll
+                for (int i = 0; i < 4; i += 2) {      // pairs (n + i, n + i + 1)
+                    y[i] = v[i] * scale;
+                    y[i + 1] = v[i + 1] * scale;
+                    if (EPI == EPI_RMSNORM_ROPE) rope_pair(a.rope, a.rope.pos[m], n + i, y[i], y[i + 1]);
+                }
+                uint16_t* const dst = a.out + (size_t)m * a.ldo + n;
+                if (n + 3 < a.N && (a.ldo & 3) == 0) {
+                    // the thread's four features as one 8-byte access (out and residual are 16-byte aligned)
+                    if (a.residual) {
+                        const uintx2 rv = *reinterpret_cast<const uintx2*>(a.residual + (size_t)m * a.ldo + n);
+                        y[0] += half_bits_to_float((uint16_t)(rv[0] & 0xffffu));
+                        y[1] += half_bits_to_float((uint16_t)(rv[0] >> 16));
+                        y[2] += half_bits_to_float((uint16_t)(rv[1] & 0xffffu));
+                        y[3] += half_bits_to_float((uint16_t)(rv[1] >> 16));
+                    }
+                    uintx2 ov;
+                    ov[0] = (unsigned)to_half_bits(y[0]) | ((unsigned)to_half_bits(y[1]) << 16);
+                    ov[1] = (unsigned)to_half_bits(y[2]) | ((unsigned)to_half_bits(y[3]) << 16);
+                    *reinterpret_cast<uintx2*>(dst) = ov;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (n + i < a.N) {
+                            float o = y[i];
+                            if (a.residual) o += half_bits_to_float(a.residual[(size_t)m * a.ldo + n + i]);
+                            dst[i] = to_half_bits(o);
+                        }
                 }
             }
         }
-        // s_part / s_red are rewritten only after every thread has passed the second barrier above, and
-        // s_sum / s_ssq only after the next slab's first barrier, which follows this epilogue
+        // s_part / s_red are written again at the end of the workgroup's next slab: everybody must be done reading
+        if (n_slabs > 1) __syncthreads();
     };
 
     for (int i = 0; i < total; i += 2) {
