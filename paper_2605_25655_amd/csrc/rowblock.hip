@@ -582,7 +582,7 @@ hipError_t launch_t_mt(const SkinnyArgs& a, int epilogue, const RowBlockPlan& p,
     const size_t gamma_lds = (size_t)SK_WAVES * gamma_pieces(a.K) * sizeof(uintx4);
     static std::once_flag attr_once;    // static (+ dynamic) LDS passes 64 KiB: every variant needs the opt-in
     std::call_once(attr_once, [] {
-        // largest static part: ~90 KiB (T = 3 or 5 with two token tiles); with this it stays inside the 160 KiB of a CU
+        // the kinds with gamma in LDS: static part <= 85 KiB, so the largest gamma slice stays inside the 160 KiB of a CU
         const int most = (int)((size_t)SK_WAVES * gamma_pieces(ROWSLAB_MAX_K) * sizeof(uintx4));
         (void)allow_lds(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_PLAIN>), 0);
         (void)allow_lds(reinterpret_cast<const void*>(skinny_rowblock<T, MT, EPI_PLAIN, true>), 0);
