@@ -24,6 +24,7 @@ import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
+UP_OFFSET_BYTES = 65536      # w_up starts this far past the end of w_gate (see device_weights)
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
@@ -78,15 +79,30 @@ def device_weights(cfg, copies, host_layer):
     out = []
     gen = torch.Generator(device="cuda")
     gen.manual_seed(20260525 + 100 * cfg.index)
+    # Placement of w_up (include/thi.h, thi_swiglu_mlp): torch hands out large tensors on 2 MiB boundaries, which
+    # puts w_up a whole multiple of 2 MiB behind w_gate -- row j of both then maps to the same HBM channel at the
+    # same k and the gate/up kernel, which streams both at once, runs 1-2 % slower.  w_gate and w_up therefore
+    # share one allocation with w_up UP_OFFSET_BYTES past the end of w_gate (THI_BENCH_UP_OFFSET overrides; 0 =
+    # back to back).
+    up_off = int(os.environ.get("THI_BENCH_UP_OFFSET", UP_OFFSET_BYTES)) // 2
+    gu = cfg.inter * cfg.hidden
     for c in range(copies):
-        if c == 0 and host_layer is not None:
-            out.append({n: to_dev(host_layer[n]) for n in names})
-            continue
         d = {}
+        pair = torch.empty(2 * gu + up_off, dtype=torch.float16, device="cuda")
+        d["w_gate"] = pair[:gu].view(cfg.inter, cfg.hidden)
+        d["w_up"] = pair[gu + up_off:].view(cfg.inter, cfg.hidden)
+        if c == 0 and host_layer is not None:
+            for n in names:
+                if n in d:
+                    d[n].copy_(to_dev(host_layer[n]))
+                else:
+                    d[n] = to_dev(host_layer[n])
+            out.append(d)
+            continue
         for n in names:
-            t = torch.empty(shapes[n], dtype=torch.float16, device="cuda")
-            t.normal_(0.0, cfg.sigma_w, generator=gen)
-            d[n] = t
+            if n not in d:
+                d[n] = torch.empty(shapes[n], dtype=torch.float16, device="cuda")
+            d[n].normal_(0.0, cfg.sigma_w, generator=gen)
         out.append(d)
     return out
 
@@ -368,7 +384,8 @@ def main():
         "dtype": "f16 storage, f32 accumulate", "data": "synthetic (seeded random fp16 weights/activations, Llama shapes)",
         "config": {"workload": workload_name(cfg, M),
                    "hidden": cfg.hidden, "n_qkv": cfg.n_qkv, "intermediate": cfg.inter, "M": M,
-                   "weight_copies_rotated": head["weight_copies_rotated"]},
+                   "weight_copies_rotated": head["weight_copies_rotated"],
+                   "w_up_offset_bytes": int(os.environ.get("THI_BENCH_UP_OFFSET", UP_OFFSET_BYTES))},
         "timing": {"blocks": BLOCKS, "launches_per_block": per_block, "warmup_launches": warmup,
                    "reported": "median of the blocks; HIP events on the launch stream",
                    "ms_per_step_blocks": head["ms_per_step_blocks"]},
