@@ -80,10 +80,9 @@ def device_weights(cfg, copies, host_layer):
     gen = torch.Generator(device="cuda")
     gen.manual_seed(20260525 + 100 * cfg.index)
     # Placement of w_up (include/thi.h, thi_swiglu_mlp): torch hands out large tensors on 2 MiB boundaries, which
-    # puts w_up a whole multiple of 2 MiB behind w_gate -- row j of both then maps to the same HBM channel at the
-    # same k and the gate/up kernel, which streams both at once, runs 1-2 % slower.  w_gate and w_up therefore
-    # share one allocation with w_up UP_OFFSET_BYTES past the end of w_gate (THI_BENCH_UP_OFFSET overrides; 0 =
-    # back to back).
+    # puts w_up a whole multiple of 2 MiB behind w_gate; the gate/up kernel, which streams the same rows of both at
+    # once, measured 1-2 % slower that way.  w_gate and w_up therefore share one allocation with w_up
+    # UP_OFFSET_BYTES past the end of w_gate (THI_BENCH_UP_OFFSET overrides; 0 = back to back).
     up_off = int(os.environ.get("THI_BENCH_UP_OFFSET", UP_OFFSET_BYTES)) // 2
     gu = cfg.inter * cfg.hidden
     for c in range(copies):

@@ -136,12 +136,12 @@ int thi_linear_static(const void* x, const void* w, void* out, int M, int N, int
  * memory.  g and u are never written to HBM.
  *
  * Placement hint (performance only, any placement is correct): the decode
- * kernel streams row j of w_gate and row j of w_up at the same time.  If
- * w_up lies a whole multiple of 2 MiB behind w_gate -- what an allocator
- * that hands out large buffers on 2 MiB boundaries produces -- both rows map
- * to the same HBM channel at the same k, and the kernel runs 1-2 % slower
- * (7B shape: 31.3 against 31.0 us at 32 tokens).  Starting w_up some tens of
- * KiB off such a multiple (bench.py: 64 KiB past the end of w_gate) avoids it.
+ * kernel streams the same rows of w_gate and w_up at the same time.  With
+ * w_up a whole multiple of 2 MiB behind w_gate -- what an allocator that
+ * hands out large buffers on 2 MiB boundaries produces -- it measured 1-2 %
+ * slower than with w_up some tens of KiB off such a multiple (7B shape at 32
+ * tokens: 31.3 against 31.0 us; bench.py places w_up 64 KiB past the end of
+ * w_gate).
  */
 int thi_swiglu_mlp(const void* x, const void* w_gate, const void* w_up, const void* w_down,
                    void* out, int M, int H, int I,
