@@ -438,6 +438,9 @@ ROWBLOCK_SPLIT = [
     (32, 8190, 8192, 2),         # 64 rows per block, the last block two short
     (9, 3000, 1024, 2),          # not admissible (K < 1024 * split): runs unshared
     (40, 4096, 4096, 2),         # two launches (32 + 8 tokens) on the same counters and slots
+    (32, 6144, 4096, 4),         # 96 rows per block: six tiles in flight, two token tiles (the largest LDS footprint)
+    (3, 6144, 8192, 4),          # the same block shape with one token tile
+    (17, 5120, 13824, 4),        # the 13B down projection: 80 rows per block, five tiles
 ]
 
 
