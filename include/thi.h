@@ -305,20 +305,6 @@ int thi_debug_handover(unsigned spin_limit, int withhold_flags);
  */
 int thi_query_kernel_family(int M, int N, int K, int fused);
 
-/*
- * Measurement probes for the benchmark (they compute nothing useful): what the GPU sustains for the
- * two resources the kernels are bound by, to be reported next to the nominal peaks.
- *
- * thi_probe_stream_read: reads `bytes` (>= 16 MiB, device memory, 16-byte aligned) once with the
- * access pattern of an ideal weight-streaming kernel.  bytes / elapsed = attainable HBM read rate.
- * thi_probe_mfma_f16: `workgroups` x 8 waves each issue iters x 8 v_mfma_f32_32x32x16_f16 on
- * register operands taken from `operands` (64 KiB of fp16 device memory: constant or random values --
- * the clock under load depends on operand toggling).  flops = workgroups * 8 * iters * 8 * 32768.
- * `sink` is 4 bytes of device memory that is (practically) never written.
- */
-int thi_probe_stream_read(const void* buffer, size_t bytes, void* sink, void* hip_stream);
-int thi_probe_mfma_f16(const void* operands, int iters, int workgroups, void* sink, void* hip_stream);
-
 #ifdef __cplusplus
 }
 #endif

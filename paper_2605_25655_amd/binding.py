@@ -17,15 +17,18 @@ THI_OP_RMSNORM_QKV, THI_OP_LINEAR, THI_OP_SWIGLU_MLP = 0, 1, 2
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libthi.so")
+_PROBE_LIB_PATH = os.path.join(_PKG, "libthi_probe.so")
 _lib = None
+_probe_lib = None
 
 EXPORTED_SYMBOLS = (
     "thi_rmsnorm_qkv", "thi_rmsnorm_qkv_rope", "thi_linear", "thi_linear_static", "thi_swiglu_mlp", "thi_swiglu_gate_up",
     "thi_linear_residual", "thi_rmsnorm_swiglu_mlp", "thi_decode_attention", "thi_attention_workspace_bytes",
     "thi_workspace_bytes",
     "thi_workspace_init", "thi_workspace_status", "thi_debug_handover", "thi_status_string", "thi_version", "thi_set_kernel_family", "thi_set_rowblock_split", "thi_set_mlp_fusion", "thi_query_kernel_family",
-    "thi_probe_stream_read", "thi_probe_mfma_f16",
 )
+# the benchmark's measurement probes live in a library of their own (include/thi_probe.h)
+PROBE_SYMBOLS = ("thi_probe_stream_read", "thi_probe_mfma_f16")
 
 
 class ThiError(RuntimeError):
@@ -92,10 +95,6 @@ def load_library():
     lib.thi_set_mlp_fusion.restype = ci
     lib.thi_set_rowblock_split.argtypes = [ci]
     lib.thi_set_rowblock_split.restype = ci
-    lib.thi_probe_stream_read.argtypes = [vp, sz, vp, vp]
-    lib.thi_probe_stream_read.restype = ci
-    lib.thi_probe_mfma_f16.argtypes = [vp, ci, ci, vp, vp]
-    lib.thi_probe_mfma_f16.restype = ci
     _lib = lib
     return lib
 
@@ -292,9 +291,31 @@ def thi_swiglu_gate_up(x, w_gate, w_up, h, workspace, stream=None, check: bool =
     return rc
 
 
+def probe_library_path() -> str:
+    return _PROBE_LIB_PATH
+
+
+def load_probe_library():
+    """Load libthi_probe.so (the benchmark's measurement probes; built next to libthi.so)."""
+    global _probe_lib
+    if _probe_lib is not None:
+        return _probe_lib
+    if not os.path.exists(_PROBE_LIB_PATH):
+        raise FileNotFoundError(f"{_PROBE_LIB_PATH} is missing: build it with `python -m paper_2605_25655_amd.build`")
+    import torch  # noqa: F401  (the same copy of the HIP runtime as the tensors', see load_library)
+    lib = ctypes.CDLL(_PROBE_LIB_PATH)
+    vp, sz, ci = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+    lib.thi_probe_stream_read.argtypes = [vp, sz, vp, vp]
+    lib.thi_probe_stream_read.restype = ci
+    lib.thi_probe_mfma_f16.argtypes = [vp, ci, ci, vp, vp]
+    lib.thi_probe_mfma_f16.restype = ci
+    _probe_lib = lib
+    return lib
+
+
 def thi_probe_stream_read(buffer, sink, stream=None) -> None:
     """Enqueue one streaming read of `buffer` (device tensor, >= 16 MiB)."""
-    rc = load_library().thi_probe_stream_read(_ptr(buffer), buffer.numel() * buffer.element_size(), _ptr(sink),
+    rc = load_probe_library().thi_probe_stream_read(_ptr(buffer), buffer.numel() * buffer.element_size(), _ptr(sink),
                                               _stream(stream))
     if rc != THI_OK:
         raise ThiError(rc, "thi_probe_stream_read")
@@ -302,7 +323,7 @@ def thi_probe_stream_read(buffer, sink, stream=None) -> None:
 
 def thi_probe_mfma_f16(operands, iters: int, workgroups: int, sink, stream=None) -> float:
     """Enqueue the register-only MFMA loop; returns the flops it performs."""
-    rc = load_library().thi_probe_mfma_f16(_ptr(operands), int(iters), int(workgroups), _ptr(sink), _stream(stream))
+    rc = load_probe_library().thi_probe_mfma_f16(_ptr(operands), int(iters), int(workgroups), _ptr(sink), _stream(stream))
     if rc != THI_OK:
         raise ThiError(rc, "thi_probe_mfma_f16")
     return float(workgroups) * 8 * iters * 8 * 32768.0

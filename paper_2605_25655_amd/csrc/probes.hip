@@ -1,7 +1,7 @@
-// Two measurement probes behind the C ABI (see include/thi.h): what this GPU actually sustains for
+// Two measurement probes behind a C ABI of their own (include/thi_probe.h, libthi_probe.so): what this GPU actually sustains for
 // the two resources the kernels are bound by.  They compute nothing useful and are only called by
 // the benchmark, which reports them next to the nominal peaks.
-#include "../../include/thi.h"
+#include "../../include/thi_probe.h"
 #include "thi_internal.h"
 
 namespace {

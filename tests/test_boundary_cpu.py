@@ -18,8 +18,8 @@ def lib():
     return binding.load_library()
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "thi.h")).read()
+def declared_symbols(header="thi.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(thi_[a-z0-9_]+)\s*\(", text)))
 
@@ -30,6 +30,19 @@ def test_header_symbols_are_exported(lib):
     assert set(names) == set(binding.EXPORTED_SYMBOLS)
     for n in names:
         assert hasattr(lib, n), n
+
+
+def test_probe_header_symbols_live_in_their_own_library(lib):
+    """The benchmark's measurement probes are declared in include/thi_probe.h and exported by libthi_probe.so,
+    not by the product library."""
+    from paper_2605_25655_amd import binding
+    names = declared_symbols("thi_probe.h")
+    assert set(names) == set(binding.PROBE_SYMBOLS) and names
+    assert os.path.exists(binding.probe_library_path())
+    probe = binding.load_probe_library()
+    for n in names:
+        assert hasattr(probe, n), n
+        assert not hasattr(lib, n), f"{n} must not be exported by libthi.so"
 
 
 def test_version_and_status_strings(lib):
