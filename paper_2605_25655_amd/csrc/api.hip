@@ -237,7 +237,7 @@ int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const ui
         const int tiles = (N + rows_per_tile - 1) / rows_per_tile;
         if ((long)tiles * ((K + SK_KC - 1) / SK_KC) > (1L << 30)) return THI_ERR_SHAPE;
         for (int m0 = 0; m0 < M; m0 += group) {
-            SkinnyArgs a;
+            SkinnyArgs a{};
             a.x = x + (size_t)m0 * K;
             a.gamma = gamma;
             a.w0 = w0;
@@ -284,7 +284,7 @@ int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const ui
         gamma = nullptr;
         epilogue = epilogue == EPI_RMSNORM ? EPI_PLAIN : epilogue == EPI_RMSNORM_ROPE ? EPI_ROPE : EPI_SWIGLU;
     }
-    GemmArgs g;
+    GemmArgs g{};
     g.x = x;
     g.w0 = w0;
     g.w1 = w1;
@@ -466,7 +466,7 @@ int thi_decode_attention(const void* q, const void* k_cache, const void* v_cache
         return THI_ERR_ALIGN;
     if (workspace_bytes < thi_attention_workspace_bytes(B, Hq, Hkv, D, S_max)) return THI_ERR_WORKSPACE;
     (void)hipGetLastError();      // an error another user of the runtime left behind is not ours to report
-    AttnArgs a;
+    AttnArgs a{};
     a.q = (const uint16_t*)q;
     a.k = (const uint16_t*)k_cache;
     a.v = (const uint16_t*)v_cache;
