@@ -281,7 +281,7 @@ int thi_set_rowblock_split(int split);
  * on h inside the kernel, the down projection (the paper's unified kernel scheduling, Sec. III-C.4) -- where the
  * library has that kernel for the shape (the 7B-shaped layer at 17..32 tokens); 0 (default) = always two launches,
  * which measured faster on MI355X.  Results are identical bit for bit either way.  The single launch keeps its
- * rendezvous tags in status words 2047..2559 of the workspace, which are then not zero between calls (every other
+ * rendezvous tags in status words 2047..2575 of the workspace, which are then not zero between calls (every other
  * status word is); like the other in-kernel hand-overs it needs all workgroups resident at once and reports a
  * time-out through thi_workspace_status().  Returns the previous setting.
  */

@@ -304,10 +304,9 @@ int run_projection(const uint16_t* x, const uint16_t* gamma, float eps, const ui
 // down projection (with the residual if given): two launches.  With thi_set_mlp_fusion(1) it is ONE launch where both
 // projections would run as row blocks, the down projection's blocks shared between workgroups, and the fused kernel
 // is built for the block shapes (the 7B-shaped layer at 17..32 tokens).  Off by default: measured on the 7B shape at
-// 32 tokens the single launch takes 66.9 us against 54.6 us for two -- 12.7 us of it the agent-scope acquire
-// (an L1/L2 invalidate per workgroup) that reading h after the in-kernel rendezvous needs, 3 us the rendezvous
-// itself; even with the acquire left out (not sound) it is 54.2 us: the kernel boundary costs no more than the
-// rendezvous that replaces it.
+// 32 tokens the single launch takes 58.0 us against 54.3 us for two (70 us while every workgroup executed the
+// agent-scope acquire that reading h after the in-kernel rendezvous needs; one workgroup per XCD does now) -- the
+// rendezvous and the device-scope stores of h cost more than the kernel boundary they replace.
 int run_mlp(const uint16_t* x, const uint16_t* gamma, float eps, const uint16_t* w_gate, const uint16_t* w_up,
             const uint16_t* w_down, const uint16_t* residual, uint16_t* out, int M, int H, int I, const Workspace& ws,
             hipStream_t stream)

@@ -500,6 +500,11 @@ __global__ __launch_bounds__(SK_THREADS) void skinny_rowblock(const uint16_t* x_
 // one, read from a status word at kernel entry and advanced by workgroup 0 once everybody has arrived -- nothing has
 // to be reset, the launch can be replayed from a captured graph, and a freshly initialised workspace (all zero)
 // never matches.  These words are the only status words that are not zero between calls.
+// Reading h afterwards needs an agent-scope acquire: h was written through eight L2s, and a line of it may sit in
+// this XCD's L2 with only this XCD's bytes current.  Executed by every workgroup the acquire (an L2 invalidate each)
+// costs 13 us; the L2 is shared by the XCD, so ONE workgroup per XCD does it -- the one with the lowest number among
+// those that report the same XCC id with their tag -- and announces it in a status word per XCD; the others wait for
+// that word (bounded like every wait here) and only drop their own vector cache's lines.
 template <int T1, int T2, int MT, int EPI1>
 __global__ __launch_bounds__(SK_THREADS) void mlp_fused(const uint16_t* x_, const uint16_t* wg_, const uint16_t* wu_,
                                                         const uint16_t* gamma_, int M_, int I_, int H_, int per_wg1,
@@ -519,13 +524,16 @@ __global__ __launch_bounds__(SK_THREADS) void mlp_fused(const uint16_t* x_, cons
     unsigned* const flags = a2.counters + MLP_FLAG_WORDS;
     // (every lane reads the same word: the value is wave-uniform)
     const unsigned launch_no = __hip_atomic_load(epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const unsigned tag = launch_no + 1u;                      // 1 .. 2^32 - 1: never the zero of a fresh workspace
+    const unsigned tag = launch_no % 0x0ffffffeu + 1u;        // 28 bits, never the zero of a fresh workspace
+    // the XCC this workgroup runs on (hardware register XCC_ID, bits 3:0), announced in the tag word's top four bits
+    const unsigned xcc = (unsigned)__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 15u;
+    unsigned* const l2_done = flags + MLP_MAX_GRID;           // [16] per XCC: the tag of the last launch whose acquire is done
 
     if (bid < grid1) rowblock_body<T1, MT, EPI1, false, true>(a1, per_wg1, bid, grid1, sm.up, s_gamma, [] {});
     // this workgroup's part of h is acknowledged by the memory system before its arrival is announced
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (threadIdx.x == 0) __hip_atomic_store(flags + bid, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (threadIdx.x == 0) __hip_atomic_store(flags + bid, tag | (xcc << 28), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (bid >= grid2) return;
 
     rowblock_body<T2, MT, EPI_PLAIN, true, false>(a2, per_wg2, bid, grid2, sm.down, s_gamma, [&] {
@@ -533,27 +541,48 @@ __global__ __launch_bounds__(SK_THREADS) void mlp_fused(const uint16_t* x_, cons
             const int lane = (int)threadIdx.x;
             unsigned spins = 0;
             bool ok = true;
+            int first_here = 0x7fffffff;          // the lowest-numbered workgroup of the second phase on this XCC
             while (true) {
                 bool all = true;
+                first_here = 0x7fffffff;
 #pragma unroll
                 for (int q = 0; q < MLP_MAX_GRID / 64; ++q) {
                     const int w = q * 64 + lane;
                     const unsigned f = __hip_atomic_load(flags + (w < everybody ? w : 0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    all = all && (w >= everybody || f == tag);
+                    all = all && (w >= everybody || (f & 0x0fffffffu) == tag);
+                    if (w < grid2 && (f >> 28) == xcc && w < first_here) first_here = w;
                 }
                 if (__builtin_amdgcn_ballot_w64(!all) == 0ull) break;
                 __builtin_amdgcn_s_sleep(1);
                 if (++spins > a2.spin_limit) { ok = false; break; }      // bounded: every wave exits
             }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                const int other = __shfl_xor(first_here, o);
+                first_here = other < first_here ? other : first_here;
+            }
+            if (ok) {
+                if (first_here == bid) {
+                    // h was written through other L2s: this XCD's L2 (and this CU's vector cache) must forget it
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                    if (lane == 0) __hip_atomic_store(l2_done + xcc, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else {
+                    while (__hip_atomic_load(l2_done + xcc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != tag) {
+                        __builtin_amdgcn_s_sleep(1);
+                        if (++spins > a2.spin_limit) { ok = false; break; }
+                    }
+                }
+            }
             if (lane == 0) {
                 if (!ok) __hip_atomic_store(a2.counters + (WS_MAX_COUNTERS - 1), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 // everybody has read the launch number (at entry, before arriving): it may advance
-                if (bid == 0) __hip_atomic_store(epoch, tag == 0xffffffffu ? 0u : tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (bid == 0) __hip_atomic_store(epoch, launch_no + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
         __syncthreads();
-        // h was written by other compute units: nothing of it may be served from this one's vector cache
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        // nothing of h may be served from this compute unit's vector cache either
+        asm volatile("buffer_inv sc0" ::: "memory");
     });
 }
 

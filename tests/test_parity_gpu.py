@@ -849,27 +849,38 @@ def test_single_launch_mlp_matches_two_launches(thi, oracle_mod, M):
     g = f16(1 + 0.1 * rng.standard_normal(H))
     r = Runner(M, H, I, H)
     xd, resd, wgd, wud, wdd, gd = (to_dev(t) for t in (x, res, wg, wu, wd, g))
-    two = to_host(r.swiglu_mlp(xd, wgd, wud, wdd))
-    two_n = to_host(r.rmsnorm_swiglu_mlp(xd, gd, 1e-6, wgd, wud, wdd, resd))
+    # a second set of activations, used alternately: h changes from launch to launch, so that a line of the previous
+    # launch's h left in some cache would show
+    x2 = f16(rng.standard_normal((M, H)) * 1.5)
+    x2d = to_dev(x2)
+    two = [to_host(r.swiglu_mlp(t, wgd, wud, wdd)) for t in (xd, x2d)]
+    two_n = [to_host(r.rmsnorm_swiglu_mlp(t, gd, 1e-6, wgd, wud, wdd, resd)) for t in (xd, x2d)]
     rows = synth.sample_rows(77, M, 4)
     y, s = oracle_mod.swiglu_mlp(x[rows], wg, wu, wd)
-    check(two[rows], y, s, "two-launch MLP", argmax=False)
+    check(two[0][rows], y, s, "two-launch MLP", argmax=False)
     prev = thi.thi_set_mlp_fusion(1)
     try:
-        for rep in range(5):
-            one = to_host(r.swiglu_mlp(xd, wgd, wud, wdd))
-            one_n = to_host(r.rmsnorm_swiglu_mlp(xd, gd, 1e-6, wgd, wud, wdd, resd))
-            assert np.array_equal(one.view(np.uint16), two.view(np.uint16)), f"plain MLP differs (repeat {rep})"
-            assert np.array_equal(one_n.view(np.uint16), two_n.view(np.uint16)), f"RMSNorm-fronted MLP differs (repeat {rep})"
+        for rep in range(6):
+            t = (xd, x2d)[rep % 2]
+            one = to_host(r.swiglu_mlp(t, wgd, wud, wdd))
+            one_n = to_host(r.rmsnorm_swiglu_mlp(t, gd, 1e-6, wgd, wud, wdd, resd))
+            assert np.array_equal(one.view(np.uint16), two[rep % 2].view(np.uint16)), f"plain MLP differs (repeat {rep})"
+            assert np.array_equal(one_n.view(np.uint16), two_n[rep % 2].view(np.uint16)), f"RMSNorm-fronted MLP differs (repeat {rep})"
     finally:
         thi.thi_set_mlp_fusion(prev)
     words = _status_words(r.ws).copy()
-    assert words[2047] == 10 and (words[2048:2048 + 256] == 10).all(), "ten single launches: tag 10 everywhere"
-    words[2047:2048 + 512] = 0
+    tags = words[2048:2048 + 256]
+    assert words[2047] == 12 and ((tags & 0x0fffffff) == 12).all(), "twelve single launches: tag 12 everywhere"
+    # the top four bits of a tag word name the XCC its workgroup ran on: eight of them, 32 workgroups each, and each
+    # XCC's acquire was announced with the same tag
+    xcc, count = np.unique(tags >> 28, return_counts=True)
+    assert len(xcc) == 8 and (count == 32).all(), (xcc, count)
+    assert (words[2048 + 512 + xcc.astype(np.int64)] == 12).all()
+    words[2047:2048 + 512 + 16] = 0
     assert not words.any()
     assert thi.thi_workspace_status(r.ws) == thi.THI_OK
     # and the two-launch path is unaffected afterwards
-    assert np.array_equal(to_host(r.swiglu_mlp(xd, wgd, wud, wdd)).view(np.uint16), two.view(np.uint16))
+    assert np.array_equal(to_host(r.swiglu_mlp(xd, wgd, wud, wdd)).view(np.uint16), two[0].view(np.uint16))
 
 
 # ------------------------------------- the layer's calls as one captured graph
@@ -931,7 +942,7 @@ def test_layer_calls_replay_from_a_captured_graph(thi, M, single_launch_mlp):
     words = _status_words(ws).copy()
     if single_launch_mlp:      # its rendezvous tags advance with every launch, replayed ones included
         assert words[2047] == 9, words[2047]      # one eager warm-up, then four rounds of one eager call and one replay
-        words[2047:2048 + 512] = 0
+        words[2047:2048 + 512 + 16] = 0
     assert not words.any()
 
 
